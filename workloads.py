@@ -1,0 +1,202 @@
+"""Seeded synthetic inputs for the sparse-convolution path.
+
+This module only draws random numbers and names layer shapes.  It holds none of
+the method's arithmetic (no convolution, no encoding, no pooling), so both the
+CPU oracle's tests and the HIP path's tests can take their inputs from here
+without sharing any code that matters for parity.
+
+The paper measures on real feature maps of trained networks (Section 8); those
+activations are not available, so every layer here is a stand-in with the
+layer's shape and the zero ratio the paper reports for such layers (Fig. 2:
+above 0.7 in deep layers; Table 3: 0.83-0.95).
+
+Recipe (all host side, numpy ``default_rng``):
+    keep  = rng.random(shape) >= z              # z = zero ratio (scalar or per channel)
+    x     = where(keep, magnitude, 0) as fp32   # magnitude never exactly 0
+    w     = rng.normal(0, std, shape) as fp32
+    seed  = 190909927 + 1000 * config_index + 7 * layer_index + batch
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 190909927
+
+
+@dataclasses.dataclass(frozen=True)
+class Layer:
+    """One convolution (optionally followed by max pooling) in the paper's notation.
+
+    C,H,W: input channels / height / width; K,R,S: filters / kernel height / width;
+    stride = c_s, pad = symmetric zero padding, groups = G; pool = (p_h, p_w, p_s) or None.
+    zero_ratio: probability that an input element is zero; ``per_channel`` draws a
+    separate ratio per channel uniformly from the given (lo, hi) range instead.
+    """
+
+    name: str
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    stride: int = 1
+    pad: int = 0
+    groups: int = 1
+    pool: Optional[Tuple[int, int, int]] = None
+    zero_ratio: float = 0.7
+    per_channel: Optional[Tuple[float, float]] = None
+    magnitude: str = "halfnormal"  # "halfnormal" = |N(0,1)|, "uniform" = U(0,1)
+    w_std: Optional[float] = None  # None = He: sqrt(2 / (C_g*R*S))
+
+    @property
+    def Cg(self) -> int:
+        return self.C // self.groups
+
+    @property
+    def Kg(self) -> int:
+        return self.K // self.groups
+
+    @property
+    def OH(self) -> int:
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def OW(self) -> int:
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    def with_zero_ratio(self, z: float) -> "Layer":
+        return dataclasses.replace(self, zero_ratio=z, per_channel=None,
+                                   name=f"{self.name}-z{z:.2f}")
+
+
+def _vgg_std(C: int) -> float:
+    return math.sqrt(2.0 / (9.0 * C))
+
+
+# Index in this list = config index of the benchmark description.
+CONFIGS: List[Dict] = [
+    {
+        "name": "tiny",
+        "batches": (1,),
+        "layers": [
+            Layer("tiny-16x28-k32", C=16, H=28, W=28, K=32, R=3, S=3, stride=1, pad=1,
+                  zero_ratio=0.7, magnitude="uniform", w_std=0.1),
+        ],
+    },
+    {
+        "name": "vgg19",
+        "batches": (1, 8),
+        "layers": [
+            Layer("vgg-256x56", C=256, H=56, W=56, K=256, R=3, S=3, pad=1,
+                  zero_ratio=0.60, w_std=_vgg_std(256)),
+            Layer("vgg-512x28", C=512, H=28, W=28, K=512, R=3, S=3, pad=1,
+                  zero_ratio=0.75, w_std=_vgg_std(512)),
+            Layer("vgg-512x14-pool", C=512, H=14, W=14, K=512, R=3, S=3, pad=1,
+                  zero_ratio=0.85, w_std=_vgg_std(512), pool=(2, 2, 2)),
+        ],
+    },
+    {
+        "name": "resnet50",
+        "batches": (1, 32),
+        "layers": [
+            Layer("rn-1x1-256to64x56", C=256, H=56, W=56, K=64, R=1, S=1,
+                  per_channel=(0.5, 0.8)),
+            Layer("rn-3x3-64x56", C=64, H=56, W=56, K=64, R=3, S=3, pad=1,
+                  per_channel=(0.5, 0.8)),
+            Layer("rn-3x3-128x56-s2", C=128, H=56, W=56, K=128, R=3, S=3, stride=2, pad=1,
+                  per_channel=(0.5, 0.8)),
+            Layer("rn-3x3-512x7", C=512, H=7, W=7, K=512, R=3, S=3, pad=1,
+                  per_channel=(0.5, 0.8)),
+        ],
+    },
+    {
+        "name": "densenet121",
+        "batches": (1, 16),
+        "layers": [
+            Layer("dn-1x1-256to128x28", C=256, H=28, W=28, K=128, R=1, S=1),
+            Layer("dn-1x1-384to128x28", C=384, H=28, W=28, K=128, R=1, S=1),
+            Layer("dn-1x1-512to128x28", C=512, H=28, W=28, K=128, R=1, S=1),
+            Layer("dn-3x3-128to32x28", C=128, H=28, W=28, K=32, R=3, S=3, pad=1),
+            Layer("dn-T-1x1-512to256x28-pool", C=512, H=28, W=28, K=256, R=1, S=1,
+                  pool=(2, 2, 2)),
+        ],
+    },
+    {
+        "name": "regnetx16gf",
+        "batches": (1, 32),
+        "layers": [
+            Layer("rx-896x14-g7", C=896, H=14, W=14, K=896, R=3, S=3, pad=1, groups=7),
+            Layer("rx-2048x7-g16", C=2048, H=7, W=7, K=2048, R=3, S=3, pad=1, groups=16),
+        ],
+    },
+]
+
+SWEEP_ZERO_RATIOS = tuple(round(0.05 * i, 2) for i in range(20))  # 0.00 .. 0.95
+
+
+def layer_seed(config_index: int, layer_index: int, batch: int) -> int:
+    return BASE_SEED + 1000 * config_index + 7 * layer_index + batch
+
+
+def make_feature_map(rng: np.random.Generator, N: int, layer: Layer) -> np.ndarray:
+    """fp32 NCHW feature map with the layer's zero ratio; nonzeros are strictly positive."""
+    shape = (N, layer.C, layer.H, layer.W)
+    if layer.per_channel is not None:
+        lo, hi = layer.per_channel
+        z = rng.uniform(lo, hi, size=(1, layer.C, 1, 1))  # same ratios for every image
+    else:
+        z = layer.zero_ratio
+    keep = rng.random(shape) >= z
+    if layer.magnitude == "uniform":
+        mag = rng.random(shape)
+    else:
+        mag = np.abs(rng.standard_normal(shape))
+    mag = mag.astype(np.float32)
+    # a drawn magnitude that rounds to exactly 0 would silently raise the zero ratio
+    mag[mag == 0] = np.float32(0.5)
+    return np.where(keep, mag, np.float32(0)).astype(np.float32)
+
+
+def make_filters(rng: np.random.Generator, layer: Layer) -> np.ndarray:
+    """fp32 filters [K][C/groups][R][S], zero-mean normal."""
+    std = layer.w_std if layer.w_std is not None else math.sqrt(2.0 / (layer.Cg * layer.R * layer.S))
+    w = rng.normal(0.0, std, size=(layer.K, layer.Cg, layer.R, layer.S))
+    return w.astype(np.float32)
+
+
+def make_layer_inputs(config_index: int, layer_index: int, N: int,
+                      layer: Optional[Layer] = None) -> Tuple[Layer, np.ndarray, np.ndarray]:
+    """(layer, x, w) for one layer of one config at batch N, seeded as the recipe states."""
+    if layer is None:
+        layer = CONFIGS[config_index]["layers"][layer_index]
+    rng = np.random.default_rng(layer_seed(config_index, layer_index, N))
+    x = make_feature_map(rng, N, layer)
+    w = make_filters(rng, layer)
+    return layer, x, w
+
+
+def make_random_case(seed: int, N: int, C: int, H: int, W: int, K: int, R: int, S: int,
+                     stride: int = 1, pad: int = 0, groups: int = 1,
+                     pool: Optional[Tuple[int, int, int]] = None, zero_ratio: float = 0.7,
+                     integer_valued: bool = False) -> Tuple[Layer, np.ndarray, np.ndarray]:
+    """Arbitrary small shape for parity tests.
+
+    integer_valued: x in {0,1,2,3} and w in {-2..2}, so every fp32 summation order is exact
+    and a GPU result must equal the fp64 result bit for bit.
+    """
+    layer = Layer(f"case-{seed}", C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad,
+                  groups=groups, pool=pool, zero_ratio=zero_ratio)
+    rng = np.random.default_rng(seed)
+    if integer_valued:
+        keep = rng.random((N, C, H, W)) >= zero_ratio
+        x = np.where(keep, rng.integers(1, 4, size=(N, C, H, W)), 0).astype(np.float32)
+        w = rng.integers(-2, 3, size=(K, C // groups, R, S)).astype(np.float32)
+    else:
+        x = make_feature_map(rng, N, layer)
+        w = make_filters(rng, layer)
+    return layer, x, w
