@@ -1,0 +1,116 @@
+/*
+ * sconv: zero-skipping direct convolution (+ fused ReLU / max-pooling) for AMD MI355X (gfx950).
+ *
+ * C ABI of the GPU library.  All tensors are fp32 and contiguous; every pointer marked
+ * "device" is HIP device memory owned by the caller.  The library allocates, frees and keeps
+ * no device memory.  Every entry point that launches work enqueues it on the given HIP stream
+ * (a hipStream_t passed as void*; NULL = the default stream) and returns without synchronising.
+ * Outputs are overwritten, never accumulated into.
+ *
+ * Notation follows Table 1 of the paper: feature map i_h x i_w (H x W here), kernel k_h x k_w
+ * (R x S), pooling window p_h x p_w, convolution stride c_s, pooling stride p_s.  Several input
+ * channels, filters and images are handled as Section 7 describes: channels are scanned one
+ * after another inside a window, filters and images only add independent results.
+ *
+ * Return value of every int function: 0 on success or a negative SCONV_E* code.  Argument
+ * checks are pure host code and run before any GPU call.
+ */
+#ifndef SCONV_H
+#define SCONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t N, C, H, W;          /* input  x[N][C][H][W]                                     */
+    int32_t K, R, S;             /* filter w[K][C/groups][R][S]                              */
+    int32_t stride, pad, groups; /* c_s; symmetric zero padding; groups G (C%G == K%G == 0)  */
+    int32_t pool_h, pool_w, pool_stride; /* p_h, p_w, p_s; read only by the pooling calls    */
+    int32_t flags;               /* SCONV_RELU: sconv_forward applies max(y, 0) before the
+                                    store (Section 5.5).  The pooling path always applies it. */
+} sconv_desc_t;
+
+enum { SCONV_RELU = 1 };
+enum { SCONV_FMT_ECR = 0, SCONV_FMT_PECR = 1 };
+enum {
+    SCONV_OK = 0,
+    SCONV_EINVAL = -1,       /* null pointer, non-positive size, C or K not divisible by groups,
+                                pad >= R or pad >= S, empty output, pooling window larger than
+                                the convolution output, unknown format or flag                 */
+    SCONV_EUNSUPPORTED = -2, /* valid problem that exceeds a kernel limit (see each call)      */
+    SCONV_ELAUNCH = -3       /* the HIP runtime reported an error for the launch               */
+};
+
+/*
+ * Output sizes (Section 5.3 and Eq. 3, floored): OH = (H + 2*pad - R)/c_s + 1, OW likewise;
+ * PH = (OH - p_h)/p_s + 1, PW likewise (0 when the descriptor has no pooling window).
+ * PH/PW may be NULL.  Host only.
+ */
+int sconv_output_dims(const sconv_desc_t* desc, int32_t* OH, int32_t* OW, int32_t* PH, int32_t* PW);
+
+/*
+ * Size of an encoding.  rows = N*G*OH*OW (ECR) or N*G*PH*PW*p_h*p_w (PECR);
+ * slots_per_row = L = (C/G)*R*S.  Host only.
+ */
+int sconv_encode_sizes(const sconv_desc_t* desc, int fmt, int64_t* rows, int64_t* slots_per_row);
+
+/*
+ * Format conversion alone (Algorithm 1 for ECR, Algorithm 3 for PECR), materialised in device
+ * memory.  One row per convolution window.  Row order: ECR (n, g, oh, ow) - one block row per
+ * output row, one entry per output column (Section 5.2); PECR (n, g, ph, pw, py, px) - the
+ * windows of one pooling window are adjacent, left to right then top to bottom (Section 6.2),
+ * and a window that lies in several pooling windows is repeated.  Within a row the window is
+ * scanned channel by channel, then kernel row, then kernel column; every element != 0 appends
+ * its value to values[row][.] and its column c*R*S + r*S + s (its position in a filter) to
+ * index[row][.].  count[row] = number appended; ECR stores -1 instead of 0 for an empty window.
+ * Slots past the count are written as value +0.0f and index 0, so whole arrays are defined.
+ *   x_dev      device, in : [N][C][H][W]
+ *   values_dev device, out: [rows][L] fp32
+ *   index_dev  device, out: [rows][L] int32
+ *   count_dev  device, out: [rows]    int32
+ * SCONV_EUNSUPPORTED if rows*L >= 2^40 or L >= 2^24.
+ */
+int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* values_dev,
+                 int32_t* index_dev, int32_t* count_dev, void* hip_stream);
+
+/*
+ * Sparse convolution (Section 5: conversion of every window to ECR on chip, then the
+ * sparse row-times-filter product of Algorithm 2, optional ReLU, one store):
+ *   y[n][k][oh][ow] = sum over the window's nonzeros of value * w[k][column],
+ * the window of group g = k / (K/G).  Zero elements are never multiplied.
+ *   x_dev device, in : [N][C][H][W]
+ *   w_dev device, in : [K][C/G][R][S]
+ *   y_dev device, out: [N][K][OH][OW]
+ * SCONV_EUNSUPPORTED if a tensor has 2^31 or more elements.
+ */
+int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
+                  void* hip_stream);
+
+/*
+ * Sparse convolution fused with ReLU and max pooling (Section 6, Algorithm 4): the convolution
+ * results of one pooling window are reduced on chip and only the pooled tensor is stored:
+ *   y[n][k][ph][pw] = max over py < p_h, px < p_w of max(0, conv[n][k][ph*p_s+py][pw*p_s+px]).
+ *   y_dev device, out: [N][K][PH][PW]
+ * SCONV_EUNSUPPORTED if p_h*p_w > 64 or a tensor has 2^31 or more elements.
+ */
+int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                       float* y_dev, void* hip_stream);
+
+/*
+ * Name of the kernel variant the two forward calls would pick for this descriptor (a static
+ * string, for benchmark records and profiles).  pooled != 0 asks about sconv_pool_forward.
+ * The environment variable SCONV_VARIANT ("rows" or "auto") pins the choice for profiling.
+ * Returns NULL for an invalid descriptor.  Host only.
+ */
+const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
+
+/* Static description of an error code. */
+const char* sconv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCONV_H */

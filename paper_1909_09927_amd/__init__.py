@@ -1,0 +1,167 @@
+"""Python binding of libsconv: zero-skipping direct convolution (+ fused max pooling) on MI355X.
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the C ABI
+declared in include/sconv.h.  PyTorch provides device memory and the current HIP stream.
+There is no CPU fallback: without the built library every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsconv.so")
+
+SCONV_RELU = 1
+FMT_ECR = 0
+FMT_PECR = 1
+SCONV_OK, SCONV_EINVAL, SCONV_EUNSUPPORTED, SCONV_ELAUNCH = 0, -1, -2, -3
+
+
+class SconvError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+class Desc(ctypes.Structure):
+    """sconv_desc_t"""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride", "pad", "groups",
+                 "pool_h", "pool_w", "pool_stride", "flags")]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; builds it first only when no built library exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        P = ctypes.POINTER
+        i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        L.sconv_output_dims.argtypes = [P(Desc), P(i32), P(i32), P(i32), P(i32)]
+        L.sconv_encode_sizes.argtypes = [P(Desc), ctypes.c_int, P(i64), P(i64)]
+        L.sconv_encode.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, vp]
+        L.sconv_forward.argtypes = [P(Desc), vp, vp, vp, vp]
+        L.sconv_pool_forward.argtypes = [P(Desc), vp, vp, vp, vp]
+        L.sconv_variant_name.argtypes = [P(Desc), ctypes.c_int]
+        L.sconv_variant_name.restype = ctypes.c_char_p
+        L.sconv_strerror.argtypes = [ctypes.c_int]
+        L.sconv_strerror.restype = ctypes.c_char_p
+        for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
+                  "sconv_pool_forward"):
+            getattr(L, f).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().sconv_strerror(code).decode()
+
+
+def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, groups=1, pool: Optional[Tuple[int, int, int]] = None,
+              relu: bool = False) -> Desc:
+    ph, pw, ps = pool if pool is not None else (0, 0, 0)
+    return Desc(N, C, H, W, K, R, S, stride, pad, groups, ph, pw, ps, SCONV_RELU if relu else 0)
+
+
+def desc_for(x, w, stride=1, pad=0, groups=1, pool=None, relu=False) -> Desc:
+    N, C, H, W = x.shape
+    K, Cg, R, S = w.shape
+    if Cg * groups != C:
+        raise ValueError("filter channel count does not match C / groups")
+    return make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, relu)
+
+
+def sconv_output_dims(desc: Desc) -> Tuple[int, int, int, int]:
+    v = [ctypes.c_int32() for _ in range(4)]
+    rc = lib().sconv_output_dims(ctypes.byref(desc), *[ctypes.byref(t) for t in v])
+    if rc:
+        raise SconvError(rc, "sconv_output_dims")
+    return tuple(t.value for t in v)
+
+
+def sconv_encode_sizes(desc: Desc, fmt: int) -> Tuple[int, int]:
+    rows, L = ctypes.c_int64(), ctypes.c_int64()
+    rc = lib().sconv_encode_sizes(ctypes.byref(desc), fmt, ctypes.byref(rows), ctypes.byref(L))
+    if rc:
+        raise SconvError(rc, "sconv_encode_sizes")
+    return rows.value, L.value
+
+
+def sconv_variant_name(desc: Desc, pooled: bool = False) -> Optional[str]:
+    s = lib().sconv_variant_name(ctypes.byref(desc), 1 if pooled else 0)
+    return s.decode() if s is not None else None
+
+
+def _check_dev(t, dtype, what):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what} must be a contiguous {dtype} tensor in device memory")
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None):
+    """Format conversion alone; returns device tensors (values[rows,L], index[rows,L], count[rows])."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    N, C, H, W = x.shape
+    K, Cg, R, S = w_shape
+    desc = make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool)
+    rows, L = sconv_encode_sizes(desc, fmt)
+    values = torch.empty((rows, L), dtype=torch.float32, device=x.device)
+    index = torch.empty((rows, L), dtype=torch.int32, device=x.device)
+    count = torch.empty((rows,), dtype=torch.int32, device=x.device)
+    rc = lib().sconv_encode(ctypes.byref(desc), fmt, x.data_ptr(), values.data_ptr(), index.data_ptr(),
+                            count.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_encode")
+    return values, index, count
+
+
+def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
+    """Sparse convolution; returns y[N,K,OH,OW] (device, fp32)."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    _check_dev(w, torch.float32, "w")
+    desc = desc_for(x, w, stride, pad, groups, None, relu)
+    OH, OW, _, _ = sconv_output_dims(desc)
+    if out is None:
+        out = torch.empty((desc.N, desc.K, OH, OW), dtype=torch.float32, device=x.device)
+    else:
+        _check_dev(out, torch.float32, "out")
+        if tuple(out.shape) != (desc.N, desc.K, OH, OW):
+            raise ValueError("out has the wrong shape")
+    rc = lib().sconv_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_forward")
+    return out
+
+
+def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None):
+    """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32)."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    _check_dev(w, torch.float32, "w")
+    desc = desc_for(x, w, stride, pad, groups, pool, True)
+    _, _, PH, PW = sconv_output_dims(desc)
+    if out is None:
+        out = torch.empty((desc.N, desc.K, PH, PW), dtype=torch.float32, device=x.device)
+    else:
+        _check_dev(out, torch.float32, "out")
+        if tuple(out.shape) != (desc.N, desc.K, PH, PW):
+            raise ValueError("out has the wrong shape")
+    rc = lib().sconv_pool_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_pool_forward")
+    return out

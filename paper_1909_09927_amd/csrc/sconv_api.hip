@@ -1,0 +1,160 @@
+// Host side of libsconv: argument checks, size helpers, variant choice.  No device code here.
+#include <stdlib.h>
+#include <string.h>
+
+#include "sconv_internal.h"
+
+namespace sconv {
+
+static bool mul_fits_31(int64_t a, int64_t b, int64_t c, int64_t d)
+{
+    // every factor is positive and below 2^31, so partial products cannot overflow int64
+    int64_t ab = a * b;
+    if (ab >= (int64_t(1) << 31)) return false;
+    int64_t abc = ab * c;
+    if (abc >= (int64_t(1) << 31)) return false;
+    return abc * d < (int64_t(1) << 31);
+}
+
+int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
+{
+    if (!d || !out) return SCONV_EINVAL;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0)
+        return SCONV_EINVAL;
+    if (d->stride <= 0 || d->pad < 0 || d->groups <= 0) return SCONV_EINVAL;
+    if (d->C % d->groups || d->K % d->groups) return SCONV_EINVAL;
+    if (d->pad >= d->R || d->pad >= d->S) return SCONV_EINVAL;
+    if (d->flags & ~SCONV_RELU) return SCONV_EINVAL;
+    if (d->H + 2 * (int64_t)d->pad < d->R || d->W + 2 * (int64_t)d->pad < d->S) return SCONV_EINVAL;
+
+    Problem p;
+    memset(&p, 0, sizeof(p));
+    p.N = d->N; p.C = d->C; p.H = d->H; p.W = d->W;
+    p.K = d->K; p.R = d->R; p.S = d->S;
+    p.stride = d->stride; p.pad = d->pad; p.G = d->groups;
+    p.Cg = d->C / d->groups;
+    p.Kg = d->K / d->groups;
+    p.OH = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    p.OW = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    p.relu = (d->flags & SCONV_RELU) ? 1 : 0;
+    if (pooled) {
+        if (d->pool_h <= 0 || d->pool_w <= 0 || d->pool_stride <= 0) return SCONV_EINVAL;
+        if (d->pool_h > p.OH || d->pool_w > p.OW) return SCONV_EINVAL;
+        p.ph = d->pool_h; p.pw = d->pool_w; p.ps = d->pool_stride;
+        p.PH = (p.OH - p.ph) / p.ps + 1;
+        p.PW = (p.OW - p.pw) / p.ps + 1;
+        p.relu = 1;
+    }
+    int64_t L = (int64_t)p.Cg * p.R * p.S;
+    if (L >= (int64_t(1) << 24)) return SCONV_EUNSUPPORTED;
+    p.L = (int)L;
+    if (!mul_fits_31(p.N, p.C, p.H, p.W) || !mul_fits_31(p.K, p.Cg, p.R, p.S) ||
+        !mul_fits_31(p.N, p.K, p.OH, p.OW))
+        return SCONV_EUNSUPPORTED;
+    *out = p;
+    return SCONV_OK;
+}
+
+enum Variant { V_ROWS, V_TAP };
+
+static Variant choose(const Problem& p, bool pooled)
+{
+    const char* pin = getenv("SCONV_VARIANT");
+    if (pin && !strcmp(pin, "rows")) return V_ROWS;
+    return tap_supported(p, pooled) ? V_TAP : V_ROWS;
+}
+
+}  // namespace sconv
+
+using namespace sconv;
+
+extern "C" int sconv_output_dims(const sconv_desc_t* desc, int32_t* OH, int32_t* OW, int32_t* PH,
+                                 int32_t* PW)
+{
+    if (!desc || !OH || !OW) return SCONV_EINVAL;
+    bool pooled = desc->pool_h > 0 || desc->pool_w > 0 || desc->pool_stride > 0;
+    Problem p;
+    int rc = fill_problem(desc, pooled, &p);
+    if (rc) return rc;
+    *OH = p.OH;
+    *OW = p.OW;
+    if (PH) *PH = p.PH;
+    if (PW) *PW = p.PW;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_encode_sizes(const sconv_desc_t* desc, int fmt, int64_t* rows,
+                                  int64_t* slots_per_row)
+{
+    if (!rows || !slots_per_row) return SCONV_EINVAL;
+    if (fmt != SCONV_FMT_ECR && fmt != SCONV_FMT_PECR) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, fmt == SCONV_FMT_PECR, &p);
+    if (rc) return rc;
+    int64_t r = (int64_t)p.N * p.G;
+    if (fmt == SCONV_FMT_ECR)
+        r *= (int64_t)p.OH * p.OW;
+    else
+        r *= (int64_t)p.PH * p.PW * p.ph * p.pw;
+    *rows = r;
+    *slots_per_row = p.L;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev,
+                            float* values_dev, int32_t* index_dev, int32_t* count_dev,
+                            void* hip_stream)
+{
+    if (!x_dev || !values_dev || !index_dev || !count_dev) return SCONV_EINVAL;
+    int64_t rows, L;
+    int rc = sconv_encode_sizes(desc, fmt, &rows, &L);
+    if (rc) return rc;
+    if (rows * L >= (int64_t(1) << 40) || rows >= (int64_t(1) << 31)) return SCONV_EUNSUPPORTED;
+    Problem p;
+    rc = fill_problem(desc, fmt == SCONV_FMT_PECR, &p);
+    if (rc) return rc;
+    return launch_encode(p, fmt, x_dev, values_dev, index_dev, count_dev, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                             float* y_dev, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (choose(p, false) == V_TAP) return launch_tap(p, false, x_dev, w_dev, y_dev, s);
+    return launch_rows(p, false, x_dev, w_dev, y_dev, s);
+}
+
+extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                  float* y_dev, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, true, &p);
+    if (rc) return rc;
+    if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (choose(p, true) == V_TAP) return launch_tap(p, true, x_dev, w_dev, y_dev, s);
+    return launch_rows(p, true, x_dev, w_dev, y_dev, s);
+}
+
+extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
+{
+    Problem p;
+    if (fill_problem(desc, pooled != 0, &p)) return NULL;
+    return choose(p, pooled != 0) == V_TAP ? "tap3x3" : "rows";
+}
+
+extern "C" const char* sconv_strerror(int code)
+{
+    switch (code) {
+    case SCONV_OK: return "success";
+    case SCONV_EINVAL: return "invalid argument";
+    case SCONV_EUNSUPPORTED: return "shape exceeds a kernel limit";
+    case SCONV_ELAUNCH: return "HIP launch failed";
+    default: return "unknown sconv error code";
+    }
+}

@@ -1,0 +1,45 @@
+// Internal declarations shared by the translation units of libsconv (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sconv.h"
+
+namespace sconv {
+
+// Problem description with every derived size filled in by the host (see fill_problem).
+struct Problem {
+    int N, C, H, W, K, R, S, stride, pad, G;
+    int Cg, Kg;          // channels / filters per group
+    int OH, OW;          // convolution output
+    int ph, pw, ps;      // pooling window and stride (0 when not pooling)
+    int PH, PW;          // pooled output (0 when not pooling)
+    int L;               // slots per window row = Cg*R*S
+    int relu;            // apply max(.,0) before the store
+};
+
+// Validates a descriptor (pure host code) and fills a Problem.  pooled: the pooling fields
+// are required and checked.  Returns SCONV_OK / SCONV_EINVAL / SCONV_EUNSUPPORTED.
+int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out);
+
+// Kernel launchers.  Each returns SCONV_OK, SCONV_EUNSUPPORTED (shape outside what the variant
+// covers; nothing was launched) or SCONV_ELAUNCH.
+int launch_encode(const Problem& p, int fmt, const float* x, float* values, int32_t* index,
+                  int32_t* count, hipStream_t stream);
+
+// General window-row kernel: any R, S, stride, pad, groups, pooling window of up to 64 results.
+int launch_rows(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+                hipStream_t stream);
+
+// Element-stationary 3x3 / stride 1 / pad 1 kernel.  tap_supported tells whether it covers p.
+bool tap_supported(const Problem& p, bool pooled);
+int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t stream);
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? SCONV_OK : SCONV_ELAUNCH;
+}
+
+}  // namespace sconv

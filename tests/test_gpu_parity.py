@@ -1,0 +1,133 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on
+the same seeded inputs.  Encoding arrays bit-exact; conv / pooled outputs within 1e-4*sum|x*w|;
+integer-valued inputs bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+import paper_1909_09927_amd as sconv
+from parity import check_encode, check_forward, check_pool_forward, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# (N, C, H, W, K, R, S, stride, pad, groups, pool)
+SMALL = [
+    (1, 1, 5, 5, 1, 3, 3, 1, 0, 1, (2, 2, 1)),          # the paper's figure geometry
+    (2, 3, 7, 6, 4, 3, 3, 1, 1, 1, (2, 2, 2)),
+    (1, 4, 9, 8, 6, 3, 2, 2, 1, 2, (2, 2, 1)),          # non-square kernel, stride 2, groups
+    (2, 6, 8, 8, 9, 1, 1, 1, 0, 3, (3, 3, 2)),          # 1x1 grouped, 3x3 pooling (9 windows)
+    (1, 2, 10, 11, 3, 5, 3, 3, 2, 1, (2, 1, 1)),        # stride 3, pad 2
+    (1, 8, 6, 6, 8, 3, 3, 1, 1, 8, (2, 2, 2)),          # depthwise
+    (3, 5, 4, 9, 2, 2, 4, 2, 1, 1, (1, 2, 1)),
+    (2, 40, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # several tiles, ragged tails in K and windows
+    (1, 33, 17, 13, 130, 3, 3, 1, 1, 1, (3, 2, 2)),
+    (1, 64, 30, 30, 300, 1, 1, 1, 0, 1, (2, 2, 2)),     # K beyond one 256-filter tile
+    (2, 96, 14, 14, 96, 3, 3, 1, 1, 3, (2, 2, 2)),
+    (1, 16, 21, 21, 20, 7, 7, 2, 3, 1, (2, 2, 2)),      # large kernel
+    (1, 8, 40, 40, 16, 3, 3, 1, 1, 1, (7, 7, 3)),       # 49-result pooling window
+]
+
+
+def _mk(seed, shp, z=0.7, integer=False):
+    N, C, H, W, K, R, S, stride, pad, groups, pool = shp
+    return workloads.make_random_case(seed, N, C, H, W, K, R, S, stride, pad, groups, pool, z, integer)
+
+
+@pytest.mark.parametrize("shp", SMALL)
+def test_encode_ecr_bit_exact(device, shp):
+    layer, x, w = _mk(101, shp)
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+
+
+@pytest.mark.parametrize("shp", SMALL)
+def test_encode_pecr_bit_exact(device, shp):
+    layer, x, w = _mk(102, shp)
+    check_encode(layer, x, w.shape, sconv.FMT_PECR)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("shp", SMALL)
+def test_forward_parity(device, shp, relu):
+    layer, x, w = _mk(103, shp)
+    check_forward(layer, x, w, relu=relu)
+
+
+@pytest.mark.parametrize("shp", SMALL)
+def test_pool_forward_parity(device, shp):
+    layer, x, w = _mk(104, shp)
+    check_pool_forward(layer, x, w)
+
+
+@pytest.mark.parametrize("shp", SMALL)
+def test_integer_inputs_bit_exact(device, shp):
+    layer, x, w = _mk(105, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    check_pool_forward(layer, x, w, integer_exact=True)
+
+
+@pytest.mark.parametrize("z", [0.0, 0.5, 0.95, 1.0])
+def test_sparsity_extremes(device, z):
+    shp = (2, 24, 15, 15, 40, 3, 3, 1, 1, 1, (2, 2, 2))
+    layer, x, w = _mk(106, shp, z=z)
+    if z == 1.0:
+        assert not x.any()
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    check_encode(layer, x, w.shape, sconv.FMT_PECR)
+    check_forward(layer, x, w, relu=False)
+    check_pool_forward(layer, x, w)
+
+
+def test_negative_zero_denormals_and_negative_values(device):
+    shp = (1, 4, 9, 9, 8, 3, 3, 1, 1, 1, (2, 2, 2))
+    layer, x, w = _mk(107, shp)
+    x = x.copy()
+    x[0, 0, 0, :3] = [-0.0, 1e-42, -2.5]
+    x[0, 1, 4, 4] = -0.0
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    check_forward(layer, x, w, relu=False)
+
+
+def test_tiny_config(device):
+    layer, x, w = workloads.make_layer_inputs(0, 0, 1)
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+
+
+def _layers(ci):
+    return list(enumerate(workloads.CONFIGS[ci]["layers"]))
+
+
+@pytest.mark.parametrize("ci,li", [(ci, li) for ci in (1, 2, 3, 4) for li, _ in _layers(ci)])
+def test_benchmark_layers_batch1(device, ci, li):
+    """Every layer shape of the benchmark configs at batch 1, whole tensor against the oracle."""
+    layer, x, w = workloads.make_layer_inputs(ci, li, 1)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
+    else:
+        check_forward(layer, x, w, relu=True)
+
+
+def test_outputs_are_overwritten_not_accumulated(device):
+    shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(108, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    out = torch.full((1, 16, 12, 12), 1e9, dtype=torch.float32, device="cuda")
+    sconv.sconv_forward(xd, wd, 1, 1, 1, relu=False, out=out)
+    ref = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+
+
+def test_runs_on_a_side_stream(device):
+    shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(109, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    ref = sconv.sconv_forward(xd, wd, 1, 1, 1)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        got = sconv.sconv_forward(xd, wd, 1, 1, 1)
+    s.synchronize()
+    assert torch.equal(got, ref)

@@ -1,0 +1,105 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and turns invalid descriptors into error codes before any GPU call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1909_09927_amd as sconv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "sconv.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(sconv_[a-z_]+)\s*\(", text))
+    assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
+            "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name"} <= names
+    L = sconv.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
+
+
+def test_output_dims_and_sizes():
+    d = sconv.make_desc(2, 16, 28, 28, 32, 3, 3, 1, 1)
+    assert sconv.sconv_output_dims(d) == (28, 28, 0, 0)
+    assert sconv.sconv_encode_sizes(d, sconv.FMT_ECR) == (2 * 784, 144)
+    d = sconv.make_desc(2, 16, 28, 28, 32, 3, 3, 1, 1, pool=(2, 2, 2))
+    assert sconv.sconv_output_dims(d) == (28, 28, 14, 14)
+    assert sconv.sconv_encode_sizes(d, sconv.FMT_PECR) == (2 * 14 * 14 * 4, 144)
+    # figure sizes: 5x5 map, 3x3 kernel -> 3x3; 2x2 pooling stride 1 -> 2x2, 4 windows each
+    d = sconv.make_desc(1, 1, 5, 5, 1, 3, 3, 1, 0, pool=(2, 2, 1))
+    assert sconv.sconv_output_dims(d) == (3, 3, 2, 2)
+    assert sconv.sconv_encode_sizes(d, sconv.FMT_PECR) == (16, 9)
+    # floor: stride 2 on 56 with pad 1 -> 28; grouped L
+    d = sconv.make_desc(1, 128, 56, 56, 128, 3, 3, 2, 1, groups=4)
+    assert sconv.sconv_output_dims(d)[:2] == (28, 28)
+    assert sconv.sconv_encode_sizes(d, sconv.FMT_ECR) == (4 * 784, 32 * 9)
+
+
+BAD = [
+    dict(N=0), dict(C=0), dict(H=-1), dict(K=0), dict(R=0), dict(S=0), dict(stride=0),
+    dict(pad=-1), dict(groups=0), dict(groups=3), dict(K=30, groups=4), dict(pad=3), dict(flags=2),
+    dict(H=1, pad=0),
+]
+
+
+@pytest.mark.parametrize("bad", BAD)
+def test_invalid_descriptors_are_rejected_on_the_host(bad):
+    base = dict(N=1, C=16, H=8, W=8, K=32, R=3, S=3, stride=1, pad=1, groups=1,
+                pool_h=0, pool_w=0, pool_stride=0, flags=0)
+    base.update(bad)
+    d = sconv.Desc(**base)
+    L = sconv.lib()
+    oh, ow = ctypes.c_int32(), ctypes.c_int32()
+    assert L.sconv_output_dims(ctypes.byref(d), ctypes.byref(oh), ctypes.byref(ow), None, None) == sconv.SCONV_EINVAL
+    # non-null dummy pointers: the descriptor check must fire before anything touches them
+    p = ctypes.c_void_p(16)
+    assert L.sconv_forward(ctypes.byref(d), p, p, p, None) == sconv.SCONV_EINVAL
+    assert L.sconv_encode(ctypes.byref(d), 0, p, p, p, p, None) == sconv.SCONV_EINVAL
+
+
+def test_null_pointers_and_bad_pool_and_format():
+    L = sconv.lib()
+    d = sconv.make_desc(1, 16, 8, 8, 32, 3, 3, 1, 1)
+    p = ctypes.c_void_p(16)
+    assert L.sconv_forward(ctypes.byref(d), None, p, p, None) == sconv.SCONV_EINVAL
+    assert L.sconv_forward(ctypes.byref(d), p, None, p, None) == sconv.SCONV_EINVAL
+    assert L.sconv_forward(ctypes.byref(d), p, p, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_forward(None, p, p, p, None) == sconv.SCONV_EINVAL
+    # pooling call without / with an oversized pooling window
+    assert L.sconv_pool_forward(ctypes.byref(d), p, p, p, None) == sconv.SCONV_EINVAL
+    d2 = sconv.make_desc(1, 16, 8, 8, 32, 3, 3, 1, 1, pool=(9, 2, 2))
+    assert L.sconv_pool_forward(ctypes.byref(d2), p, p, p, None) == sconv.SCONV_EINVAL
+    d3 = sconv.make_desc(1, 16, 20, 20, 32, 3, 3, 1, 1, pool=(9, 9, 2))
+    assert L.sconv_pool_forward(ctypes.byref(d3), p, p, p, None) == sconv.SCONV_EUNSUPPORTED
+    rows, sl = ctypes.c_int64(), ctypes.c_int64()
+    assert L.sconv_encode_sizes(ctypes.byref(d), 7, ctypes.byref(rows), ctypes.byref(sl)) == sconv.SCONV_EINVAL
+    assert L.sconv_encode_sizes(ctypes.byref(d), sconv.FMT_PECR, ctypes.byref(rows), ctypes.byref(sl)) == sconv.SCONV_EINVAL
+
+
+def test_too_large_tensors_are_unsupported():
+    L = sconv.lib()
+    p = ctypes.c_void_p(16)
+    d = sconv.make_desc(4096, 1024, 1024, 1024, 8, 1, 1)
+    assert L.sconv_forward(ctypes.byref(d), p, p, p, None) == sconv.SCONV_EUNSUPPORTED
+
+
+def test_strerror_and_variant_name():
+    assert sconv.strerror(0) == "success"
+    assert "invalid" in sconv.strerror(sconv.SCONV_EINVAL)
+    assert sconv.strerror(-99).startswith("unknown")
+    d = sconv.make_desc(1, 256, 56, 56, 64, 1, 1)
+    assert sconv.sconv_variant_name(d) in ("rows", "tap3x3")
+    assert sconv.sconv_variant_name(sconv.Desc()) is None
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    x = torch.zeros(1, 2, 4, 4)
+    w = torch.zeros(2, 2, 3, 3)
+    with pytest.raises(TypeError):
+        sconv.sconv_forward(x, w, pad=1)
