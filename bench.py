@@ -1,0 +1,299 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse convolution (+ fused pooling) path on one MI355X.
+
+Default run: the VGG-19-shaped layer set at batch 8 (three layers: 256->256 @56x56 and
+512->512 @28x28 through sconv_forward with ReLU, 512->512 @14x14 through sconv_pool_forward
+with 2x2/2 max pooling).  One step = one pass over all three layers.  Inputs are synthetic,
+seeded, and resident in device memory before the timed region; consecutive steps rotate through
+several copies of every buffer so that a step does not find its operands in the last-level cache.
+
+Prints ONE JSON line: whole-step dense-equivalent GFLOP/s (the flops a dense convolution of the
+same shapes would need, divided by the time), per-layer figures, the roofline position of the
+dominant kernel (timed live with events on the launch stream), and the CPU oracle timed on a
+bounded sample of the same workload.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config vgg19] [--batch 8]
+  python bench.py --table          # every layer of every config at both batch sizes -> JSON lines
+  python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TF = 157.3  # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
+CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
+
+
+def sum_count(x: np.ndarray, layer: workloads.Layer) -> int:
+    """Total number of stored nonzeros over all window rows (bookkeeping for the flop count):
+    every nonzero element counts once per window that contains it."""
+    def cover(n_in, k, out, stride, pad):
+        c = np.zeros(n_in, np.int64)
+        for o in range(out):
+            lo = o * stride - pad
+            c[max(lo, 0):min(lo + k, n_in)] += 1
+        return c
+    ch = cover(layer.H, layer.R, layer.OH, layer.stride, layer.pad)
+    cw = cover(layer.W, layer.S, layer.OW, layer.stride, layer.pad)
+    nz = (x != 0)
+    per_h = nz.sum(axis=(0, 1)).astype(np.int64)          # [H, W]
+    return int((per_h * np.outer(ch, cw)).sum())
+
+
+def layer_work(layer: workloads.Layer, N: int, x: np.ndarray) -> dict:
+    OH, OW = layer.OH, layer.OW
+    if layer.pool:
+        ph, pw, ps = layer.pool
+        out_elems = N * layer.K * ((OH - ph) // ps + 1) * ((OW - pw) // ps + 1)
+    else:
+        out_elems = N * layer.K * OH * OW
+    dense_flops = 2.0 * N * layer.K * OH * OW * layer.Cg * layer.R * layer.S
+    nz_flops = 2.0 * layer.Kg * sum_count(x, layer)
+    alg_bytes = 4.0 * (x.size + layer.K * layer.Cg * layer.R * layer.S + out_elems)
+    return {"dense_flops": dense_flops, "nz_flops": nz_flops, "alg_bytes": alg_bytes,
+            "zero_ratio": float((x == 0).mean())}
+
+
+class DeviceLayer:
+    """One layer's operands on the device, in `copies` rotating sets."""
+
+    def __init__(self, layer, N, x, w, copies):
+        import torch
+        import paper_1909_09927_amd as sconv
+        self.layer, self.N = layer, N
+        self.sconv = sconv
+        xd = torch.from_numpy(x).cuda()
+        wd = torch.from_numpy(w).cuda()
+        self.sets = []
+        for i in range(copies):
+            xs = xd if i == 0 else xd.clone()
+            ws = wd if i == 0 else wd.clone()
+            if layer.pool:
+                y = sconv.sconv_pool_forward(xs, ws, layer.pool, layer.stride, layer.pad, layer.groups)
+            else:
+                y = sconv.sconv_forward(xs, ws, layer.stride, layer.pad, layer.groups, relu=True)
+            self.sets.append((xs, ws, y))
+        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+        self.variant = sconv.sconv_variant_name(d, bool(layer.pool))
+        self.i = 0
+
+    def run(self):
+        xs, ws, y = self.sets[self.i]
+        self.i = (self.i + 1) % len(self.sets)
+        L = self.layer
+        if L.pool:
+            self.sconv.sconv_pool_forward(xs, ws, L.pool, L.stride, L.pad, L.groups, out=y)
+        else:
+            self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y)
+
+
+def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
+    """Average launch duration in ms, events on the launch stream (torch's current stream)."""
+    import torch
+    for _ in range(warmup):
+        dl.run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        dl.run()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
+    t = ms * 1e-3
+    t_hbm = work["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_valu = work["nz_flops"] / (FP32_VECTOR_PEAK_TF * 1e12)
+    return {
+        "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "ms": round(ms, 5),
+        "zero_ratio": round(work["zero_ratio"], 4),
+        "dense_equiv_gflops": round(work["dense_flops"] / t / 1e9, 1),
+        "nonzero_mac_gflops": round(work["nz_flops"] / t / 1e9, 1),
+        "alg_GBps": round(work["alg_bytes"] / t / 1e9, 1),
+        "hbm_frac": round(work["alg_bytes"] / t / 1e9 / HBM_PEAK_GBS, 4),
+        "valu_frac": round(work["nz_flops"] / t / 1e12 / FP32_VECTOR_PEAK_TF, 4),
+        "bound": "hbm" if t_hbm >= t_valu else "alu",
+        "bound_frac": round(max(t_hbm, t_valu) / t, 4),
+    }
+
+
+def copies_for(work_list) -> int:
+    per_set = sum(w["alg_bytes"] for w in work_list)
+    return int(max(2, min(16, -(-CACHE_BYTES // int(per_set)))))
+
+
+def cpu_baseline(config_index: int) -> dict:
+    """The oracle as it stands, on the host cores, on the same layer set at batch 1."""
+    import oracle
+    cfg = workloads.CONFIGS[config_index]
+    flops, secs = 0.0, 0.0
+    for li, _ in enumerate(cfg["layers"]):
+        layer, x, w = workloads.make_layer_inputs(config_index, li, 1)
+        t0 = time.perf_counter()
+        if layer.pool:
+            oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+        else:
+            oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
+        secs += time.perf_counter() - t0
+        flops += 2.0 * layer.K * layer.OH * layer.OW * layer.Cg * layer.R * layer.S
+    return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
+            "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"one pass over the {cfg['name']} layer set at batch 1 (fp64 dense oracle, "
+                      f"{secs:.2f} s wall)"}
+
+
+def paper_context() -> dict:
+    return {"hardware": "NVIDIA GeForce RTX 2080Ti, CUDA 10.2, cuDNN 7.6.5 (paper, Table 2)",
+            "note": "relative speedups only; context, not a target",
+            "vgg19_conv_layers_vs_cudnn_fast": 3.91, "vgg19_whole_net_vs_cudnn_fast": 1.97,
+            "vgg19_conv_layers_vs_cusparse": 3.28, "single_layer_vs_cudnn_fast": [2.24, 2.78],
+            "single_layer_vs_cusparse": [2.97, 3.99]}
+
+
+def run_headline(args) -> None:
+    import torch
+    ci = [c["name"] for c in workloads.CONFIGS].index(args.config)
+    cfg = workloads.CONFIGS[ci]
+    N = args.batch if args.batch else max(cfg["batches"])
+    host = [workloads.make_layer_inputs(ci, li, N) for li in range(len(cfg["layers"]))]
+    works = [layer_work(layer, N, x) for layer, x, w in host]
+    copies = copies_for(works)
+    dls = [DeviceLayer(layer, N, x, w, copies) for layer, x, w in host]
+    torch.cuda.synchronize()
+
+    def step():
+        for dl in dls:
+            dl.run()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations, events on the launch stream
+    recs = []
+    for dl, wk in zip(dls, works):
+        ms = time_layer(dl, max(20, args.steps), 5)
+        recs.append(layer_record(dl, wk, ms))
+    dom = max(range(len(recs)), key=lambda i: recs[i]["ms"])
+    r, wk = recs[dom], works[dom]
+    t = r["ms"] * 1e-3
+    if r["bound"] == "hbm":
+        roof = {"bound": "hbm", "achieved": round(wk["alg_bytes"] / t / 1e9, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(wk["alg_bytes"] / t / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        ach = wk["nz_flops"] / t / 1e12
+        roof = {"bound": "alu", "achieved": round(ach, 2), "peak": FP32_VECTOR_PEAK_TF, "unit": "TFLOP/s",
+                "frac": round(ach / FP32_VECTOR_PEAK_TF, 4), "traffic": None,
+                "frac_of_unpacked_fp32_peak": round(ach / FP32_UNPACKED_PEAK_TF, 4)}
+    roof["kernel"] = f"{r['variant']} on {r['layer']} N={N}"
+    roof["kernel_ms"] = r["ms"]
+    roof["alg_bytes_per_launch"] = wk["alg_bytes"]
+    roof["nonzero_flops_per_launch"] = wk["nz_flops"]
+
+    dense_total = sum(w["dense_flops"] for w in works)
+    out = {
+        "metric": "dense-equiv GFLOP/s + HBM GB/s (% roofline) per sparse conv(+pool) layer",
+        "value": round(dense_total / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GFLOP/s (dense-equivalent, whole step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}-shaped layer set ({', '.join(l.name for l in cfg['layers'])}), "
+                               f"batch {N}, conv+ReLU / fused conv+ReLU+2x2 max-pool",
+                   "batch": N, "buffer_copies_rotated": copies},
+        "layers": recs,
+        "roofline": roof,
+        "paper_context": paper_context(),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ci)
+    print(json.dumps(out), flush=True)
+
+
+def run_table(args) -> None:
+    """Every layer of every config at each of its batch sizes; one JSON line per layer."""
+    import torch
+    for ci, cfg in enumerate(workloads.CONFIGS):
+        for N in cfg["batches"]:
+            for li in range(len(cfg["layers"])):
+                layer, x, w = workloads.make_layer_inputs(ci, li, N)
+                wk = layer_work(layer, N, x)
+                dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+                ms = time_layer(dl, args.steps, args.warmup)
+                rec = layer_record(dl, wk, ms)
+                rec["config"] = cfg["name"]
+                print(json.dumps(rec), flush=True)
+                del dl
+                torch.cuda.empty_cache()
+
+
+def run_sweep(args) -> None:
+    """Zero-ratio sweep on the RegNetX 896-channel grouped layer (batch from --batch, default 32)."""
+    import torch
+    ci = 4
+    base = workloads.CONFIGS[ci]["layers"][0]
+    N = args.batch or 32
+    for z in workloads.SWEEP_ZERO_RATIOS:
+        layer = base.with_zero_ratio(z)
+        layer, x, w = workloads.make_layer_inputs(ci, 0, N, layer)
+        wk = layer_work(layer, N, x)
+        dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+        ms = time_layer(dl, args.steps, args.warmup)
+        rec = layer_record(dl, wk, ms)
+        rec["config"] = "regnetx16gf-sweep"
+        print(json.dumps(rec), flush=True)
+        del dl
+        torch.cuda.empty_cache()
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="vgg19", choices=[c["name"] for c in workloads.CONFIGS])
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--table", action="store_true")
+    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path has no multi-GPU part (images or filters would "
+                 "simply be split across devices with no exchange); run with --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    import paper_1909_09927_amd as sconv
+    if not os.path.exists(sconv.LIB_PATH):
+        sys.exit("libsconv.so is not built; run python -m paper_1909_09927_amd.build")
+    if args.table:
+        run_table(args)
+    elif args.sweep:
+        run_sweep(args)
+    else:
+        run_headline(args)
+
+
+if __name__ == "__main__":
+    main()
