@@ -1,6 +1,381 @@
-// placeholder: element-stationary 3x3 kernel (not yet enabled)
+// Element-stationary kernel for 3x3 / stride 1 / pad 1 convolutions (the bulk of the VGG-, ResNet-,
+// DenseNet- and RegNet-shaped layers), with the optional 2x2 / stride 2 max-pooling epilogue.
+//
+// Same arithmetic as the window-row formulation (Section 5.4: only nonzero elements are
+// multiplied), different bookkeeping.  A nonzero element x[c][h][w] appears in up to nine window
+// rows, at nine different filter positions; instead of storing it nine times (the "extended"
+// part of ECR) a wavefront finds it once and issues all of its products:
+//   - lanes hold output channels (64*KPL filters per wavefront, KPL per lane);
+//   - the accumulators of a TH x TW output tile live in registers, statically indexed;
+//   - per input channel, the 9*KPL filter values of the lane's filters are read once from an
+//     LDS-staged filter tile and stay in registers while the whole input tile of that channel is
+//     processed (filter reuse = number of nonzeros of the channel inside the tile);
+//   - the input tile (output tile plus halo) is read from HBM/L2 with one coalesced load per
+//     64 positions, one element per lane; ballot(x != 0) gives the nonzero mask - the wavefront
+//     level compaction; zero elements cost one scalar bit test;
+//   - for each set bit the value is broadcast from its lane (readlane -> scalar register) and
+//     the code for that position, which knows at compile time which accumulators and which
+//     filter taps the position touches, runs up to 9*KPL FMAs with a scalar operand.
+// Several wavefronts of a workgroup share the filter tile: NT of them own different spatial
+// tiles, NCS of them split the input channels of one tile (partial sums are reduced through LDS
+// at the end), so that small batches still fill the machine.
+#include <utility>
+
 #include "sconv_internal.h"
+
 namespace sconv {
-bool tap_supported(const Problem&, bool) { return false; }
-int launch_tap(const Problem&, bool, const float*, const float*, float*, hipStream_t) { return SCONV_EUNSUPPORTED; }
+
+namespace {
+
+constexpr int kStageFloats = 9216;  // filter floats per LDS buffer: 16/KPL channels x 9 x 64*KPL
+
+template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_>
+struct Geom {
+    static constexpr int KPL = KPL_;            // filters per lane
+    static constexpr int TH = TH_, TW = TW_;    // output tile
+    static constexpr int HH = HH_, HW = HW_;    // 1: tile carries a halo row/column on each side;
+                                                // 0: tile spans the whole map in that direction
+    static constexpr bool POOL = POOL_;
+    static constexpr int IH = TH + 2 * HH, IW = TW + 2 * HW;
+    static constexpr int NPOS = IH * IW;
+    static constexpr int NX = (NPOS + 63) / 64;  // input registers per channel
+    static constexpr int ACC = TH * TW;
+    static constexpr int KB = 64 * KPL;          // filters per workgroup
+    static constexpr int KBP = KB + 1;           // LDS row stride (odd: conflict-free transposed writes)
+    static constexpr int CCH = 16 / KPL;         // channels per staged chunk
+    static constexpr int ROWS = CCH * 9;         // LDS rows per buffer
+    static constexpr int BUF = ROWS * KBP;       // floats per buffer
+    // 16 wavefronts per workgroup leave 128 registers per lane; tiles whose accumulators and
+    // filter registers do not fit run with 8 wavefronts (up to 256 registers) instead.
+    static constexpr int MAXW = (KPL * ACC + 9 * KPL + 26 > 128) ? 8 : 16;
+};
+
+struct TapCfg {
+    int NT, NCS;        // wavefronts per workgroup = NT spatial tiles x NCS channel slices
+    int CPW;            // channels per wavefront per chunk = CCH / NCS
+    int tiles_x, tiles_y, ntiles;
+};
+
+// One input position P of the tile: test its mask bit, broadcast the value, run its products.
+template <class G, int P>
+__device__ __forceinline__ void position(const unsigned (&mask)[2 * G::NX],
+                                         const float (&xv)[G::NX], float (&acc)[G::KPL][G::ACC],
+                                         const float (&wr)[G::KPL][9])
+{
+    constexpr int q = P / 64, l = P % 64;
+    constexpr int ih = P / G::IW, iw = P % G::IW;
+    if (mask[P / 32] & (1u << (P % 32))) {   // one scalar bit test per position
+        const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xv[q]), l));
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            // x row (oh0 - HH + ih) feeds output row oh = xrow + 1 - r
+            const int orow = ih - G::HH + 1 - r;
+            if (orow < 0 || orow >= G::TH) continue;
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int ocol = iw - G::HW + 1 - s;
+                if (ocol < 0 || ocol >= G::TW) continue;
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+                    acc[i][orow * G::TW + ocol] = fmaf(v, wr[i][r * 3 + s], acc[i][orow * G::TW + ocol]);
+            }
+        }
+    }
 }
+
+template <class G, int... Ps>
+__device__ __forceinline__ void all_positions(std::integer_sequence<int, Ps...>,
+                                              const unsigned (&mask)[2 * G::NX],
+                                              const float (&xv)[G::NX],
+                                              float (&acc)[G::KPL][G::ACC],
+                                              const float (&wr)[G::KPL][9])
+{
+    (position<G, Ps>(mask, xv, acc, wr), ...);
+}
+
+template <class G, int NWV>
+__global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, const float* __restrict__ x,
+                                                   const float* __restrict__ w, float* __restrict__ y)
+{
+    extern __shared__ __align__(16) float lds[];  // two filter buffers; reused for the reduction
+
+    const int tid = threadIdx.x;
+    constexpr int nthr = NWV * 64;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ts = wave % cfg.NT;                  // spatial tile slot
+    const int cs = wave / cfg.NT;                  // channel slice
+    const int n = blockIdx.z / p.G;
+    const int g = blockIdx.z - n * p.G;
+    const int kb0 = blockIdx.y * G::KB;            // first filter of the block inside the group
+    const int tile = blockIdx.x * cfg.NT + ts;
+    const bool tile_ok = tile < cfg.ntiles;
+    const int ty = tile / cfg.tiles_x, tx = tile - ty * cfg.tiles_x;
+    const int oh0 = ty * G::TH, ow0 = tx * G::TW;
+    const int HWp = p.H * p.W;
+
+    // this lane's input positions (one per input register)
+    unsigned xoff[G::NX];   // offset inside a channel plane; 0 (a valid address) when unused
+    bool xok[G::NX];
+#pragma unroll
+    for (int q = 0; q < G::NX; ++q) {
+        const int P = q * 64 + lane;
+        const int ih = P / G::IW, iw = P - ih * G::IW;
+        const int xr = oh0 - G::HH + ih, xc = ow0 - G::HW + iw;
+        xok[q] = tile_ok && P < G::NPOS && xr >= 0 && xr < p.H && xc >= 0 && xc < p.W;
+        xoff[q] = xok[q] ? (unsigned)(xr * p.W + xc) : 0u;
+    }
+    const float* xg = x + ((size_t)n * p.C + (size_t)g * p.Cg) * HWp;
+    const float* wg = w + ((size_t)g * p.Kg + kb0) * p.L;  // filter k of the block: wg + k*L
+    const int kvalid = min(G::KB, p.Kg - kb0);
+
+    float acc[G::KPL][G::ACC];
+#pragma unroll
+    for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+        for (int a = 0; a < G::ACC; ++a) acc[i][a] = 0.0f;
+
+    // filter staging: element e of a chunk = (k, c, j) with c*9+j fastest, as laid out in memory
+    // A filter past the group's last one (ragged last block) re-reads the last valid filter: its
+    // lanes compute values that are never stored, and no address leaves the tensor.
+    constexpr int EPT = kStageFloats / nthr;      // 9 (16 wavefronts) or 18 (8 wavefronts)
+    static_assert(EPT * nthr == kStageFloats, "staging must divide evenly");
+    float stage[EPT];
+    // The element -> (filter, row) arithmetic is redone for every chunk (a few dozen integer
+    // instructions against thousands of FMAs) instead of being kept in registers across the
+    // channel loop: the empty asm hides the thread index from loop-invariant code motion.
+    auto fetch_chunk = [&](int c0) {
+        const float* base = wg + c0 * 9;           // uniform
+        int t = tid;
+        asm volatile("" : "+v"(t));
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int e = t + i * nthr;
+            const int k = e / G::ROWS, rem = e - k * G::ROWS;       // rem = c*9 + j
+            stage[i] = base[(unsigned)(min(k, kvalid - 1) * p.L + rem)];
+        }
+    };
+    auto store_chunk = [&](float* buf) {
+        int t = tid;
+        asm volatile("" : "+v"(t));
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int e = t + i * nthr;
+            const int k = e / G::ROWS, rem = e - k * G::ROWS;
+            buf[rem * G::KBP + k] = stage[i];
+        }
+    };
+    auto load_x = [&](int c, float (&dst)[G::NX]) {
+        const float* base = xg + (size_t)min(c, p.Cg - 1) * HWp;   // uniform; past-the-end prefetch
+#pragma unroll                                                    // re-reads the last channel
+        for (int q = 0; q < G::NX; ++q) {
+            const float t = base[xoff[q]];
+            dst[q] = xok[q] ? t : 0.0f;
+        }
+    };
+
+    const int nchunks = (p.Cg + G::CCH - 1) / G::CCH;
+    fetch_chunk(0);
+    float xn[G::NX];
+    load_x(cs * cfg.CPW, xn);
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        float* buf = lds + (ch & 1) * G::BUF;
+        store_chunk(buf);
+        __syncthreads();
+        if (ch + 1 < nchunks) fetch_chunk((ch + 1) * G::CCH);
+
+        const int cbase = ch * G::CCH + cs * cfg.CPW;   // this wavefront's channels of the chunk
+        for (int cc = 0; cc < cfg.CPW; ++cc) {
+            float xv[G::NX];
+            unsigned mask[2 * G::NX];
+#pragma unroll
+            for (int q = 0; q < G::NX; ++q) {
+                xv[q] = xn[q];
+                const unsigned long long m = __ballot(xv[q] != 0.0f);
+                mask[2 * q] = (unsigned)m;
+                mask[2 * q + 1] = (unsigned)(m >> 32);
+            }
+            // next channel of this wavefront (next chunk's first one after the last of this chunk)
+            const int cnext = (cc + 1 < cfg.CPW) ? cbase + cc + 1 : cbase + G::CCH;
+            load_x(cnext, xn);
+
+            unsigned any = 0;
+#pragma unroll
+            for (int q = 0; q < 2 * G::NX; ++q) any |= mask[q];
+            if (any) {
+                float wr[G::KPL][9];
+                const float* wl = buf + (cs * cfg.CPW + cc) * 9 * G::KBP + lane;
+#pragma unroll
+                for (int j = 0; j < 9; ++j)
+#pragma unroll
+                    for (int i = 0; i < G::KPL; ++i) wr[i][j] = wl[j * G::KBP + 64 * i];
+                all_positions<G>(std::make_integer_sequence<int, G::NPOS>{}, mask, xv, acc, wr);
+            }
+        }
+    }
+
+    // reduce the channel slices: slice r hands its partial sums to slice 0 through LDS
+    if (cfg.NCS > 1) {
+        float* red = lds;  // [NT][KPL*ACC][64]
+        for (int r = 1; r < cfg.NCS; ++r) {
+            __syncthreads();
+            if (cs == r) {
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+                    for (int a = 0; a < G::ACC; ++a)
+                        red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane] = acc[i][a];
+            }
+            __syncthreads();
+            if (cs == 0) {
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+                    for (int a = 0; a < G::ACC; ++a)
+                        acc[i][a] += red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane];
+            }
+        }
+    }
+    if (cs != 0 || !tile_ok) return;
+
+    // epilogue: lane owns filters kb0 + lane + 64*i
+    if (!G::POOL) {
+        const int plane = p.OH * p.OW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            if (k >= kvalid) continue;
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+#pragma unroll
+            for (int a = 0; a < G::ACC; ++a) {
+                const int oh = oh0 + a / G::TW, ow = ow0 + a % G::TW;
+                if (oh < p.OH && ow < p.OW) {
+                    float v = acc[i][a];
+                    if (p.relu) v = fmaxf(v, 0.0f);
+                    yk[oh * p.OW + ow] = v;
+                }
+            }
+        }
+    } else {
+        // 2x2 / stride 2 windows never straddle tiles (TH, TW even, tile origins even)
+        const int plane = p.PH * p.PW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            if (k >= kvalid) continue;
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+#pragma unroll
+            for (int a = 0; a < (G::TH / 2) * (G::TW / 2); ++a) {
+                const int pr = a / (G::TW / 2), pc = a % (G::TW / 2);
+                const int phh = oh0 / 2 + pr, pww = ow0 / 2 + pc;
+                if (phh < p.PH && pww < p.PW) {
+                    const int b = (2 * pr) * G::TW + 2 * pc;
+                    float m = fmaxf(fmaxf(acc[i][b], acc[i][b + 1]),
+                                    fmaxf(acc[i][b + G::TW], acc[i][b + G::TW + 1]));
+                    yk[phh * p.PW + pww] = fmaxf(m, 0.0f);
+                }
+            }
+        }
+    }
+}
+
+template <class G, int NWV>
+int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
+               const float* w, float* y, hipStream_t stream)
+{
+    auto kern = tap_kernel<G, NWV>;
+    static bool opted = false;  // dynamic LDS above 48 KiB is opted into once per kernel
+    if (!opted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return SCONV_ELAUNCH;
+        opted = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, x, w, y);
+    return launch_status();
+}
+
+template <class G>
+int launch_geom(const Problem& p, const float* x, const float* w, float* y, hipStream_t stream)
+{
+    TapCfg cfg;
+    cfg.tiles_y = (p.OH + G::TH - 1) / G::TH;
+    cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
+    cfg.ntiles = cfg.tiles_x * cfg.tiles_y;
+    const int kblocks = (p.Kg + G::KB - 1) / G::KB;
+    const long long tile_waves = (long long)cfg.ntiles * kblocks * p.N * p.G;
+    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
+
+    // Channel slices: enough wavefronts for about 4 per SIMD (4096 on 256 CUs) when the tiles
+    // alone do not provide them; a slice needs at least one channel of every staged chunk.
+    int ncs = 1;
+    while (ncs < G::CCH && ncs < 8 && tile_waves * ncs < 4096) ncs *= 2;
+    // Spatial tiles per workgroup: share the staged filters as widely as 16 wavefronts allow,
+    // within what the reduction buffer holds, and no more slots than there are tiles.
+    if (ncs > G::MAXW) ncs = G::MAXW;
+    int nt = G::MAXW / ncs;
+    if (ncs > 1)
+        while (nt > 1 && nt * red_per_tile > lds_bytes) nt /= 2;
+    while (nt > 1 && nt / 2 >= cfg.ntiles) nt /= 2;
+    // Workgroups have 8 or 16 wavefronts: widen the channel split of small launches.
+    while (nt * ncs < 8 && ncs < G::CCH) ncs *= 2;
+    if (nt * ncs != 8 && nt * ncs != G::MAXW) return SCONV_EUNSUPPORTED;
+    if (ncs > 1 && nt * red_per_tile > lds_bytes) return SCONV_EUNSUPPORTED;
+    cfg.NT = nt;
+    cfg.NCS = ncs;
+    cfg.CPW = G::CCH / ncs;
+
+    const unsigned gx = (unsigned)((cfg.ntiles + nt - 1) / nt);
+    const unsigned gz = (unsigned)(p.N * p.G);
+    if (gz > 65535u || kblocks > 65535) return SCONV_EUNSUPPORTED;
+    const dim3 grid(gx, (unsigned)kblocks, gz);
+    if constexpr (G::MAXW == 16) {
+        if (nt * ncs == 16) return launch_nwv<G, 16>(p, cfg, grid, lds_bytes, x, w, y, stream);
+    }
+    return launch_nwv<G, 8>(p, cfg, grid, lds_bytes, x, w, y, stream);
+}
+
+// Geometry choice.  Generic: 5x7 output tiles with halo (63 input positions, one register).
+// Maps 7 wide and 7 high: one 7x7 tile, no halo (padding contributes nothing).  Pooled: even
+// tiles, 4x14 without column halo for 14-wide maps, else 4x6 with halo.
+enum GeomId { G_NONE, G_5x7, G_7x7_FULL, G_POOL_4x14, G_POOL_4x6 };
+
+GeomId pick(const Problem& p, bool pooled)
+{
+    if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1) return G_NONE;
+    if (p.Cg % (p.Kg > 64 ? 8 : 16)) return G_NONE;   // whole staged chunks of channels only
+    if (pooled) {
+        if (p.ph != 2 || p.pw != 2 || p.ps != 2) return G_NONE;
+        return p.W == 14 ? G_POOL_4x14 : G_POOL_4x6;
+    }
+    if (p.H == 7 && p.W == 7) return G_7x7_FULL;
+    return G_5x7;
+}
+
+template <int KPL>
+int launch_kpl(GeomId id, const Problem& p, const float* x, const float* w, float* y, hipStream_t s)
+{
+    switch (id) {
+    case G_5x7: return launch_geom<Geom<KPL, 5, 7, 1, 1, false>>(p, x, w, y, s);
+    case G_7x7_FULL: return launch_geom<Geom<KPL, 7, 7, 0, 0, false>>(p, x, w, y, s);
+    case G_POOL_4x14: return launch_geom<Geom<KPL, 4, 14, 1, 0, true>>(p, x, w, y, s);
+    case G_POOL_4x6: return launch_geom<Geom<KPL, 4, 6, 1, 1, true>>(p, x, w, y, s);
+    default: return SCONV_EUNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+bool tap_supported(const Problem& p, bool pooled) { return pick(p, pooled) != G_NONE; }
+
+int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t stream)
+{
+    const GeomId id = pick(p, pooled);
+    if (id == G_NONE) return SCONV_EUNSUPPORTED;
+    return p.Kg > 64 ? launch_kpl<2>(id, p, x, w, y, stream) : launch_kpl<1>(id, p, x, w, y, stream);
+}
+
+}  // namespace sconv

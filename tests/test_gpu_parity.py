@@ -26,6 +26,15 @@ SMALL = [
     (2, 96, 14, 14, 96, 3, 3, 1, 1, 3, (2, 2, 2)),
     (1, 16, 21, 21, 20, 7, 7, 2, 3, 1, (2, 2, 2)),      # large kernel
     (1, 8, 40, 40, 16, 3, 3, 1, 1, 1, (7, 7, 3)),       # 49-result pooling window
+    # 3x3 / stride 1 / pad 1 with whole 8- or 16-channel chunks: the element-stationary kernel
+    (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # one filter per lane, ragged filter block
+    (1, 16, 28, 28, 32, 3, 3, 1, 1, 1, (2, 2, 2)),      # half-empty filter block
+    (2, 24, 17, 30, 200, 3, 3, 1, 1, 1, (2, 2, 2)),     # two filters per lane, ragged block, odd sizes
+    (3, 64, 7, 7, 128, 3, 3, 1, 1, 1, (2, 2, 2)),       # whole-map 7x7 tile
+    (2, 48, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)),     # 14-wide pooled tile
+    (2, 64, 14, 14, 64, 3, 3, 1, 1, 2, (2, 2, 2)),      # grouped
+    (1, 256, 9, 12, 256, 3, 3, 1, 1, 1, (2, 2, 2)),     # many chunks, channel slices
+    (9, 16, 6, 5, 130, 3, 3, 1, 1, 1, (2, 2, 2)),       # maps smaller than a tile
 ]
 
 
