@@ -15,6 +15,7 @@ bounded sample of the same workload.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config vgg19] [--batch 8]
   python bench.py --table          # every layer of every config at both batch sizes -> JSON lines
   python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
+  python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
 """
 from __future__ import annotations
 
@@ -267,6 +268,24 @@ def run_sweep(args) -> None:
         torch.cuda.empty_cache()
 
 
+def run_layer(args) -> None:
+    """One layer alone (for profiling): --layer CONFIG:INDEX at --batch."""
+    name, li = args.layer.split(":")
+    ci = [c["name"] for c in workloads.CONFIGS].index(name)
+    N = args.batch or max(workloads.CONFIGS[ci]["batches"])
+    layer, x, w = workloads.make_layer_inputs(ci, int(li), N)
+    if args.zero_ratio >= 0:
+        layer, x, w = workloads.make_layer_inputs(ci, int(li), N, layer.with_zero_ratio(args.zero_ratio))
+    wk = layer_work(layer, N, x)
+    dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+    ms = time_layer(dl, args.steps, args.warmup)
+    rec = layer_record(dl, wk, ms)
+    rec["config"] = name
+    rec["alg_bytes"] = wk["alg_bytes"]
+    rec["nonzero_flops"] = wk["nz_flops"]
+    print(json.dumps(rec), flush=True)
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -277,6 +296,8 @@ def main() -> None:
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
+    ap.add_argument("--zero-ratio", type=float, default=-1.0, help="override the layer's zero ratio (--layer)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part (images or filters would "
@@ -287,7 +308,9 @@ def main() -> None:
     import paper_1909_09927_amd as sconv
     if not os.path.exists(sconv.LIB_PATH):
         sys.exit("libsconv.so is not built; run python -m paper_1909_09927_amd.build")
-    if args.table:
+    if args.layer:
+        run_layer(args)
+    elif args.table:
         run_table(args)
     elif args.sweep:
         run_sweep(args)

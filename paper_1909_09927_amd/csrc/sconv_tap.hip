@@ -27,7 +27,6 @@ namespace sconv {
 
 namespace {
 
-constexpr int kStageFloats = 9216;  // filter floats per LDS buffer: 16/KPL channels x 9 x 64*KPL
 
 template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_>
 struct Geom {
@@ -135,35 +134,26 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
 #pragma unroll
         for (int a = 0; a < G::ACC; ++a) acc[i][a] = 0.0f;
 
-    // filter staging: element e of a chunk = (k, c, j) with c*9+j fastest, as laid out in memory
-    // A filter past the group's last one (ragged last block) re-reads the last valid filter: its
-    // lanes compute values that are never stored, and no address leaves the tensor.
-    constexpr int EPT = kStageFloats / nthr;      // 9 (16 wavefronts) or 18 (8 wavefronts)
-    static_assert(EPT * nthr == kStageFloats, "staging must divide evenly");
+    // Filter staging.  A chunk is KB filters x ROWS = CCH*9 consecutive floats of each filter.
+    // TPF threads share one filter, each moving EPT consecutive floats, so both the global offset
+    // and the LDS index are one per-thread base plus compile-time steps.  A filter past the
+    // group's last one (ragged last block) re-reads the last valid filter: its lanes compute
+    // values that are never stored, and no address leaves the tensor.
+    constexpr int TPF = nthr / G::KB;
+    constexpr int EPT = G::ROWS / TPF;             // 9 (16 wavefronts) or 18 (8 wavefronts)
+    static_assert(TPF * G::KB == nthr && EPT * TPF == G::ROWS, "staging must divide evenly");
     float stage[EPT];
-    // The element -> (filter, row) arithmetic is redone for every chunk (a few dozen integer
-    // instructions against thousands of FMAs) instead of being kept in registers across the
-    // channel loop: the empty asm hides the thread index from loop-invariant code motion.
+    const int sk = tid / TPF, ssub = tid - sk * TPF;
+    const unsigned sgoff = (unsigned)(min(sk, kvalid - 1) * p.L + ssub * EPT);
+    const int sloff = ssub * EPT * G::KBP + sk;
     auto fetch_chunk = [&](int c0) {
-        const float* base = wg + c0 * 9;           // uniform
-        int t = tid;
-        asm volatile("" : "+v"(t));
+        const float* base = wg + c0 * 9 + sgoff;
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const int e = t + i * nthr;
-            const int k = e / G::ROWS, rem = e - k * G::ROWS;       // rem = c*9 + j
-            stage[i] = base[(unsigned)(min(k, kvalid - 1) * p.L + rem)];
-        }
+        for (int i = 0; i < EPT; ++i) stage[i] = base[i];
     };
     auto store_chunk = [&](float* buf) {
-        int t = tid;
-        asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const int e = t + i * nthr;
-            const int k = e / G::ROWS, rem = e - k * G::ROWS;
-            buf[rem * G::KBP + k] = stage[i];
-        }
+        for (int i = 0; i < EPT; ++i) buf[sloff + i * G::KBP] = stage[i];
     };
     auto load_x = [&](int c, float (&dst)[G::NX]) {
         const float* base = xg + (size_t)min(c, p.Cg - 1) * HWp;   // uniform; past-the-end prefetch
@@ -280,6 +270,21 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     }
 }
 
+// Workgroups of one kernel instantiation that fit on a compute unit (asked once).
+template <class G, int NWV>
+int occupancy(size_t lds_bytes)
+{
+    static int occ = 0;
+    if (occ == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, tap_kernel<G, NWV>, NWV * 64, lds_bytes) !=
+                hipSuccess || nb < 1)
+            nb = 1;
+        occ = nb;
+    }
+    return occ;
+}
+
 template <class G, int NWV>
 int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
                const float* w, float* y, hipStream_t stream)
@@ -296,6 +301,13 @@ int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes,
     return launch_status();
 }
 
+// Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
+// each walking Cg channels.  Two knobs: NCS wavefronts split the channels of a tile (more, shorter
+// wavefronts: fills the machine at small batch, evens out the last round of workgroups), and NT
+// tiles share a workgroup (fewer workgroups re-reading the same filters from L2).  Every
+// candidate is priced with a simple model - rounds of workgroups over 256 compute units, SIMDs
+// saturating at about three resident wavefronts, filter staging at 64 bytes per clock per
+// compute unit - and the cheapest is launched.
 template <class G>
 int launch_geom(const Problem& p, const float* x, const float* w, float* y, hipStream_t stream)
 {
@@ -304,35 +316,43 @@ int launch_geom(const Problem& p, const float* x, const float* w, float* y, hipS
     cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
     cfg.ntiles = cfg.tiles_x * cfg.tiles_y;
     const int kblocks = (p.Kg + G::KB - 1) / G::KB;
-    const long long tile_waves = (long long)cfg.ntiles * kblocks * p.N * p.G;
     const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
     const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
+    const double t_channel = 300.0 + 800.0 * G::KPL;   // clocks of one wavefront on one channel
+    const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
-    // Channel slices: enough wavefronts for about 4 per SIMD (4096 on 256 CUs) when the tiles
-    // alone do not provide them; a slice needs at least one channel of every staged chunk.
-    int ncs = 1;
-    while (ncs < G::CCH && ncs < 8 && tile_waves * ncs < 4096) ncs *= 2;
-    // Spatial tiles per workgroup: share the staged filters as widely as 16 wavefronts allow,
-    // within what the reduction buffer holds, and no more slots than there are tiles.
-    if (ncs > G::MAXW) ncs = G::MAXW;
-    int nt = G::MAXW / ncs;
-    if (ncs > 1)
-        while (nt > 1 && nt * red_per_tile > lds_bytes) nt /= 2;
-    while (nt > 1 && nt / 2 >= cfg.ntiles) nt /= 2;
-    // Workgroups have 8 or 16 wavefronts: widen the channel split of small launches.
-    while (nt * ncs < 8 && ncs < G::CCH) ncs *= 2;
-    if (nt * ncs != 8 && nt * ncs != G::MAXW) return SCONV_EUNSUPPORTED;
-    if (ncs > 1 && nt * red_per_tile > lds_bytes) return SCONV_EUNSUPPORTED;
-    cfg.NT = nt;
-    cfg.NCS = ncs;
-    cfg.CPW = G::CCH / ncs;
+    double best = -1.0;
+    int best_nt = 0, best_ncs = 0, best_nwv = 0;
+    for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
+        const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
+        for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
+            const int nt = nwv / ncs;
+            if (ncs > 1 && nt * red_per_tile > lds_bytes) continue;
+            if (nt > 1 && nt / 2 >= cfg.ntiles) continue;       // half of the tile slots empty
+            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            const long long slots = 256LL * occ;
+            const long long rounds = (wgs + slots - 1) / slots;
+            const double per_cu = wgs >= slots ? occ : (double)wgs / 256.0;  // resident workgroups
+            double r = per_cu * nwv / 4.0;                                  // wavefronts per SIMD
+            if (r < 3.0) r = 3.0;
+            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
+                                (ncs - 1) * 2000.0;                       // reduction steps
+            if (best < 0.0 || cost < best) {
+                best = cost; best_nt = nt; best_ncs = ncs; best_nwv = nwv;
+            }
+        }
+    }
+    if (best < 0.0) return SCONV_EUNSUPPORTED;
+    cfg.NT = best_nt;
+    cfg.NCS = best_ncs;
+    cfg.CPW = G::CCH / best_ncs;
 
-    const unsigned gx = (unsigned)((cfg.ntiles + nt - 1) / nt);
+    const long long gx = (cfg.ntiles + cfg.NT - 1) / cfg.NT;
     const unsigned gz = (unsigned)(p.N * p.G);
-    if (gz > 65535u || kblocks > 65535) return SCONV_EUNSUPPORTED;
-    const dim3 grid(gx, (unsigned)kblocks, gz);
+    if (gz > 65535u || kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)kblocks, gz);
     if constexpr (G::MAXW == 16) {
-        if (nt * ncs == 16) return launch_nwv<G, 16>(p, cfg, grid, lds_bytes, x, w, y, stream);
+        if (best_nwv == 16) return launch_nwv<G, 16>(p, cfg, grid, lds_bytes, x, w, y, stream);
     }
     return launch_nwv<G, 8>(p, cfg, grid, lds_bytes, x, w, y, stream);
 }
