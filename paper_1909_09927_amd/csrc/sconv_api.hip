@@ -124,7 +124,10 @@ extern "C" int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const
     int rc = fill_problem(desc, false, &p);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
-    if (choose(p, false) == V_TAP) return launch_tap(p, false, x_dev, w_dev, y_dev, s);
+    if (choose(p, false) == V_TAP) {
+        rc = launch_tap(p, false, x_dev, w_dev, y_dev, s);
+        if (rc != SCONV_EUNSUPPORTED) return rc;   // no applicable tile plan: the general kernel runs
+    }
     return launch_rows(p, false, x_dev, w_dev, y_dev, s);
 }
 
@@ -137,7 +140,10 @@ extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, 
     if (rc) return rc;
     if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
     hipStream_t s = (hipStream_t)hip_stream;
-    if (choose(p, true) == V_TAP) return launch_tap(p, true, x_dev, w_dev, y_dev, s);
+    if (choose(p, true) == V_TAP) {
+        rc = launch_tap(p, true, x_dev, w_dev, y_dev, s);
+        if (rc != SCONV_EUNSUPPORTED) return rc;
+    }
     return launch_rows(p, true, x_dev, w_dev, y_dev, s);
 }
 

@@ -19,6 +19,10 @@
 // Several wavefronts of a workgroup share the filter tile: NT of them own different spatial
 // tiles, NCS of them split the input channels of one tile (partial sums are reduced through LDS
 // at the end), so that small batches still fill the machine.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
 #include <utility>
 
 #include "sconv_internal.h"
@@ -301,16 +305,26 @@ int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes,
     return launch_status();
 }
 
+// Plan of one launch: the split of a geometry's work over wavefronts and its modelled cost.
+struct Plan {
+    double cost = -1.0;   // model clocks; negative = not applicable
+    TapCfg cfg;
+    int nwv = 0;
+    int kblocks = 0;
+};
+
 // Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
 // each walking Cg channels.  Two knobs: NCS wavefronts split the channels of a tile (more, shorter
 // wavefronts: fills the machine at small batch, evens out the last round of workgroups), and NT
 // tiles share a workgroup (fewer workgroups re-reading the same filters from L2).  Every
 // candidate is priced with a simple model - rounds of workgroups over 256 compute units, SIMDs
-// saturating at about three resident wavefronts, filter staging at 64 bytes per clock per
-// compute unit - and the cheapest is launched.
+// saturating at about four resident wavefronts, one scalar test per input position and channel,
+// filter staging at 64 bytes per clock per compute unit - and the cheapest is launched.  The
+// density of the input is not known on the host; the model assumes 30 % nonzeros.
 template <class G>
-int launch_geom(const Problem& p, const float* x, const float* w, float* y, hipStream_t stream)
+Plan plan_geom(const Problem& p)
 {
+    Plan best;
     TapCfg cfg;
     cfg.tiles_y = (p.OH + G::TH - 1) / G::TH;
     cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
@@ -318,84 +332,124 @@ int launch_geom(const Problem& p, const float* x, const float* w, float* y, hipS
     const int kblocks = (p.Kg + G::KB - 1) / G::KB;
     const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
     const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
-    const double t_channel = 300.0 + 800.0 * G::KPL;   // clocks of one wavefront on one channel
+    // clocks of SIMD issue time for one wavefront on one channel: a bit test and branch per
+    // position, and per nonzero a broadcast plus its share of the tile's 9*ACC*KPL FMAs
+    const double nnz = 0.3 * G::NPOS;
+    const double t_channel = 60.0 + 6.0 * G::NPOS + nnz * (14.0 + 4.5 * 9.0 * G::ACC * G::KPL / G::NPOS);
     const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
-    double best = -1.0;
-    int best_nt = 0, best_ncs = 0, best_nwv = 0;
+    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_TAP_SPLIT="nwv,ncs"
+    if (const char* pin = getenv("SCONV_TAP_SPLIT")) {
+        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
+    }
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
+            if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
             if (ncs > 1 && nt * red_per_tile > lds_bytes) continue;
-            if (nt > 1 && nt / 2 >= cfg.ntiles) continue;       // half of the tile slots empty
+            if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
             const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
             const long long slots = 256LL * occ;
             const long long rounds = (wgs + slots - 1) / slots;
-            const double per_cu = wgs >= slots ? occ : (double)wgs / 256.0;  // resident workgroups
-            double r = per_cu * nwv / 4.0;                                  // wavefronts per SIMD
-            if (r < 3.0) r = 3.0;
+            const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
+            double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
+            if (r < 4.0) r = 4.0;
             const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
-                                (ncs - 1) * 2000.0;                       // reduction steps
-            if (best < 0.0 || cost < best) {
-                best = cost; best_nt = nt; best_ncs = ncs; best_nwv = nwv;
+                                (ncs - 1) * 2000.0;                              // reduction steps
+            if (best.cost < 0.0 || cost < best.cost) {
+                best.cost = cost;
+                best.cfg = cfg;
+                best.cfg.NT = nt;
+                best.cfg.NCS = ncs;
+                best.cfg.CPW = G::CCH / ncs;
+                best.nwv = nwv;
+                best.kblocks = kblocks;
             }
         }
     }
-    if (best < 0.0) return SCONV_EUNSUPPORTED;
-    cfg.NT = best_nt;
-    cfg.NCS = best_ncs;
-    cfg.CPW = G::CCH / best_ncs;
+    return best;
+}
 
-    const long long gx = (cfg.ntiles + cfg.NT - 1) / cfg.NT;
+template <class G>
+int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+                hipStream_t stream)
+{
+    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
     const unsigned gz = (unsigned)(p.N * p.G);
-    if (gz > 65535u || kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
-    const dim3 grid((unsigned)gx, (unsigned)kblocks, gz);
+    if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, gz);
     if constexpr (G::MAXW == 16) {
-        if (best_nwv == 16) return launch_nwv<G, 16>(p, cfg, grid, lds_bytes, x, w, y, stream);
+        if (pl.nwv == 16) return launch_nwv<G, 16>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
     }
-    return launch_nwv<G, 8>(p, cfg, grid, lds_bytes, x, w, y, stream);
+    return launch_nwv<G, 8>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
 }
 
-// Geometry choice.  Generic: 5x7 output tiles with halo (63 input positions, one register).
-// Maps 7 wide and 7 high: one 7x7 tile, no halo (padding contributes nothing).  Pooled: even
-// tiles, 4x14 without column halo for 14-wide maps, else 4x6 with halo.
-enum GeomId { G_NONE, G_5x7, G_7x7_FULL, G_POOL_4x14, G_POOL_4x6 };
+// Geometries.  Generic: 5x7 output tiles with halo (63 input positions, one register).  Maps
+// 7 wide and 7 high: one 7x7 tile, no halo (padding contributes nothing).  Pooled: even tiles,
+// 4x14 without column halo for 14-wide maps, or 4x6 with halo.
+using G57_1 = Geom<1, 5, 7, 1, 1, false>;
+using G57_2 = Geom<2, 5, 7, 1, 1, false>;
+using G77_1 = Geom<1, 7, 7, 0, 0, false>;
+using G77_2 = Geom<2, 7, 7, 0, 0, false>;
+using P414_1 = Geom<1, 4, 14, 1, 0, true>;
+using P414_2 = Geom<2, 4, 14, 1, 0, true>;
+using P46_1 = Geom<1, 4, 6, 1, 1, true>;
+using P46_2 = Geom<2, 4, 6, 1, 1, true>;
 
-GeomId pick(const Problem& p, bool pooled)
+bool shape_ok(const Problem& p, bool pooled)
 {
-    if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1) return G_NONE;
-    if (p.Cg % (p.Kg > 64 ? 8 : 16)) return G_NONE;   // whole staged chunks of channels only
-    if (pooled) {
-        if (p.ph != 2 || p.pw != 2 || p.ps != 2) return G_NONE;
-        return p.W == 14 ? G_POOL_4x14 : G_POOL_4x6;
-    }
-    if (p.H == 7 && p.W == 7) return G_7x7_FULL;
-    return G_5x7;
+    if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1) return false;
+    if (p.Cg % 16) return false;                      // whole staged chunks of channels only
+    if (pooled && (p.ph != 2 || p.pw != 2 || p.ps != 2)) return false;
+    return true;
 }
 
-template <int KPL>
-int launch_kpl(GeomId id, const Problem& p, const float* x, const float* w, float* y, hipStream_t s)
-{
-    switch (id) {
-    case G_5x7: return launch_geom<Geom<KPL, 5, 7, 1, 1, false>>(p, x, w, y, s);
-    case G_7x7_FULL: return launch_geom<Geom<KPL, 7, 7, 0, 0, false>>(p, x, w, y, s);
-    case G_POOL_4x14: return launch_geom<Geom<KPL, 4, 14, 1, 0, true>>(p, x, w, y, s);
-    case G_POOL_4x6: return launch_geom<Geom<KPL, 4, 6, 1, 1, true>>(p, x, w, y, s);
-    default: return SCONV_EUNSUPPORTED;
-    }
-}
+struct Candidate {
+    const char* name;
+    Plan (*plan)(const Problem&);
+    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    bool pooled, two_per_lane, needs_7x7, needs_w14;
+};
+
+const Candidate kCandidates[] = {
+    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, false, false, false},
+    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, true, false, false},
+    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, false, true, false},
+    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, true, true, false},
+    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, false, false, true},
+    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, true, false, true},
+    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, false, false, false},
+    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, true, false, false},
+};
 
 }  // namespace
 
-bool tap_supported(const Problem& p, bool pooled) { return pick(p, pooled) != G_NONE; }
+bool tap_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
 int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t stream)
 {
-    const GeomId id = pick(p, pooled);
-    if (id == G_NONE) return SCONV_EUNSUPPORTED;
-    return p.Kg > 64 ? launch_kpl<2>(id, p, x, w, y, stream) : launch_kpl<1>(id, p, x, w, y, stream);
+    if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
+    const char* pin = getenv("SCONV_TAP_GEOM");   // tuning aid: candidate name
+    const Candidate* best = nullptr;
+    Plan best_plan;
+    for (const Candidate& c : kCandidates) {
+        if (c.pooled != pooled) continue;
+        if (c.two_per_lane && p.Kg <= 64) continue;
+        if (c.needs_7x7 && !(p.H == 7 && p.W == 7)) continue;
+        if (c.needs_w14 && p.W != 14) continue;
+        if (pin && strcmp(pin, c.name)) continue;
+        const Plan pl = c.plan(p);
+        if (pl.cost < 0.0) continue;
+        if (!best || pl.cost < best_plan.cost) {
+            best = &c;
+            best_plan = pl;
+        }
+    }
+    if (!best) return SCONV_EUNSUPPORTED;
+    return best->launch(best_plan, p, x, w, y, stream);
 }
 
 }  // namespace sconv
