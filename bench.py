@@ -139,24 +139,24 @@ def copies_for(work_list) -> int:
     return int(max(2, min(16, -(-CACHE_BYTES // int(per_set)))))
 
 
-def cpu_baseline(config_index: int) -> dict:
-    """The oracle as it stands, on the host cores, on the same layer set at batch 1."""
+def cpu_baseline(config_index: int, batch: int = 2) -> dict:
+    """The oracle as it stands, on the host cores, on the same layer set at a small batch."""
     import oracle
     cfg = workloads.CONFIGS[config_index]
     flops, secs = 0.0, 0.0
     for li, _ in enumerate(cfg["layers"]):
-        layer, x, w = workloads.make_layer_inputs(config_index, li, 1)
+        layer, x, w = workloads.make_layer_inputs(config_index, li, batch)
         t0 = time.perf_counter()
         if layer.pool:
             oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
         else:
             oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
         secs += time.perf_counter() - t0
-        flops += 2.0 * layer.K * layer.OH * layer.OW * layer.Cg * layer.R * layer.S
+        flops += 2.0 * batch * layer.K * layer.OH * layer.OW * layer.Cg * layer.R * layer.S
     return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
             "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"one pass over the {cfg['name']} layer set at batch 1 (fp64 dense oracle, "
-                      f"{secs:.2f} s wall)"}
+            "sample": f"one pass over the {cfg['name']} layer set at batch {batch} (fp64 dense oracle, "
+                      f"{secs:.2f} s wall, about {secs * oracle.threads():.0f} core-seconds)"}
 
 
 def paper_context() -> dict:
@@ -286,6 +286,18 @@ def run_layer(args) -> None:
     print(json.dumps(rec), flush=True)
 
 
+def run_copy_calibration(args) -> None:
+    """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    nbytes = 1 << 30
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+    b = torch.empty_like(a)
+    for _ in range(5):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "launches": 5}), flush=True)
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +308,8 @@ def main() -> None:
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a 1 GiB device copy (scales the HBM traffic counters)")
     ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
     ap.add_argument("--zero-ratio", type=float, default=-1.0, help="override the layer's zero ratio (--layer)")
     args = ap.parse_args()
@@ -308,7 +322,9 @@ def main() -> None:
     import paper_1909_09927_amd as sconv
     if not os.path.exists(sconv.LIB_PATH):
         sys.exit("libsconv.so is not built; run python -m paper_1909_09927_amd.build")
-    if args.layer:
+    if args.copy_calibration:
+        run_copy_calibration(args)
+    elif args.layer:
         run_layer(args)
     elif args.table:
         run_table(args)
