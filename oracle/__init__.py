@@ -59,6 +59,8 @@ def _load():
         lib.oracle_spmv.restype = None
         lib.oracle_conv.argtypes = [P(Shape), P(f32), P(f32), ctypes.c_int, P(f64), P(f64)]
         lib.oracle_conv.restype = None
+        lib.oracle_conv_at.argtypes = [P(Shape), P(f32), P(f32), ctypes.c_int, i64, P(i32), P(f64), P(f64)]
+        lib.oracle_conv_at.restype = None
         lib.oracle_maxpool.argtypes = [P(Shape), P(f64), P(f64), P(f64), P(f64)]
         lib.oracle_maxpool.restype = None
         lib.oracle_conv_pool.argtypes = [P(Shape), P(f32), P(f32), P(f64), P(f64), P(f64), P(f64)]
@@ -146,6 +148,20 @@ def conv(x, w, stride=1, pad=0, groups=1, relu=False, want_absdot=True):
     a = np.empty_like(y) if want_absdot else None
     lib.oracle_conv(ctypes.byref(shape), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
                     1 if relu else 0, _ptr(y, ctypes.c_double), _ptr(a, ctypes.c_double))
+    return y, a
+
+
+def conv_at(x, w, points, stride=1, pad=0, groups=1, relu=False):
+    """The plain fp64 convolution at listed outputs: points[i] = (n, k, oh, ow) -> (y[i], absdot[i])."""
+    lib = _load()
+    x, w = _f32(x), _f32(w)
+    shape = make_shape(x.shape, w.shape, stride, pad, groups)
+    pts = np.ascontiguousarray(points, np.int32).reshape(-1, 4)
+    y = np.empty((pts.shape[0],), np.float64)
+    a = np.empty_like(y)
+    lib.oracle_conv_at(ctypes.byref(shape), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
+                       1 if relu else 0, pts.shape[0], _ptr(pts, ctypes.c_int32),
+                       _ptr(y, ctypes.c_double), _ptr(a, ctypes.c_double))
     return y, a
 
 

@@ -207,6 +207,32 @@ void oracle_conv(const oracle_shape_t* s, const float* x, const float* w, int re
 }
 
 /*
+ * The same definition evaluated at listed outputs only (for tensors too large to compute whole):
+ * points[i] = (n, k, oh, ow); y[i] and absdot[i] as in oracle_conv.
+ */
+void oracle_conv_at(const oracle_shape_t* s, const float* x, const float* w, int relu, int64_t npoints,
+                    const int32_t* points, double* y, double* absdot)
+{
+    const int Cg = s->C / s->groups, Kg = s->K / s->groups;
+    for (int64_t i = 0; i < npoints; ++i) {
+        const int n = points[4 * i], k = points[4 * i + 1], oh = points[4 * i + 2], ow = points[4 * i + 3];
+        const int g = k / Kg;
+        double acc = 0.0, mag = 0.0;
+        for (int c = 0; c < Cg; ++c)
+            for (int r = 0; r < s->R; ++r)
+                for (int q = 0; q < s->S; ++q) {
+                    double xv = X(x, s, n, g * Cg + c, oh * s->stride - s->pad + r, ow * s->stride - s->pad + q);
+                    double wv = w[(((size_t)k * Cg + c) * s->R + r) * s->S + q];
+                    acc += xv * wv;
+                    mag += fabs(xv * wv);
+                }
+        if (relu && acc < 0.0) acc = 0.0;
+        y[i] = acc;
+        if (absdot) absdot[i] = mag;
+    }
+}
+
+/*
  * Max pooling p_h x p_w with stride p_s, no padding, floor sizes, over an [N][K][OH][OW]
  * tensor: z[N][K][PH][PW] = max over the window.  scale_in/scale_out (optional) carry the
  * error scale: the window maximum of it (max is 1-Lipschitz in every argument).

@@ -410,18 +410,20 @@ struct Candidate {
     const char* name;
     Plan (*plan)(const Problem&);
     int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
-    bool pooled, two_per_lane, needs_7x7, needs_w14;
+    bool pooled;
+    int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
+    bool needs_7x7, needs_w14;
 };
 
 const Candidate kCandidates[] = {
-    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, false, false, false},
-    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, true, false, false},
-    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, false, true, false},
-    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, true, true, false},
-    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, false, false, true},
-    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, true, false, true},
-    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, false, false, false},
-    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, true, false, false},
+    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, 1, false, false},
+    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, 2, false, false},
+    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, 1, true, false},
+    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, 2, true, false},
+    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, 1, false, true},
+    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, 2, false, true},
+    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, false, false},
+    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, false, false},
 };
 
 }  // namespace
@@ -437,7 +439,7 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     Plan best_plan;
     for (const Candidate& c : kCandidates) {
         if (c.pooled != pooled) continue;
-        if (c.two_per_lane && p.Kg <= 64) continue;
+        if (p.Kg <= 64 * (c.kpl - 1)) continue;
         if (c.needs_7x7 && !(p.H == 7 && p.W == 7)) continue;
         if (c.needs_w14 && p.W != 14) continue;
         if (pin && strcmp(pin, c.name)) continue;

@@ -118,6 +118,61 @@ def test_benchmark_layers_batch1(device, ci, li):
         check_forward(layer, x, w, relu=True)
 
 
+def _full_size_cases():
+    out = []
+    for ci in (1, 2, 3, 4):
+        N = max(workloads.CONFIGS[ci]["batches"])
+        for li, _ in _layers(ci):
+            out.append((ci, li, N))
+    return out
+
+
+@pytest.mark.parametrize("ci,li,N", _full_size_cases())
+def test_benchmark_layers_full_batch_sampled(device, ci, li, N):
+    """Every benchmark layer at its largest batch, in the launch configuration bench.py times:
+    sampled outputs against the oracle evaluated point by point, plus properties that hold for the
+    whole tensor (ReLU range, all-zero images give zero, same result when called twice)."""
+    import oracle
+    from parity import TOL
+    layer, x, w = workloads.make_layer_inputs(ci, li, N)
+    x[N - 1] = 0                                   # one all-zero image: its outputs must be exactly 0
+    xd, wd = to_dev(x), to_dev(w)
+    rng = np.random.default_rng(1000 * ci + li)
+    if layer.pool:
+        y = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+        y2 = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+    else:
+        y = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
+        y2 = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    got = y.cpu().numpy()
+    assert (got >= 0).all() and np.isfinite(got).all()
+    assert not got[N - 1].any()
+    npts = 4000
+    pts = np.stack([rng.integers(0, d, size=npts) for d in got.shape], axis=1)
+    # corners and edges of the map and the last filter are always among the samples
+    pts[:8, 2] = [0, 0, got.shape[2] - 1, got.shape[2] - 1, 0, got.shape[2] - 1, 1, 0]
+    pts[:8, 3] = [0, got.shape[3] - 1, 0, got.shape[3] - 1, 1, 1, 0, 0]
+    pts[:8, 1] = got.shape[1] - 1
+    if layer.pool:
+        ph, pw, ps = layer.pool
+        ref = np.zeros(npts)
+        scale = np.zeros(npts)
+        for py in range(ph):
+            for px in range(pw):
+                q = pts.copy()
+                q[:, 2] = pts[:, 2] * ps + py
+                q[:, 3] = pts[:, 3] * ps + px
+                v, a = oracle.conv_at(x, w, q, layer.stride, layer.pad, layer.groups, relu=True)
+                ref = np.maximum(ref, v)
+                scale = np.maximum(scale, a)
+    else:
+        ref, scale = oracle.conv_at(x, w, pts, layer.stride, layer.pad, layer.groups, relu=True)
+    err = np.abs(got[tuple(pts.T)].astype(np.float64) - ref)
+    assert (err <= TOL * scale).all(), f"worst ratio {np.max(err / np.maximum(scale, 1e-300)):.3e}"
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)

@@ -148,6 +148,20 @@ def test_integer_inputs_are_exact():
         assert np.array_equal(y, np.round(y))
 
 
+@pytest.mark.parametrize("shp", SHAPES)
+def test_conv_at_points_matches_library(shp):
+    layer, x, w = _case(13, shp)
+    ref = _torch_conv(x, w, shp[7], shp[8], shp[9])
+    ref_a = _torch_conv(np.abs(x), np.abs(w), shp[7], shp[8], shp[9])
+    rng = np.random.default_rng(1)
+    pts = np.stack([rng.integers(0, d, size=40) for d in ref.shape], axis=1)
+    y, a = oracle.conv_at(x, w, pts, shp[7], shp[8], shp[9])
+    np.testing.assert_allclose(y, ref[tuple(pts.T)], rtol=0, atol=1e-11)
+    np.testing.assert_allclose(a, ref_a[tuple(pts.T)], rtol=1e-12, atol=1e-12)
+    yr, _ = oracle.conv_at(x, w, pts, shp[7], shp[8], shp[9], relu=True)
+    np.testing.assert_array_equal(yr, np.maximum(y, 0))
+
+
 def test_relu_flag():
     shp = SHAPES[1]
     layer, x, w = _case(41, shp)
