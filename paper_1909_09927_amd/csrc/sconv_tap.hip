@@ -1,5 +1,6 @@
-// Element-stationary kernel for 3x3 / stride 1 / pad 1 convolutions (the bulk of the VGG-, ResNet-,
-// DenseNet- and RegNet-shaped layers), with the optional 2x2 / stride 2 max-pooling epilogue.
+// Element-stationary kernel for 3x3 / pad 1 convolutions of stride 1 or 2 (the bulk of the VGG-,
+// ResNet-, DenseNet- and RegNet-shaped layers), with the optional 2x2 / stride 2 max-pooling
+// epilogue (stride 1 only).
 //
 // Same arithmetic as the window-row formulation (Section 5.4: only nonzero elements are
 // multiplied), different bookkeeping.  A nonzero element x[c][h][w] appears in up to nine window
@@ -32,14 +33,16 @@ namespace sconv {
 namespace {
 
 
-template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_>
+template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_, int STRIDE_ = 1>
 struct Geom {
     static constexpr int KPL = KPL_;            // filters per lane
     static constexpr int TH = TH_, TW = TW_;    // output tile
     static constexpr int HH = HH_, HW = HW_;    // 1: tile carries a halo row/column on each side;
                                                 // 0: tile spans the whole map in that direction
     static constexpr bool POOL = POOL_;
-    static constexpr int IH = TH + 2 * HH, IW = TW + 2 * HW;
+    static constexpr int STRIDE = STRIDE_;      // convolution stride (2 only with halo on both axes)
+    // input rows oh0*STRIDE - HH .. (oh0+TH-1)*STRIDE + 1 (pad 1, 3 taps)
+    static constexpr int IH = (TH - 1) * STRIDE + 1 + 2 * HH, IW = (TW - 1) * STRIDE + 1 + 2 * HW;
     static constexpr int NPOS = IH * IW;
     static constexpr int NX = (NPOS + 63) / 64;  // input registers per channel
     static constexpr int ACC = TH * TW;
@@ -71,13 +74,15 @@ __device__ __forceinline__ void position(const unsigned (&mask)[2 * G::NX],
         const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xv[q]), l));
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
-            // x row (oh0 - HH + ih) feeds output row oh = xrow + 1 - r
-            const int orow = ih - G::HH + 1 - r;
-            if (orow < 0 || orow >= G::TH) continue;
+            // x row xr = oh0*STRIDE - HH + ih feeds the output row oh with oh*STRIDE - 1 + r = xr
+            const int nr = ih - G::HH + 1 - r;
+            if (nr < 0 || nr % G::STRIDE != 0 || nr / G::STRIDE >= G::TH) continue;
+            const int orow = nr / G::STRIDE;
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                const int ocol = iw - G::HW + 1 - s;
-                if (ocol < 0 || ocol >= G::TW) continue;
+                const int nc = iw - G::HW + 1 - s;
+                if (nc < 0 || nc % G::STRIDE != 0 || nc / G::STRIDE >= G::TW) continue;
+                const int ocol = nc / G::STRIDE;
 #pragma unroll
                 for (int i = 0; i < G::KPL; ++i)
                     acc[i][orow * G::TW + ocol] = fmaf(v, wr[i][r * 3 + s], acc[i][orow * G::TW + ocol]);
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     for (int q = 0; q < G::NX; ++q) {
         const int P = q * 64 + lane;
         const int ih = P / G::IW, iw = P - ih * G::IW;
-        const int xr = oh0 - G::HH + ih, xc = ow0 - G::HW + iw;
+        const int xr = oh0 * G::STRIDE - G::HH + ih, xc = ow0 * G::STRIDE - G::HW + iw;
         xok[q] = tile_ok && P < G::NPOS && xr >= 0 && xr < p.H && xc >= 0 && xc < p.W;
         xoff[q] = xok[q] ? (unsigned)(xr * p.W + xc) : 0u;
     }
@@ -397,10 +402,13 @@ using P414_1 = Geom<1, 4, 14, 1, 0, true>;
 using P414_2 = Geom<2, 4, 14, 1, 0, true>;
 using P46_1 = Geom<1, 4, 6, 1, 1, true>;
 using P46_2 = Geom<2, 4, 6, 1, 1, true>;
+using S34_1 = Geom<1, 3, 4, 1, 1, false, 2>;   // stride 2: 7x9 input positions feed 3x4 outputs
+using S34_2 = Geom<2, 3, 4, 1, 1, false, 2>;
 
 bool shape_ok(const Problem& p, bool pooled)
 {
-    if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1) return false;
+    if (p.R != 3 || p.S != 3 || p.pad != 1) return false;
+    if (p.stride != 1 && !(p.stride == 2 && !pooled)) return false;
     if (p.Cg % 16) return false;                      // whole staged chunks of channels only
     if (pooled && (p.ph != 2 || p.pw != 2 || p.ps != 2)) return false;
     return true;
@@ -413,17 +421,20 @@ struct Candidate {
     bool pooled;
     int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
     bool needs_7x7, needs_w14;
+    int stride;
 };
 
 const Candidate kCandidates[] = {
-    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, 1, false, false},
-    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, 2, false, false},
-    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, 1, true, false},
-    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, 2, true, false},
-    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, 1, false, true},
-    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, 2, false, true},
-    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, false, false},
-    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, false, false},
+    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, 1, false, false, 1},
+    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, 2, false, false, 1},
+    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, 1, true, false, 1},
+    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, 2, true, false, 1},
+    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, 1, false, true, 1},
+    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, 2, false, true, 1},
+    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, false, false, 1},
+    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, false, false, 1},
+    {"s2-3x4k1", plan_geom<S34_1>, launch_plan<S34_1>, false, 1, false, false, 2},
+    {"s2-3x4k2", plan_geom<S34_2>, launch_plan<S34_2>, false, 2, false, false, 2},
 };
 
 }  // namespace
@@ -438,7 +449,7 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {
-        if (c.pooled != pooled) continue;
+        if (c.pooled != pooled || c.stride != p.stride) continue;
         if (p.Kg <= 64 * (c.kpl - 1)) continue;
         if (c.needs_7x7 && !(p.H == 7 && p.W == 7)) continue;
         if (c.needs_w14 && p.W != 14) continue;

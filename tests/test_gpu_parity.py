@@ -35,6 +35,10 @@ SMALL = [
     (2, 64, 14, 14, 64, 3, 3, 1, 1, 2, (2, 2, 2)),      # grouped
     (1, 256, 9, 12, 256, 3, 3, 1, 1, 1, (2, 2, 2)),     # many chunks, channel slices
     (9, 16, 6, 5, 130, 3, 3, 1, 1, 1, (2, 2, 2)),       # maps smaller than a tile
+    # 3x3 / stride 2 / pad 1: the stride-2 tiles of the same kernel
+    (2, 32, 19, 23, 70, 3, 3, 2, 1, 1, (2, 2, 2)),      # odd sizes, one filter per lane
+    (1, 48, 28, 28, 160, 3, 3, 2, 1, 1, (2, 2, 2)),     # two filters per lane, ragged block
+    (3, 64, 8, 9, 64, 3, 3, 2, 1, 4, (2, 2, 1)),        # grouped, tiny maps
 ]
 
 
