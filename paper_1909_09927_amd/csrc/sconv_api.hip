@@ -55,13 +55,31 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     return SCONV_OK;
 }
 
-enum Variant { V_ROWS, V_TAP };
+enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW };
 
 static Variant choose(const Problem& p, bool pooled)
 {
     const char* pin = getenv("SCONV_VARIANT");
     if (pin && !strcmp(pin, "rows")) return V_ROWS;
+    if (pin && !strcmp(pin, "tap")) return tap_supported(p, pooled) ? V_TAP : V_ROWS;
+    if (pw_supported(p, pooled)) return V_PW;
+    if (quad_supported(p, pooled)) return V_QUAD;
     return tap_supported(p, pooled) ? V_TAP : V_ROWS;
+}
+
+static int run(Variant v, const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t s)
+{
+    int rc = SCONV_EUNSUPPORTED;
+    if (v == V_PW) rc = launch_pointwise(p, pooled, x, w, y, s);
+    if (v == V_QUAD) {
+        rc = launch_quad(p, pooled, x, w, y, s);
+        if (rc == SCONV_EUNSUPPORTED && tap_supported(p, pooled)) v = V_TAP;
+    }
+    if (v == V_TAP) rc = launch_tap(p, pooled, x, w, y, s);
+    // no applicable tile plan: the general kernel runs
+    if (rc == SCONV_EUNSUPPORTED) rc = launch_rows(p, pooled, x, w, y, s);
+    return rc;
 }
 
 }  // namespace sconv
@@ -123,12 +141,7 @@ extern "C" int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const
     Problem p;
     int rc = fill_problem(desc, false, &p);
     if (rc) return rc;
-    hipStream_t s = (hipStream_t)hip_stream;
-    if (choose(p, false) == V_TAP) {
-        rc = launch_tap(p, false, x_dev, w_dev, y_dev, s);
-        if (rc != SCONV_EUNSUPPORTED) return rc;   // no applicable tile plan: the general kernel runs
-    }
-    return launch_rows(p, false, x_dev, w_dev, y_dev, s);
+    return run(choose(p, false), p, false, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
 extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
@@ -139,19 +152,19 @@ extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, 
     int rc = fill_problem(desc, true, &p);
     if (rc) return rc;
     if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
-    hipStream_t s = (hipStream_t)hip_stream;
-    if (choose(p, true) == V_TAP) {
-        rc = launch_tap(p, true, x_dev, w_dev, y_dev, s);
-        if (rc != SCONV_EUNSUPPORTED) return rc;
-    }
-    return launch_rows(p, true, x_dev, w_dev, y_dev, s);
+    return run(choose(p, true), p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
 extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
 {
     Problem p;
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
-    return choose(p, pooled != 0) == V_TAP ? "tap3x3" : "rows";
+    switch (choose(p, pooled != 0)) {
+    case V_PW: return "quad1x1";
+    case V_QUAD: return "quad3x3";
+    case V_TAP: return "tap3x3";
+    default: return "rows";
+    }
 }
 
 extern "C" const char* sconv_strerror(int code)

@@ -37,6 +37,16 @@ bool tap_supported(const Problem& p, bool pooled);
 int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t stream);
 
+// Matrix-core variant of the same kernel (3x3 / stride 1 / pad 1): four inputs per instruction.
+bool quad_supported(const Problem& p, bool pooled);
+int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+                hipStream_t stream);
+
+// Matrix-core kernel for 1x1 / stride 1 / pad 0 convolutions (optional 2x2 / stride 2 pooling).
+bool pw_supported(const Problem& p, bool pooled);
+int launch_pointwise(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+                     hipStream_t stream);
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? SCONV_OK : SCONV_ELAUNCH;

@@ -1,0 +1,478 @@
+// Matrix-core variant of the element-stationary kernel for 3x3 / stride 1 / pad 1 convolutions,
+// with the optional 2x2 / stride 2 max-pooling epilogue.
+//
+// Same arithmetic and the same bookkeeping as the vector kernel (lanes hold output channels, the
+// filters of one input channel stay in registers while that channel's input tile is processed,
+// ballot(x != 0) is the compaction), but the products are issued four input positions at a time
+// on the matrix pipe: v_mfma_f32_4x4x1 computes 16 independent 4x4 outer products
+// D[b][i][j] += A[b][i] * B[b][j].  Here j (with the block number b) is the lane's filter, B is
+// the lane's filter value for one tap, and A - broadcast from one 4-lane block of the input
+// register to all blocks - holds four horizontally adjacent input elements, so one instruction
+// adds tap (r, s) of four adjacent inputs to the four adjacent outputs of an accumulator quad
+// for 64 filters: 256 multiply-adds in the time the vector pipe needs for 128.  It is full fp32
+// arithmetic.  Zero skipping works on the six input elements that feed one accumulator quad from
+// one input row (four outputs times three tap columns): when their six mask bits are all clear,
+// one scalar test replaces up to nine matrix instructions per filter register (probability z^6
+// for i.i.d. zero ratio z); finer tests cost more issue slots than the instructions they save.
+//
+// Input tile layout: rows of RP lanes (RP = 16 or 32, TW + 2 of them used); the three tap
+// columns s = 0, 1, 2 need the register shifted by s lanes so that the four wanted elements sit
+// on a 4-lane block boundary; the shifted copies come from DPP wavefront shifts.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <utility>
+
+#include "sconv_internal.h"
+
+namespace sconv {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int KPL_, int TH_, int RP_, int NQ_, int TW_, bool POOL_>
+struct Geom {
+    static constexpr int KPL = KPL_;            // filters per lane
+    static constexpr int TH = TH_;              // output rows of the tile
+    static constexpr int RP = RP_;              // lanes per input row
+    static constexpr int NQ = NQ_;              // accumulator quads per output row
+    static constexpr int TW = TW_;              // valid output columns (<= 4*NQ, TW + 2 <= RP)
+    static constexpr bool POOL = POOL_;
+    static constexpr int IH = TH + 2;           // input rows oh0 - 1 .. oh0 + TH
+    static constexpr int NPOS = IH * RP;
+    static constexpr int NX = (NPOS + 63) / 64;  // input registers per channel
+    static constexpr int ACC = TH * NQ * 4;      // accumulator floats per filter
+    static constexpr int KB = 64 * KPL;          // filters per workgroup
+    static constexpr int KBP = KB + 1;           // LDS row stride (odd: conflict-free transposed writes)
+    static constexpr int CCH = 16 / KPL;         // channels per staged chunk
+    static constexpr int ROWS = CCH * 9;         // LDS rows per buffer
+    static constexpr int BUF = ROWS * KBP;       // floats per buffer
+    static constexpr int MAXW = (KPL * ACC + 9 * KPL + 3 * NX + 26 > 128) ? 8 : 16;
+    static_assert(64 % RP == 0 && TW + 2 <= RP && TW <= 4 * NQ, "tile layout");
+};
+
+struct TapCfg {
+    int NT, NCS;        // wavefronts per workgroup = NT spatial tiles x NCS channel slices
+    int CPW;            // channels per wavefront per chunk = CCH / NCS
+    int tiles_x, tiles_y, ntiles;
+};
+
+// One accumulator quad's worth of input: row IHI of the tile, output quad CQ.  Its three tap
+// columns read lanes b0 .. b0 + 5 of input register Q (b0 on a block boundary); in the copy
+// shifted by s lanes the four elements of tap column s are block number b0 / 4.  One scalar test
+// of those six mask bits guards the up to nine matrix instructions (three tap columns times the
+// tap rows whose output row lies in the tile) of each of the lane's filters.
+template <class G, int IHI, int CQ>
+__device__ __forceinline__ void quad_group(const unsigned (&mask)[2 * G::NX],
+                                           const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
+                                           const float (&wr)[G::KPL][9])
+{
+    constexpr int P0 = IHI * G::RP + CQ * 4;     // lane position of the block in the tile
+    constexpr int Q = P0 / 64, B0 = P0 % 64;
+    constexpr unsigned long long bits = (B0 + 5 < 64) ? (0x3Full << B0) : ((~0ull) << B0);
+    constexpr unsigned lo = (unsigned)bits, hi = (unsigned)(bits >> 32);
+    unsigned hit = 0;
+    if (lo) hit |= mask[2 * Q] & lo;
+    if (hi) hit |= mask[2 * Q + 1] & hi;
+    if (hit) {
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                // input row oh0 - 1 + IHI feeds output row oh0 + IHI - r through tap row r
+                const int orow = IHI - r;
+                if (orow < 0 || orow >= G::TH) continue;
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+                    acc[i][orow * G::NQ + CQ] = __builtin_amdgcn_mfma_f32_4x4x1f32(
+                        xs[s][Q], wr[i][r * 3 + s], acc[i][orow * G::NQ + CQ], 4, B0 / 4, 0);
+            }
+        }
+    }
+}
+
+template <class G, int IHI, int... CQs>
+__device__ __forceinline__ void quad_row(std::integer_sequence<int, CQs...>,
+                                         const unsigned (&mask)[2 * G::NX],
+                                         const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
+                                         const float (&wr)[G::KPL][9])
+{
+    (quad_group<G, IHI, CQs>(mask, xs, acc, wr), ...);
+}
+
+template <class G, int... IHIs>
+__device__ __forceinline__ void all_quads(std::integer_sequence<int, IHIs...>,
+                                          const unsigned (&mask)[2 * G::NX],
+                                          const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
+                                          const float (&wr)[G::KPL][9])
+{
+    (quad_row<G, IHIs>(std::make_integer_sequence<int, G::NQ>{}, mask, xs, acc, wr), ...);
+}
+
+// x[l] <- x[l + 1] over the whole wavefront (lane 63 gets 0)
+__device__ __forceinline__ float wave_shl1(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false));
+}
+
+template <class G, int NWV>
+__global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, const float* __restrict__ x,
+                                                   const float* __restrict__ w, float* __restrict__ y)
+{
+    extern __shared__ __align__(16) float lds[];  // two filter buffers; reused for the reduction
+
+    const int tid = threadIdx.x;
+    constexpr int nthr = NWV * 64;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ts = wave % cfg.NT;                  // spatial tile slot
+    const int cs = wave / cfg.NT;                  // channel slice
+    const int n = blockIdx.z / p.G;
+    const int g = blockIdx.z - n * p.G;
+    const int kb0 = blockIdx.y * G::KB;            // first filter of the block inside the group
+    const int tile = blockIdx.x * cfg.NT + ts;
+    const bool tile_ok = tile < cfg.ntiles;
+    const int ty = tile / cfg.tiles_x, tx = tile - ty * cfg.tiles_x;
+    const int oh0 = ty * G::TH, ow0 = tx * G::TW;
+    const int HWp = p.H * p.W;
+
+    // this lane's input positions (one per input register)
+    unsigned xoff[G::NX];   // offset inside a channel plane; 0 (a valid address) when unused
+    bool xok[G::NX];
+#pragma unroll
+    for (int q = 0; q < G::NX; ++q) {
+        const int P = q * 64 + lane;
+        const int ih = P / G::RP, ic = P - ih * G::RP;
+        const int xr = oh0 - 1 + ih, xc = ow0 - 1 + ic;
+        xok[q] = tile_ok && ih < G::IH && ic < G::TW + 2 && xr >= 0 && xr < p.H && xc >= 0 && xc < p.W;
+        xoff[q] = xok[q] ? (unsigned)(xr * p.W + xc) : 0u;
+    }
+    const float* xg = x + ((size_t)n * p.C + (size_t)g * p.Cg) * HWp;
+    const float* wg = w + ((size_t)g * p.Kg + kb0) * p.L;  // filter k of the block: wg + k*L
+    const int kvalid = min(G::KB, p.Kg - kb0);
+
+    v4f acc[G::KPL][G::TH * G::NQ];
+#pragma unroll
+    for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+        for (int a = 0; a < G::TH * G::NQ; ++a) acc[i][a] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // Filter staging.  A chunk is KB filters x ROWS = CCH*9 consecutive floats of each filter.
+    // TPF threads share one filter, each moving EPT consecutive floats, so both the global offset
+    // and the LDS index are one per-thread base plus compile-time steps.  A filter past the
+    // group's last one (ragged last block) re-reads the last valid filter: its lanes compute
+    // values that are never stored, and no address leaves the tensor.
+    constexpr int TPF = nthr / G::KB;
+    constexpr int EPT = G::ROWS / TPF;             // 9 (16 wavefronts) or 18 (8 wavefronts)
+    static_assert(TPF * G::KB == nthr && EPT * TPF == G::ROWS, "staging must divide evenly");
+    float stage[EPT];
+    const int sk = tid / TPF, ssub = tid - sk * TPF;
+    const unsigned sgoff = (unsigned)(min(sk, kvalid - 1) * p.L + ssub * EPT);
+    const int sloff = ssub * EPT * G::KBP + sk;
+    auto fetch_chunk = [&](int c0) {
+        const float* base = wg + c0 * 9 + sgoff;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) stage[i] = base[i];
+    };
+    auto store_chunk = [&](float* buf) {
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) buf[sloff + i * G::KBP] = stage[i];
+    };
+    auto load_x = [&](int c, float (&dst)[G::NX]) {
+        const float* base = xg + (size_t)min(c, p.Cg - 1) * HWp;   // uniform; past-the-end prefetch
+#pragma unroll                                                    // re-reads the last channel
+        for (int q = 0; q < G::NX; ++q) {
+            const float t = base[xoff[q]];
+            dst[q] = xok[q] ? t : 0.0f;
+        }
+    };
+
+    const int nchunks = (p.Cg + G::CCH - 1) / G::CCH;
+    fetch_chunk(0);
+    float xn[G::NX];
+    load_x(cs * cfg.CPW, xn);
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        float* buf = lds + (ch & 1) * G::BUF;
+        store_chunk(buf);
+        __syncthreads();
+        if (ch + 1 < nchunks) fetch_chunk((ch + 1) * G::CCH);
+
+        const int cbase = ch * G::CCH + cs * cfg.CPW;   // this wavefront's channels of the chunk
+        for (int cc = 0; cc < cfg.CPW; ++cc) {
+            float xs[3][G::NX];
+            unsigned mask[2 * G::NX];
+#pragma unroll
+            for (int q = 0; q < G::NX; ++q) {
+                xs[0][q] = xn[q];
+                const unsigned long long m = __ballot(xs[0][q] != 0.0f);
+                mask[2 * q] = (unsigned)m;
+                mask[2 * q + 1] = (unsigned)(m >> 32);
+            }
+            // next channel of this wavefront (next chunk's first one after the last of this chunk)
+            const int cnext = (cc + 1 < cfg.CPW) ? cbase + cc + 1 : cbase + G::CCH;
+            load_x(cnext, xn);
+
+            unsigned any = 0;
+#pragma unroll
+            for (int q = 0; q < 2 * G::NX; ++q) any |= mask[q];
+            if (any) {
+#pragma unroll
+                for (int q = 0; q < G::NX; ++q) {
+                    xs[1][q] = wave_shl1(xs[0][q]);
+                    xs[2][q] = wave_shl1(xs[1][q]);
+                }
+                float wr[G::KPL][9];
+                const float* wl = buf + (cs * cfg.CPW + cc) * 9 * G::KBP + lane;
+#pragma unroll
+                for (int j = 0; j < 9; ++j)
+#pragma unroll
+                    for (int i = 0; i < G::KPL; ++i) wr[i][j] = wl[j * G::KBP + 64 * i];
+                all_quads<G>(std::make_integer_sequence<int, G::IH>{}, mask, xs, acc, wr);
+            }
+        }
+    }
+
+    // reduce the channel slices: slice r hands its partial sums to slice 0 through LDS
+    if (cfg.NCS > 1) {
+        float* red = lds;  // [NT][KPL*ACC][64]
+        for (int r = 1; r < cfg.NCS; ++r) {
+            __syncthreads();
+            if (cs == r) {
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+                    for (int a = 0; a < G::ACC; ++a)
+                        red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane] = acc[i][a / 4][a % 4];
+            }
+            __syncthreads();
+            if (cs == 0) {
+#pragma unroll
+                for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+                    for (int a = 0; a < G::ACC; ++a)
+                        acc[i][a / 4][a % 4] += red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane];
+            }
+        }
+    }
+    if (cs != 0 || !tile_ok) return;
+
+    // epilogue: lane owns filters kb0 + lane + 64*i; accumulator (row, quad, e) = output column 4*quad + e
+    if (!G::POOL) {
+        const int plane = p.OH * p.OW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            if (k >= kvalid) continue;
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+#pragma unroll
+            for (int a = 0; a < G::ACC; ++a) {
+                const int orow = a / (4 * G::NQ), ocol = a % (4 * G::NQ);
+                if (ocol >= G::TW) continue;
+                const int oh = oh0 + orow, ow = ow0 + ocol;
+                if (oh < p.OH && ow < p.OW) {
+                    float v = acc[i][a / 4][a % 4];
+                    if (p.relu) v = fmaxf(v, 0.0f);
+                    yk[oh * p.OW + ow] = v;
+                }
+            }
+        }
+    } else {
+        // 2x2 / stride 2 windows never straddle tiles (TH, TW even, tile origins even)
+        const int plane = p.PH * p.PW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            if (k >= kvalid) continue;
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+#pragma unroll
+            for (int a = 0; a < (G::TH / 2) * (G::TW / 2); ++a) {
+                const int pr = a / (G::TW / 2), pc = a % (G::TW / 2);
+                const int phh = oh0 / 2 + pr, pww = ow0 / 2 + pc;
+                if (phh < p.PH && pww < p.PW) {
+                    const int q0 = (2 * pr) * G::NQ + (2 * pc) / 4, e = (2 * pc) % 4;   // e is 0 or 2
+                    float m = fmaxf(fmaxf(acc[i][q0][e], acc[i][q0][e + 1]),
+                                    fmaxf(acc[i][q0 + G::NQ][e], acc[i][q0 + G::NQ][e + 1]));
+                    yk[phh * p.PW + pww] = fmaxf(m, 0.0f);
+                }
+            }
+        }
+    }
+}
+
+// Workgroups of one kernel instantiation that fit on a compute unit (asked once).
+template <class G, int NWV>
+int occupancy(size_t lds_bytes)
+{
+    static int occ = 0;
+    if (occ == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, quad_kernel<G, NWV>, NWV * 64, lds_bytes) !=
+                hipSuccess || nb < 1)
+            nb = 1;
+        occ = nb;
+    }
+    return occ;
+}
+
+template <class G, int NWV>
+int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
+               const float* w, float* y, hipStream_t stream)
+{
+    auto kern = quad_kernel<G, NWV>;
+    static bool opted = false;  // dynamic LDS above 48 KiB is opted into once per kernel
+    if (!opted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return SCONV_ELAUNCH;
+        opted = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, x, w, y);
+    return launch_status();
+}
+
+// Plan of one launch: the split of a geometry's work over wavefronts and its modelled cost.
+struct Plan {
+    double cost = -1.0;   // model clocks; negative = not applicable
+    TapCfg cfg;
+    int nwv = 0;
+    int kblocks = 0;
+};
+
+// Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
+// each walking Cg channels.  Two knobs: NCS wavefronts split the channels of a tile (more, shorter
+// wavefronts: fills the machine at small batch, evens out the last round of workgroups), and NT
+// tiles share a workgroup (fewer workgroups re-reading the same filters from L2).  Every
+// candidate is priced with a simple model - rounds of workgroups over 256 compute units, SIMDs
+// saturating at about four resident wavefronts, one scalar test per input position and channel,
+// filter staging at 64 bytes per clock per compute unit - and the cheapest is launched.  The
+// density of the input is not known on the host; the model assumes 30 % nonzeros.
+template <class G>
+Plan plan_geom(const Problem& p)
+{
+    Plan best;
+    TapCfg cfg;
+    cfg.tiles_y = (p.OH + G::TH - 1) / G::TH;
+    cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
+    cfg.ntiles = cfg.tiles_x * cfg.tiles_y;
+    const int kblocks = (p.Kg + G::KB - 1) / G::KB;
+    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
+    // clocks of one wavefront on one channel: a test per input row and quad, and for the groups
+    // with a nonzero (88 % at 30 % density) their share of the 9 * TH * NQ * KPL matrix
+    // instructions at about 9 clocks each
+    const double groups = (double)G::IH * G::NQ;
+    const double t_channel = 200.0 + 9.0 * groups + 0.88 * 9.0 * G::TH * G::NQ * G::KPL * 9.2;
+    const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
+
+    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_QUAD_SPLIT="nwv,ncs"
+    if (const char* pin = getenv("SCONV_QUAD_SPLIT")) {
+        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
+    }
+    for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
+        const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
+        for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
+            const int nt = nwv / ncs;
+            if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
+            if (ncs > 1 && nt * red_per_tile > lds_bytes) continue;
+            if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
+            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            const long long slots = 256LL * occ;
+            const long long rounds = (wgs + slots - 1) / slots;
+            const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
+            double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
+            if (r < 4.0) r = 4.0;
+            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
+                                (ncs - 1) * 2000.0;                              // reduction steps
+            if (best.cost < 0.0 || cost < best.cost) {
+                best.cost = cost;
+                best.cfg = cfg;
+                best.cfg.NT = nt;
+                best.cfg.NCS = ncs;
+                best.cfg.CPW = G::CCH / ncs;
+                best.nwv = nwv;
+                best.kblocks = kblocks;
+            }
+        }
+    }
+    return best;
+}
+
+template <class G>
+int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+                hipStream_t stream)
+{
+    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
+    const unsigned gz = (unsigned)(p.N * p.G);
+    if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, gz);
+    if constexpr (G::MAXW == 16) {
+        if (pl.nwv == 16) return launch_nwv<G, 16>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+    }
+    return launch_nwv<G, 8>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+}
+
+// Geometries.  Maps wider than 14: rows of 32 lanes, 28 output columns (7 quads), 2 output rows.
+// Maps up to 14 wide: rows of 16 lanes, 14 output columns in 4 quads (the last two columns of
+// the fourth quad are computed from the neighbouring row's lanes and never stored), 2 output rows.
+using Q32_1 = Geom<1, 2, 32, 7, 28, false>;
+using Q32_2 = Geom<2, 1, 32, 7, 28, false>;
+using Q16_2 = Geom<2, 2, 16, 4, 14, false>;
+using QP32_1 = Geom<1, 2, 32, 7, 28, true>;
+using QP16_2 = Geom<2, 2, 16, 4, 14, true>;
+
+bool shape_ok(const Problem& p, bool pooled)
+{
+    if (p.R != 3 || p.S != 3 || p.pad != 1 || p.stride != 1) return false;
+    if (p.Cg % 16) return false;                      // whole staged chunks of channels only
+    if (pooled && (p.ph != 2 || p.pw != 2 || p.ps != 2)) return false;
+    return true;
+}
+
+struct Candidate {
+    const char* name;
+    Plan (*plan)(const Problem&);
+    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    bool pooled;
+    int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
+    bool wide;            // for maps wider than 14
+};
+
+const Candidate kCandidates[] = {
+    {"q32k1", plan_geom<Q32_1>, launch_plan<Q32_1>, false, 1, true},
+    {"q32k2", plan_geom<Q32_2>, launch_plan<Q32_2>, false, 2, true},
+    {"q16k2", plan_geom<Q16_2>, launch_plan<Q16_2>, false, 2, false},
+    {"qp32k1", plan_geom<QP32_1>, launch_plan<QP32_1>, true, 1, true},
+    {"qp16k2", plan_geom<QP16_2>, launch_plan<QP16_2>, true, 2, false},
+};
+
+}  // namespace
+
+bool quad_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
+
+int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+                hipStream_t stream)
+{
+    if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
+    const char* pin = getenv("SCONV_QUAD_GEOM");   // tuning aid: candidate name
+    const Candidate* best = nullptr;
+    Plan best_plan;
+    for (const Candidate& c : kCandidates) {
+        if (c.pooled != pooled) continue;
+        if (p.Kg <= 64 * (c.kpl - 1)) continue;
+        if (pin ? strcmp(pin, c.name) != 0 : (c.wide != (p.W > 14))) continue;
+        const Plan pl = c.plan(p);
+        if (pl.cost < 0.0) continue;
+        if (!best || pl.cost < best_plan.cost) {
+            best = &c;
+            best_plan = pl;
+        }
+    }
+    if (!best) return SCONV_EUNSUPPORTED;
+    return best->launch(best_plan, p, x, w, y, stream);
+}
+
+}  // namespace sconv

@@ -35,6 +35,12 @@ SMALL = [
     (2, 64, 14, 14, 64, 3, 3, 1, 1, 2, (2, 2, 2)),      # grouped
     (1, 256, 9, 12, 256, 3, 3, 1, 1, 1, (2, 2, 2)),     # many chunks, channel slices
     (9, 16, 6, 5, 130, 3, 3, 1, 1, 1, (2, 2, 2)),       # maps smaller than a tile
+    # 1x1 / stride 1 / pad 0 with whole 64-channel chunks: the pointwise matrix-core kernel
+    (2, 64, 9, 11, 70, 1, 1, 1, 0, 1, (2, 2, 2)),       # ragged filter block, odd plane size
+    (1, 128, 28, 28, 128, 1, 1, 1, 0, 1, (2, 2, 2)),
+    (3, 256, 7, 7, 64, 1, 1, 1, 0, 2, (2, 2, 2)),       # grouped, plane smaller than a tile
+    (1, 192, 30, 58, 40, 1, 1, 1, 0, 1, (2, 2, 2)),     # pooled tiles: ragged columns (58 = 2*28 + 2)
+    (2, 64, 5, 8, 64, 1, 1, 1, 0, 1, (2, 2, 2)),        # odd height: last row unpooled
     # 3x3 / stride 2 / pad 1: the stride-2 tiles of the same kernel
     (2, 32, 19, 23, 70, 3, 3, 2, 1, 1, (2, 2, 2)),      # odd sizes, one filter per lane
     (1, 48, 28, 28, 160, 3, 3, 2, 1, 1, (2, 2, 2)),     # two filters per lane, ragged block
