@@ -385,7 +385,7 @@ Plan plan_geom(const Problem& p)
             double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
             if (r < 4.0) r = 4.0;
             const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
-                                (ncs - 1) * 2000.0;                              // reduction steps
+                                (ncs - 1) * 8000.0;   // reduction steps and barrier-bound short slices
             if (best.cost < 0.0 || cost < best.cost) {
                 best.cost = cost;
                 best.cfg = cfg;
