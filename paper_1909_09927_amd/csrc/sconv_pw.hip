@@ -9,17 +9,22 @@
 // ballot(x != 0) is the compaction.  The products are issued four positions at a time on the
 // matrix pipe: v_mfma_f32_4x4x1 with the A operand broadcast from 4-lane block b of the input
 // register adds x[c][p0+4b .. p0+4b+3] * w[k][c] to accumulator quad b for all 64 lanes - full
-// fp32 arithmetic, 256 multiply-adds per instruction.  Zero skipping works on groups of eight
-// positions: when the eight mask bits of a group are clear, one scalar test replaces its two
-// matrix instructions (a finer test costs more issue slots than it saves; ReLU maps with dead
-// channels or empty regions skip whole channels at a time).
+// fp32 arithmetic, 256 multiply-adds per instruction.  Zero skipping works on a whole channel of
+// the tile: when none of its 64 elements is nonzero (dead channels, empty regions of a ReLU map)
+// one scalar test replaces its sixteen matrix instructions.  Finer tests were measured to cost
+// more than they save on this machine: scalar tests, branches and matrix instructions of all the
+// wavefronts of a SIMD share its issue slots (about 4.5 clocks per instruction, 9 per matrix
+// instruction), so a test of eight positions (three instructions) only pays when more than 70 %
+// of such groups are empty, which i.i.d. zeros reach above a zero ratio of 0.96.
 //
 // A workgroup is NT position tiles x NCS channel slices sharing one LDS-staged (double-buffered)
 // filter chunk of 64 channels x 64 filters; slices reduce through LDS at the end.  Activations
-// are prefetched eight channels ahead.
+// are prefetched sixteen channels ahead.
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+
+#include <utility>
 
 #include "sconv_internal.h"
 
@@ -33,7 +38,7 @@ constexpr int KB = 64;            // filters per workgroup (one per lane)
 constexpr int KBP = KB + 1;       // LDS row stride (odd: conflict-free transposed writes)
 constexpr int CCH = 64;           // channels per staged chunk
 constexpr int BUF = CCH * KBP;    // floats per LDS buffer
-constexpr int XB = 8;             // channels per activation batch
+constexpr int XB = 16;            // activation registers: a channel is loaded XB channels ahead
 
 struct PwCfg {
     int NT, NCS;        // wavefronts per workgroup = NT position tiles x NCS channel slices
@@ -49,18 +54,12 @@ __host__ __device__ constexpr bool block_used(int b)
     return POOL ? (b % 8) != 7 : true;
 }
 
-// One group of eight positions (blocks 2*GQ and 2*GQ + 1) of one channel: a scalar test of its
-// eight mask bits guards its two matrix instructions.
-template <bool POOL, int GQ>
-__device__ __forceinline__ void group8(unsigned mlo, unsigned mhi, float xv, float wv, v4f (&acc)[16])
+// The sixteen matrix instructions of one channel (one per 4-lane block of the input register).
+template <bool POOL, int... Bs>
+__device__ __forceinline__ void all_blocks(std::integer_sequence<int, Bs...>, float xv, float wv, v4f (&acc)[16])
 {
-    const unsigned half = GQ < 4 ? mlo : mhi;
-    if (half & (0xFFu << (8 * (GQ & 3)))) {
-        if constexpr (block_used<POOL>(2 * GQ))
-            acc[2 * GQ] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv, wv, acc[2 * GQ], 4, 2 * GQ, 0);
-        if constexpr (block_used<POOL>(2 * GQ + 1))
-            acc[2 * GQ + 1] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv, wv, acc[2 * GQ + 1], 4, 2 * GQ + 1, 0);
-    }
+    ((block_used<POOL>(Bs) ? (void)(acc[Bs] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv, wv, acc[Bs], 4, Bs, 0))
+                           : (void)0), ...);
 }
 
 template <bool POOL, int NWV>
@@ -124,21 +123,20 @@ __global__ __launch_bounds__(NWV * 64) void pw_kernel(Problem p, PwCfg cfg, cons
 #pragma unroll
         for (int i = 0; i < EPT; ++i) buf[sloff + i * KBP] = stage[i];
     };
-    // activations of XB consecutive channels starting at c (clamped: a prefetch past the end
-    // re-reads the last channels and is never used)
-    auto load_x = [&](int c, float (&dst)[XB]) {
-        const float* base = xg + (size_t)min(c, p.Cg - XB) * HWp;
-#pragma unroll
-        for (int j = 0; j < XB; ++j) {
-            const float t = base[(size_t)j * HWp + xoff];
-            dst[j] = xok ? t : 0.0f;
-        }
-    };
+    // activations of one channel (clamped: a prefetch past the end re-reads the last channel and is
+    // never used)
+    // (the value of a lane without a position is replaced by zero where it is consumed, so that
+    // the wait for the load sits there and not behind the load)
+    auto load_x = [&](int c) -> float { return xg[(size_t)min(c, p.Cg - 1) * HWp + xoff]; };
 
     const int nchunks = p.Cg / CCH;                // Cg is a multiple of CCH
     fetch_chunk(0);
-    float xn[XB];
-    load_x(cs * cfg.CPW, xn);
+    // Rotating activation registers: slot j holds channel (first + j) of the current group of XB
+    // channels; as soon as its matrix instructions are issued it is reloaded with the channel XB
+    // further on, so XB loads of 256 bytes stay in flight per wavefront.
+    float xb[XB];
+#pragma unroll
+    for (int j = 0; j < XB; ++j) xb[j] = load_x(cs * cfg.CPW + j);
 
     for (int ch = 0; ch < nchunks; ++ch) {
         float* buf = lds + (ch & 1) * BUF;
@@ -148,11 +146,8 @@ __global__ __launch_bounds__(NWV * 64) void pw_kernel(Problem p, PwCfg cfg, cons
 
         const int cbase = ch * CCH + cs * cfg.CPW;      // this wavefront's channels of the chunk
         for (int cc = 0; cc < cfg.CPW; cc += XB) {
-            float xv[XB];
-#pragma unroll
-            for (int j = 0; j < XB; ++j) xv[j] = xn[j];
-            // next batch of this wavefront (the next chunk's first one after the last of this chunk)
-            load_x((cc + XB < cfg.CPW) ? cbase + cc + XB : cbase + CCH, xn);
+            // the group after this one: in this chunk, or the slice's first group of the next chunk
+            const int cnext = (cc + XB < cfg.CPW) ? cbase + cc + XB : cbase + CCH;
             float wv[XB];
             const float* wl = buf + (cs * cfg.CPW + cc) * KBP + lane;
 #pragma unroll
@@ -160,16 +155,10 @@ __global__ __launch_bounds__(NWV * 64) void pw_kernel(Problem p, PwCfg cfg, cons
 
 #pragma unroll
             for (int j = 0; j < XB; ++j) {
-                const unsigned long long m = __ballot(xv[j] != 0.0f);
-                const unsigned mlo = (unsigned)m, mhi = (unsigned)(m >> 32);
-                group8<POOL, 0>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 1>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 2>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 3>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 4>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 5>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 6>(mlo, mhi, xv[j], wv[j], acc);
-                group8<POOL, 7>(mlo, mhi, xv[j], wv[j], acc);
+                const float xv = xok ? xb[j] : 0.0f;
+                // one test per channel and tile: a channel without a nonzero in the tile is skipped
+                if (__ballot(xv != 0.0f)) all_blocks<POOL>(std::make_integer_sequence<int, 16>{}, xv, wv[j], acc);
+                xb[j] = load_x(cnext + j);
             }
         }
     }

@@ -183,6 +183,26 @@ def test_benchmark_layers_full_batch_sampled(device, ci, li, N):
     assert (err <= TOL * scale).all(), f"worst ratio {np.max(err / np.maximum(scale, 1e-300)):.3e}"
 
 
+@pytest.mark.parametrize("variant", ["rows", "tap", None])
+@pytest.mark.parametrize("shp", [
+    (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),
+    (2, 48, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)),
+    (1, 128, 28, 28, 128, 1, 1, 1, 0, 1, (2, 2, 2)),
+    (2, 64, 30, 30, 96, 3, 3, 2, 1, 1, (2, 2, 2)),
+])
+def test_every_kernel_variant_on_the_same_input(device, monkeypatch, shp, variant):
+    """The dispatch can be pinned; every variant that covers a shape must meet the same bars."""
+    if variant is None:
+        monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    else:
+        monkeypatch.setenv("SCONV_VARIANT", variant)
+    layer, x, w = _mk(110, shp)
+    check_forward(layer, x, w, relu=True)
+    check_pool_forward(layer, x, w)
+    layer, x, w = _mk(111, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)

@@ -92,8 +92,12 @@ def test_strerror_and_variant_name():
     assert sconv.strerror(0) == "success"
     assert "invalid" in sconv.strerror(sconv.SCONV_EINVAL)
     assert sconv.strerror(-99).startswith("unknown")
-    d = sconv.make_desc(1, 256, 56, 56, 64, 1, 1)
-    assert sconv.sconv_variant_name(d) in ("rows", "tap3x3")
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 256, 56, 56, 64, 1, 1)) == "quad1x1"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 250, 56, 56, 64, 1, 1)) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 2, 1)) == "tap3x3"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 5, 5, 1, 2)) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1, pool=(3, 3, 2)), True) == "rows"
     assert sconv.sconv_variant_name(sconv.Desc()) is None
 
 
