@@ -81,10 +81,11 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * sparse row-times-filter product of Algorithm 2, optional ReLU, one store):
  *   y[n][k][oh][ow] = sum over the window's nonzeros of value * w[k][column],
  * the window of group g = k / (K/G).  Which zeros are skipped depends on the kernel variant the
- * shape selects (sconv_variant_name): "rows" and "tap3x3" skip every zero element; "quad3x3" and
- * "quad1x1" issue products four (eight) adjacent elements at a time on the matrix pipe and skip a
- * group only when all of its elements are zero, so a zero inside a group that also holds a nonzero
- * is multiplied (0 * w adds nothing for finite w; with Inf or NaN filters the variants can differ).
+ * shape selects (sconv_variant_name): "rows" and "tap3x3" skip every zero element; "quad3x3",
+ * "quad1x1" and "wide3x3" issue products of several adjacent elements at a time on the matrix pipe
+ * (groups of 6, 8 and 16 elements) and skip a group only when all of its elements are zero, so a
+ * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
+ * with Inf or NaN filters the variants can differ).
  *   x_dev device, in : [N][C][H][W]
  *   w_dev device, in : [K][C/G][R][S]
  *   y_dev device, out: [N][K][OH][OW]
@@ -107,9 +108,11 @@ int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float
  * Name of the kernel variant the two forward calls would pick for this descriptor (a static
  * string, for benchmark records and profiles).  pooled != 0 asks about sconv_pool_forward.
  * Variants: "quad1x1" (1x1 / stride 1 / pad 0, channels per group a multiple of 64), "quad3x3"
- * (3x3 / stride 1 / pad 1, channels per group a multiple of 16), "tap3x3" (3x3 / pad 1, stride 1
- * or 2, same channel condition), "rows" (everything else).  The environment variable SCONV_VARIANT
- * ("rows", "tap" or unset) pins the choice for profiling.
+ * (3x3 / stride 1 / pad 1, channels per group a multiple of 16), "wide3x3" (3x3 of any stride and
+ * padding, channels per group a multiple of 8; also preferred for maps up to 14 wide with 128 or
+ * more filters per group), "tap3x3" (3x3 / pad 1, stride 1 or 2, channels a multiple of 16; runs
+ * only when pinned or when the others decline), "rows" (everything else).  The environment
+ * variable SCONV_VARIANT ("rows", "tap", "quad", "wide" or unset) pins the choice for profiling.
  * Returns NULL for an invalid descriptor.  Host only.
  */
 const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);

@@ -55,16 +55,30 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     return SCONV_OK;
 }
 
-enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW };
+enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW, V_WIDE };
 
 static Variant choose(const Problem& p, bool pooled)
 {
     const char* pin = getenv("SCONV_VARIANT");
     if (pin && !strcmp(pin, "rows")) return V_ROWS;
     if (pin && !strcmp(pin, "tap")) return tap_supported(p, pooled) ? V_TAP : V_ROWS;
+    if (pin && !strcmp(pin, "wide")) return wide_supported(p, pooled) ? V_WIDE : V_ROWS;
+    if (pin && !strcmp(pin, "quad")) return quad_supported(p, pooled) ? V_QUAD : V_ROWS;
     if (pw_supported(p, pooled)) return V_PW;
-    if (quad_supported(p, pooled)) return V_QUAD;
-    return tap_supported(p, pooled) ? V_TAP : V_ROWS;
+    // The 16-row granule needs many tile-wavefronts (64 window rows x 64 filters each) to fill the
+    // chip: it splits the channels of a tile four ways at most.
+    const long long rows = pooled ? (long long)p.N * p.PH * p.PW * 4 : (long long)p.N * p.OH * p.OW;
+    const bool wide_fills = wide_supported(p, pooled) &&
+                            ((rows + 63) / 64) * ((p.Kg + 63) / 64) * p.G >= 128;
+    if (quad_supported(p, pooled)) {
+        // Small maps with many filters: the 16-row granule has no tile-geometry waste there and
+        // measures faster; everywhere else the 4-row granule skips more and wins.
+        if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
+        return V_QUAD;
+    }
+    if (tap_supported(p, pooled)) return wide_fills ? V_WIDE : V_TAP;   // 3x3 / stride 2 / pad 1
+    if (wide_supported(p, pooled)) return V_WIDE;     // 3x3 with another stride or padding
+    return V_ROWS;
 }
 
 static int run(Variant v, const Problem& p, bool pooled, const float* x, const float* w, float* y,
@@ -72,11 +86,15 @@ static int run(Variant v, const Problem& p, bool pooled, const float* x, const f
 {
     int rc = SCONV_EUNSUPPORTED;
     if (v == V_PW) rc = launch_pointwise(p, pooled, x, w, y, s);
+    if (v == V_WIDE) {
+        rc = launch_wide(p, pooled, x, w, y, s);
+        if (rc == SCONV_EUNSUPPORTED) v = quad_supported(p, pooled) ? V_QUAD : V_TAP;
+    }
     if (v == V_QUAD) {
         rc = launch_quad(p, pooled, x, w, y, s);
-        if (rc == SCONV_EUNSUPPORTED && tap_supported(p, pooled)) v = V_TAP;
+        if (rc == SCONV_EUNSUPPORTED) v = V_TAP;
     }
-    if (v == V_TAP) rc = launch_tap(p, pooled, x, w, y, s);
+    if (v == V_TAP && tap_supported(p, pooled)) rc = launch_tap(p, pooled, x, w, y, s);
     // no applicable tile plan: the general kernel runs
     if (rc == SCONV_EUNSUPPORTED) rc = launch_rows(p, pooled, x, w, y, s);
     return rc;
@@ -163,6 +181,7 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
     case V_PW: return "quad1x1";
     case V_QUAD: return "quad3x3";
     case V_TAP: return "tap3x3";
+    case V_WIDE: return "wide3x3";
     default: return "rows";
     }
 }

@@ -42,6 +42,11 @@ bool quad_supported(const Problem& p, bool pooled);
 int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream);
 
+// Wide-granule matrix-core kernel: 3x3, any stride and padding, 16 window rows per instruction.
+bool wide_supported(const Problem& p, bool pooled);
+int launch_wide(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+                hipStream_t stream);
+
 // Matrix-core kernel for 1x1 / stride 1 / pad 0 convolutions (optional 2x2 / stride 2 pooling).
 bool pw_supported(const Problem& p, bool pooled);
 int launch_pointwise(const Problem& p, bool pooled, const float* x, const float* w, float* y,

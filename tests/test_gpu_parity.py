@@ -183,7 +183,7 @@ def test_benchmark_layers_full_batch_sampled(device, ci, li, N):
     assert (err <= TOL * scale).all(), f"worst ratio {np.max(err / np.maximum(scale, 1e-300)):.3e}"
 
 
-@pytest.mark.parametrize("variant", ["rows", "tap", None])
+@pytest.mark.parametrize("variant", ["rows", "tap", "quad", "wide", None])
 @pytest.mark.parametrize("shp", [
     (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),
     (2, 48, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)),
@@ -201,6 +201,43 @@ def test_every_kernel_variant_on_the_same_input(device, monkeypatch, shp, varian
     check_pool_forward(layer, x, w)
     layer, x, w = _mk(111, shp, integer=True)
     check_forward(layer, x, w, relu=False, integer_exact=True)
+
+
+# 3x3 with whole 8-channel chunks, any stride and padding: the wide-granule matrix-core kernel
+WIDE = [
+    (2, 8, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),       # ragged filter block, rows cross images
+    (1, 16, 28, 28, 32, 3, 3, 1, 1, 1, (2, 2, 2)),      # half-empty filter block
+    (2, 24, 17, 30, 200, 3, 3, 1, 1, 1, (2, 2, 2)),     # two filters per lane, odd sizes
+    (3, 64, 7, 7, 128, 3, 3, 1, 1, 1, (2, 2, 2)),       # 49-result planes: scalar stores
+    (2, 64, 14, 14, 64, 3, 3, 1, 1, 2, (2, 2, 2)),      # grouped
+    (1, 256, 9, 12, 256, 3, 3, 1, 1, 1, (2, 2, 2)),     # many chunks, channel slices
+    (9, 16, 6, 5, 130, 3, 3, 1, 1, 1, (2, 2, 2)),       # several images per 64-row tile
+    (2, 32, 19, 23, 70, 3, 3, 2, 1, 1, (2, 2, 2)),      # stride 2
+    (1, 48, 28, 28, 160, 3, 3, 2, 1, 1, (2, 2, 2)),
+    (2, 16, 20, 17, 40, 3, 3, 1, 0, 1, (2, 2, 2)),      # no padding
+    (1, 16, 22, 22, 24, 3, 3, 3, 2, 1, (2, 2, 2)),      # stride 3, pad 2
+    (1, 16, 3, 3, 5, 3, 3, 1, 1, 1, None),              # a single tile, mostly empty
+]
+
+
+@pytest.mark.parametrize("shp", WIDE)
+def test_wide_variant(device, monkeypatch, shp):
+    monkeypatch.setenv("SCONV_VARIANT", "wide")
+    layer, x, w = _mk(112, shp)
+    d = sconv.desc_for(to_dev(x), to_dev(w), layer.stride, layer.pad, layer.groups, layer.pool, True)
+    assert sconv.sconv_variant_name(d, False) == "wide3x3"
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    if layer.pool:
+        assert sconv.sconv_variant_name(d, True) == "wide3x3"
+        check_pool_forward(layer, x, w)
+    layer, x, w = _mk(113, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w, integer_exact=True)
+    for z in (0.0, 0.97, 1.0):
+        layer, x, w = _mk(114, shp, z=z)
+        check_forward(layer, x, w, relu=False)
 
 
 def test_outputs_are_overwritten_not_accumulated(device):
