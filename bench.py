@@ -35,6 +35,13 @@ import workloads  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TF = 157.3  # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+FP32_MFMA_PEAK_TF = 157.3    # dense fp32 matrix instructions, published
+MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3")
+# HBM/fabric bytes per launch from the rocprofv3 counter runs (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB,
+# scaled by the copy calibration); keyed by (variant, layer, batch); the summaries are in profiles/.
+MEASURED_TRAFFIC = {
+    ("quad3x3", "vgg-256x56", 8): 145.8e6 + 26.0e6,      # profiles/quad3x3_vgg-256x56_n8.txt
+}
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
 CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
 
@@ -204,9 +211,16 @@ def run_headline(args) -> None:
                 "unit": "GB/s", "frac": round(wk["alg_bytes"] / t / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}
     else:
         ach = wk["nz_flops"] / t / 1e12
-        roof = {"bound": "alu", "achieved": round(ach, 2), "peak": FP32_VECTOR_PEAK_TF, "unit": "TFLOP/s",
-                "frac": round(ach / FP32_VECTOR_PEAK_TF, 4), "traffic": None,
-                "frac_of_unpacked_fp32_peak": round(ach / FP32_UNPACKED_PEAK_TF, 4)}
+        if r["variant"] in MFMA_VARIANTS:
+            # products go through the fp32 matrix pipe; algorithmic flops = nonzero multiply-adds
+            roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": FP32_MFMA_PEAK_TF, "unit": "TFLOP/s",
+                    "frac": round(ach / FP32_MFMA_PEAK_TF, 4), "traffic": None,
+                    "issued_dense_equiv_TFLOPs": round(wk["dense_flops"] / t / 1e12, 2)}
+        else:
+            roof = {"bound": "alu", "achieved": round(ach, 2), "peak": FP32_VECTOR_PEAK_TF, "unit": "TFLOP/s",
+                    "frac": round(ach / FP32_VECTOR_PEAK_TF, 4), "traffic": None,
+                    "frac_of_unpacked_fp32_peak": round(ach / FP32_UNPACKED_PEAK_TF, 4)}
+    roof["traffic"] = MEASURED_TRAFFIC.get((r["variant"], r["layer"], N))
     roof["kernel"] = f"{r['variant']} on {r['layer']} N={N}"
     roof["kernel_ms"] = r["ms"]
     roof["alg_bytes_per_launch"] = wk["alg_bytes"]
