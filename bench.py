@@ -16,6 +16,7 @@ bounded sample of the same workload.
   python bench.py --table          # every layer of every config at both batch sizes -> JSON lines
   python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
   python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
+  python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
 """
 from __future__ import annotations
 
@@ -300,6 +301,70 @@ def run_layer(args) -> None:
     print(json.dumps(rec), flush=True)
 
 
+def _time(fn, iters, warmup) -> float:
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def run_split(args) -> None:
+    """Two of the paper's measurements on this hardware, every layer at its largest batch:
+    (1) the format conversion alone (sconv_encode, materialised in HBM) next to the whole
+    convolution kernel, which converts on chip and never stores the format (the paper reports the
+    conversion at 14-50 % of its kernels' time); (2) for the layers followed by pooling, the fused
+    call next to convolution + stand-alone pooling kernel (the fused kernel saves the convolution
+    tensor's round trip through memory).  Same buffers every launch (warm caches)."""
+    import torch
+    import paper_1909_09927_amd as sconv
+    for ci, cfg in enumerate(workloads.CONFIGS):
+        if ci == 0:
+            continue
+        N = max(cfg["batches"])
+        for li in range(len(cfg["layers"])):
+            layer, x, w = workloads.make_layer_inputs(ci, li, N)
+            xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+            L = layer
+            fmt = sconv.FMT_PECR if L.pool else sconv.FMT_ECR
+            desc = sconv.desc_for(xd, wd, L.stride, L.pad, L.groups, L.pool, True)
+            rows, slots = sconv.sconv_encode_sizes(desc, fmt)
+            vals = torch.empty((rows, slots), dtype=torch.float32, device="cuda")
+            idx = torch.empty((rows, slots), dtype=torch.int32, device="cuda")
+            cnt = torch.empty((rows,), dtype=torch.int32, device="cuda")
+            t_enc = _time(lambda: sconv.sconv_encode(xd, w.shape, fmt, L.stride, L.pad, L.groups, L.pool,
+                                                     out=(vals, idx, cnt)), args.steps, args.warmup)
+            y = sconv.sconv_forward(xd, wd, L.stride, L.pad, L.groups, relu=True)
+            t_fwd = _time(lambda: sconv.sconv_forward(xd, wd, L.stride, L.pad, L.groups, relu=True, out=y),
+                          args.steps, args.warmup)
+            rec = {"config": cfg["name"], "layer": L.name, "N": N,
+                   "variant": sconv.sconv_variant_name(desc, False),
+                   "forward_ms": round(t_fwd, 5), "encode_only_ms": round(t_enc, 5),
+                   "format": "PECR" if L.pool else "ECR",
+                   "encoded_MB": round(rows * (slots * 8 + 4) / 1e6, 1),
+                   "encode_over_forward": round(t_enc / t_fwd, 3)}
+            if L.pool:
+                z = sconv.sconv_pool_forward(xd, wd, L.pool, L.stride, L.pad, L.groups)
+                t_fused = _time(lambda: sconv.sconv_pool_forward(xd, wd, L.pool, L.stride, L.pad, L.groups,
+                                                                 out=z), args.steps, args.warmup)
+                t_pool = _time(lambda: sconv.sconv_maxpool(y, x.shape, w.shape, L.pool, L.stride, L.pad,
+                                                           L.groups, out=z), args.steps, args.warmup)
+                rec.update({"fused_ms": round(t_fused, 5), "pool_only_ms": round(t_pool, 5),
+                            "unfused_ms": round(t_fwd + t_pool, 5),
+                            "fused_speedup": round((t_fwd + t_pool) / t_fused, 3),
+                            "conv_tensor_MB": round(y.numel() * 4 / 1e6, 1),
+                            "pool_only_GBps": round((y.numel() + z.numel()) * 4 / (t_pool * 1e-3) / 1e9, 1)})
+            print(json.dumps(rec), flush=True)
+            del vals, idx, cnt, y
+            torch.cuda.empty_cache()
+
+
 def run_copy_calibration(args) -> None:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -321,6 +386,8 @@ def main() -> None:
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--split", action="store_true",
+                    help="conversion-only and unfused-pooling timings beside the whole kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
@@ -344,6 +411,8 @@ def main() -> None:
         run_table(args)
     elif args.sweep:
         run_sweep(args)
+    elif args.split:
+        run_split(args)
     else:
         run_headline(args)
 

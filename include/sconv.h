@@ -105,6 +105,17 @@ int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float
                        float* y_dev, void* hip_stream);
 
 /*
+ * The unfused second step, for comparison with sconv_pool_forward: ReLU and max pooling of a
+ * convolution tensor that sconv_forward stored (Section 5.5 followed by a pooling layer; Section 6
+ * fuses the two to save this tensor's trip through memory):
+ *   y[n][k][ph][pw] = max over py < p_h, px < p_w of max(0, conv[n][k][ph*p_s+py][pw*p_s+px]).
+ * The descriptor is the convolution's (it fixes OH, OW) with its pooling fields.
+ *   conv_dev device, in : [N][K][OH][OW]
+ *   y_dev    device, out: [N][K][PH][PW]
+ */
+int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev, void* hip_stream);
+
+/*
  * Name of the kernel variant the two forward calls would pick for this descriptor (a static
  * string, for benchmark records and profiles).  pooled != 0 asks about sconv_pool_forward.
  * Variants: "quad1x1" (1x1 / stride 1 / pad 0, channels per group a multiple of 64), "quad3x3"

@@ -50,12 +50,13 @@ def lib() -> ctypes.CDLL:
         L.sconv_encode.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, vp]
         L.sconv_forward.argtypes = [P(Desc), vp, vp, vp, vp]
         L.sconv_pool_forward.argtypes = [P(Desc), vp, vp, vp, vp]
+        L.sconv_maxpool.argtypes = [P(Desc), vp, vp, vp]
         L.sconv_variant_name.argtypes = [P(Desc), ctypes.c_int]
         L.sconv_variant_name.restype = ctypes.c_char_p
         L.sconv_strerror.argtypes = [ctypes.c_int]
         L.sconv_strerror.restype = ctypes.c_char_p
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
-                  "sconv_pool_forward"):
+                  "sconv_pool_forward", "sconv_maxpool"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -111,17 +112,26 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None):
-    """Format conversion alone; returns device tensors (values[rows,L], index[rows,L], count[rows])."""
+def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None, out=None):
+    """Format conversion alone; returns device tensors (values[rows,L], index[rows,L], count[rows]).
+    out: an earlier result to write into instead of new tensors."""
     import torch
     _check_dev(x, torch.float32, "x")
     N, C, H, W = x.shape
     K, Cg, R, S = w_shape
     desc = make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool)
     rows, L = sconv_encode_sizes(desc, fmt)
-    values = torch.empty((rows, L), dtype=torch.float32, device=x.device)
-    index = torch.empty((rows, L), dtype=torch.int32, device=x.device)
-    count = torch.empty((rows,), dtype=torch.int32, device=x.device)
+    if out is None:
+        values = torch.empty((rows, L), dtype=torch.float32, device=x.device)
+        index = torch.empty((rows, L), dtype=torch.int32, device=x.device)
+        count = torch.empty((rows,), dtype=torch.int32, device=x.device)
+    else:
+        values, index, count = out
+        _check_dev(values, torch.float32, "values")
+        _check_dev(index, torch.int32, "index")
+        _check_dev(count, torch.int32, "count")
+        if tuple(values.shape) != (rows, L) or tuple(index.shape) != (rows, L) or tuple(count.shape) != (rows,):
+            raise ValueError("out has the wrong shapes")
     rc = lib().sconv_encode(ctypes.byref(desc), fmt, x.data_ptr(), values.data_ptr(), index.data_ptr(),
                             count.data_ptr(), _stream())
     if rc:
@@ -145,6 +155,28 @@ def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
     rc = lib().sconv_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
     if rc:
         raise SconvError(rc, "sconv_forward")
+    return out
+
+
+def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=None):
+    """ReLU + max pooling of a stored convolution tensor conv[N,K,OH,OW]; returns y[N,K,PH,PW]."""
+    import torch
+    _check_dev(conv, torch.float32, "conv")
+    N, C, H, W = x_shape
+    K, Cg, R, S = w_shape
+    desc = make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, True)
+    OH, OW, PH, PW = sconv_output_dims(desc)
+    if tuple(conv.shape) != (N, K, OH, OW):
+        raise ValueError("conv has the wrong shape")
+    if out is None:
+        out = torch.empty((N, K, PH, PW), dtype=torch.float32, device=conv.device)
+    else:
+        _check_dev(out, torch.float32, "out")
+        if tuple(out.shape) != (N, K, PH, PW):
+            raise ValueError("out has the wrong shape")
+    rc = lib().sconv_maxpool(ctypes.byref(desc), conv.data_ptr(), out.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_maxpool")
     return out
 
 

@@ -173,6 +173,16 @@ extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, 
     return run(choose(p, true), p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
+                             void* hip_stream)
+{
+    if (!conv_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, true, &p);
+    if (rc) return rc;
+    return launch_maxpool(p, conv_dev, y_dev, (hipStream_t)hip_stream);
+}
+
 extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
 {
     Problem p;

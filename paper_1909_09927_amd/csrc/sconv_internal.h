@@ -28,6 +28,9 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out);
 int launch_encode(const Problem& p, int fmt, const float* x, float* values, int32_t* index,
                   int32_t* count, hipStream_t stream);
 
+// ReLU + max pooling of a stored convolution tensor [N][K][OH][OW] -> [N][K][PH][PW].
+int launch_maxpool(const Problem& p, const float* conv, float* y, hipStream_t stream);
+
 // General window-row kernel: any R, S, stride, pad, groups, pooling window of up to 64 results.
 int launch_rows(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream);

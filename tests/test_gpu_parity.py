@@ -240,6 +240,25 @@ def test_wide_variant(device, monkeypatch, shp):
         check_forward(layer, x, w, relu=False)
 
 
+@pytest.mark.parametrize("shp", [SMALL[0], SMALL[1], SMALL[3], SMALL[7], SMALL[12], SMALL[17], SMALL[24]])
+def test_unfused_pooling_kernel(device, shp):
+    """ReLU + max pooling of a stored tensor is exact: equal to the oracle's pooling of the same
+    fp32 values; and convolution followed by it meets the fused call's bar."""
+    import oracle
+    from parity import TOL
+    layer, x, w = _mk(115, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    conv = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=False)
+    got = sconv.sconv_maxpool(conv, x.shape, w.shape, layer.pool, layer.stride, layer.pad, layer.groups)
+    torch.cuda.synchronize()
+    conv_h = conv.cpu().numpy()
+    want, _ = oracle.maxpool(np.maximum(conv_h, 0).astype(np.float64), layer.pool)
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+    ref, scale = oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+    err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+    assert (err <= TOL * scale).all()
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)

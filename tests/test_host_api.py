@@ -17,7 +17,7 @@ def test_library_exports_every_declared_symbol():
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(sconv_[a-z_]+)\s*\(", text))
     assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
-            "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name"} <= names
+            "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
@@ -76,6 +76,7 @@ def test_null_pointers_and_bad_pool_and_format():
     assert L.sconv_pool_forward(ctypes.byref(d2), p, p, p, None) == sconv.SCONV_EINVAL
     d3 = sconv.make_desc(1, 16, 20, 20, 32, 3, 3, 1, 1, pool=(9, 9, 2))
     assert L.sconv_pool_forward(ctypes.byref(d3), p, p, p, None) == sconv.SCONV_EUNSUPPORTED
+    assert L.sconv_maxpool(ctypes.byref(d), p, p, None) == sconv.SCONV_EINVAL
     rows, sl = ctypes.c_int64(), ctypes.c_int64()
     assert L.sconv_encode_sizes(ctypes.byref(d), 7, ctypes.byref(rows), ctypes.byref(sl)) == sconv.SCONV_EINVAL
     assert L.sconv_encode_sizes(ctypes.byref(d), sconv.FMT_PECR, ctypes.byref(rows), ctypes.byref(sl)) == sconv.SCONV_EINVAL
