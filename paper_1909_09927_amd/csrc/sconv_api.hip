@@ -74,6 +74,11 @@ static Variant choose(const Problem& p, bool pooled)
         // Small maps with many filters: the 16-row granule has no tile-geometry waste there and
         // measures faster; everywhere else the 4-row granule skips more and wins.
         if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
+        // Few tile-wavefronts (2 output rows x 28 columns x 64 filters each): the vector kernel's
+        // smaller tiles spread over more of the chip and measure faster at small batch.
+        const long long quad_tiles = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
+                                     p.N * p.G;
+        if (quad_tiles < 640 && tap_supported(p, pooled)) return V_TAP;
         return V_QUAD;
     }
     if (tap_supported(p, pooled)) return wide_fills ? V_WIDE : V_TAP;   // 3x3 / stride 2 / pad 1

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(NWV * 64) void pw_kernel(Problem p, PwCfg cfg, cons
     const int tid = threadIdx.x;
     constexpr int nthr = NWV * 64;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: scalar registers
     const int ts = wave % cfg.NT;                  // tile slot
     const int cs = wave / cfg.NT;                  // channel slice
     const int n = blockIdx.z / p.G;

@@ -45,7 +45,8 @@ struct Geom {
     static constexpr int NX = (NPOS + 63) / 64;  // input registers per channel
     static constexpr int ACC = TH * NQ * 4;      // accumulator floats per filter
     static constexpr int KB = 64 * KPL;          // filters per workgroup
-    static constexpr int KBP = KB + 1;           // LDS row stride (odd: conflict-free transposed writes)
+    static constexpr int KBP = KB;               // LDS row stride: 256-byte aligned rows, so the filter
+                                                 // reads need no address arithmetic
     static constexpr int CCH = 16 / KPL;         // channels per staged chunk
     static constexpr int ROWS = CCH * 9;         // LDS rows per buffer
     static constexpr int BUF = ROWS * KBP;       // floats per buffer
@@ -114,7 +115,7 @@ __device__ __forceinline__ void all_quads(std::integer_sequence<int, IHIs...>,
 // x[l] <- x[l + 1] over the whole wavefront (lane 63 gets 0)
 __device__ __forceinline__ float wave_shl1(float v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
 }
 
 template <class G, int NWV>
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
     const int tid = threadIdx.x;
     constexpr int nthr = NWV * 64;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: scalar registers
     const int ts = wave % cfg.NT;                  // spatial tile slot
     const int cs = wave / cfg.NT;                  // channel slice
     const int n = blockIdx.z / p.G;

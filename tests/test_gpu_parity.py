@@ -220,6 +220,25 @@ WIDE = [
 ]
 
 
+QUAD = [s for s in SMALL if s[5:9] == (3, 3, 1, 1) and (s[1] // s[9]) % 16 == 0]
+
+
+@pytest.mark.parametrize("shp", QUAD)
+def test_quad_variant(device, monkeypatch, shp):
+    """The default dispatch sends small launches to the vector kernel; the matrix-core 3x3 kernel
+    is pinned here so that its ragged and small-map cases stay covered."""
+    monkeypatch.setenv("SCONV_VARIANT", "quad")
+    layer, x, w = _mk(116, shp)
+    d = sconv.desc_for(to_dev(x), to_dev(w), layer.stride, layer.pad, layer.groups, layer.pool, True)
+    assert sconv.sconv_variant_name(d, False) == "quad3x3"
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    check_pool_forward(layer, x, w)
+    layer, x, w = _mk(117, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    check_pool_forward(layer, x, w, integer_exact=True)
+
+
 @pytest.mark.parametrize("shp", WIDE)
 def test_wide_variant(device, monkeypatch, shp):
     monkeypatch.setenv("SCONV_VARIANT", "wide")
