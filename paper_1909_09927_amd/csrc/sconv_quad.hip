@@ -58,6 +58,7 @@ struct TapCfg {
     int NT, NCS;        // wavefronts per workgroup = NT spatial tiles x NCS channel slices
     int CPW;            // channels per wavefront per chunk = CCH / NCS
     int tiles_x, tiles_y, ntiles;
+    int tr;             // plain epilogue: transpose each output row through LDS (it fits)
 };
 
 // One accumulator quad's worth of input: row IHI of the tile, output quad CQ.  Its three tap
@@ -258,9 +259,49 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
             }
         }
     }
+    // epilogue: lane owns filters kb0 + lane + 64*i; accumulator (row, quad, e) = output column 4*quad + e
+    if (!G::POOL && cfg.tr) {
+        // Stored from the accumulator layout, every lane of a store would go to a different
+        // output plane, four bytes each.  Instead each output row of the tile is transposed
+        // through LDS (64 filters x TS floats), and a group of RP lanes stores the run of up to
+        // TW contiguous floats one filter has in that row.
+        constexpr int TS = 4 * G::NQ + 8;          // row stride: 16-byte aligned, spreads the banks
+        constexpr int FPI = 64 / G::RP;            // filters per store instruction
+        __syncthreads();   // every wavefront is done with the filter buffers and the reduction
+        if (cs != 0 || !tile_ok) return;
+        float* tr = lds + ts * (64 * TS);
+        const int plane = p.OH * p.OW;
+        const int col = lane % G::RP, fsub = lane / G::RP;
+        const bool col_ok = col < G::TW && ow0 + col < p.OW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int kleft = kvalid - 64 * i;     // filters of this register that exist
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + 64 * i) * plane;
+#pragma unroll
+            for (int orow = 0; orow < G::TH; ++orow) {
+                const int oh = oh0 + orow;         // uniform
+                if (oh >= p.OH) break;
+#pragma unroll
+                for (int q = 0; q < G::NQ; ++q) {
+                    v4f v = acc[i][orow * G::NQ + q];
+                    if (p.relu) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                    }
+                    *reinterpret_cast<v4f*>(tr + lane * TS + 4 * q) = v;
+                }
+                // wavefront-private region: the LDS accesses of one wavefront complete in order
+#pragma unroll
+                for (int kk = 0; kk < G::RP; ++kk) {
+                    const int k = kk * FPI + fsub;
+                    if (col_ok && k < kleft) yk[(size_t)k * plane + oh * p.OW + ow0 + col] = tr[k * TS + col];
+                }
+            }
+        }
+        return;
+    }
     if (cs != 0 || !tile_ok) return;
 
-    // epilogue: lane owns filters kb0 + lane + 64*i; accumulator (row, quad, e) = output column 4*quad + e
     if (!G::POOL) {
         const int plane = p.OH * p.OW;
 #pragma unroll
@@ -393,6 +434,7 @@ Plan plan_geom(const Problem& p)
                 best.cfg.NT = nt;
                 best.cfg.NCS = ncs;
                 best.cfg.CPW = G::CCH / ncs;
+                best.cfg.tr = (size_t)nt * 64 * (4 * G::NQ + 8) * sizeof(float) <= lds_bytes ? 1 : 0;
                 best.nwv = nwv;
                 best.kblocks = kblocks;
             }
