@@ -272,12 +272,14 @@ def run_sweep(args) -> None:
     N = args.batch or 32
     for z in workloads.SWEEP_ZERO_RATIOS:
         layer = base.with_zero_ratio(z)
+        if args.structure != "iid":
+            layer = layer.with_structure(args.structure)
         layer, x, w = workloads.make_layer_inputs(ci, 0, N, layer)
         wk = layer_work(layer, N, x)
         dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
         ms = time_layer(dl, args.steps, args.warmup)
         rec = layer_record(dl, wk, ms)
-        rec["config"] = "regnetx16gf-sweep"
+        rec["config"] = "regnetx16gf-sweep" + ("" if args.structure == "iid" else "-" + args.structure)
         print(json.dumps(rec), flush=True)
         del dl
         torch.cuda.empty_cache()
@@ -290,7 +292,11 @@ def run_layer(args) -> None:
     N = args.batch or max(workloads.CONFIGS[ci]["batches"])
     layer, x, w = workloads.make_layer_inputs(ci, int(li), N)
     if args.zero_ratio >= 0:
-        layer, x, w = workloads.make_layer_inputs(ci, int(li), N, layer.with_zero_ratio(args.zero_ratio))
+        layer = layer.with_zero_ratio(args.zero_ratio)
+    if args.structure != "iid":
+        layer = layer.with_structure(args.structure)
+    if args.zero_ratio >= 0 or args.structure != "iid":
+        layer, x, w = workloads.make_layer_inputs(ci, int(li), N, layer)
     wk = layer_work(layer, N, x)
     dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
     ms = time_layer(dl, args.steps, args.warmup)
@@ -393,6 +399,9 @@ def main() -> None:
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
     ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
     ap.add_argument("--zero-ratio", type=float, default=-1.0, help="override the layer's zero ratio (--layer)")
+    ap.add_argument("--structure", default="iid", choices=["iid", "clustered"],
+                    help="zero pattern of the input for --sweep / --layer: independent zeros, or dead "
+                         "planes plus spatial patches at the same overall ratio")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part (images or filters would "

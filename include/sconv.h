@@ -5,7 +5,10 @@
  * "device" is HIP device memory owned by the caller.  The library allocates, frees and keeps
  * no device memory.  Every entry point that launches work enqueues it on the given HIP stream
  * (a hipStream_t passed as void*; NULL = the default stream) and returns without synchronising.
- * Outputs are overwritten, never accumulated into.
+ * Outputs are overwritten, never accumulated into.  Calls may come from several host threads
+ * (planning and enqueueing are serialised inside the library); the only state kept between calls
+ * is cached launch information (occupancy answers) for the device the first calls ran on, so one
+ * process should drive one device.
  *
  * Notation follows Table 1 of the paper: feature map i_h x i_w (H x W here), kernel k_h x k_w
  * (R x S), pooling window p_h x p_w, convolution stride c_s, pooling stride p_s.  Several input

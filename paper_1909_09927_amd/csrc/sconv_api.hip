@@ -2,6 +2,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "sconv_internal.h"
 
 namespace sconv {
@@ -89,6 +91,10 @@ static Variant choose(const Problem& p, bool pooled)
 static int run(Variant v, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t s)
 {
+    // the launchers cache occupancy answers and attribute opt-ins in static variables: planning and
+    // enqueueing are serialised across host threads (they take microseconds)
+    static std::mutex guard;
+    std::lock_guard<std::mutex> lock(guard);
     int rc = SCONV_EUNSUPPORTED;
     if (v == V_PW) rc = launch_pointwise(p, pooled, x, w, y, s);
     if (v == V_WIDE) {

@@ -51,6 +51,7 @@ class Layer:
     zero_ratio: float = 0.7
     per_channel: Optional[Tuple[float, float]] = None
     magnitude: str = "halfnormal"  # "halfnormal" = |N(0,1)|, "uniform" = U(0,1)
+    structure: str = "iid"         # "iid" zeros, or "clustered": dead planes + spatial clusters
     w_std: Optional[float] = None  # None = He: sqrt(2 / (C_g*R*S))
 
     @property
@@ -68,6 +69,10 @@ class Layer:
     @property
     def OW(self) -> int:
         return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    def with_structure(self, structure: str) -> "Layer":
+        return dataclasses.replace(self, structure=structure, per_channel=None,
+                                   name=f"{self.name}-{structure}")
 
     def with_zero_ratio(self, z: float) -> "Layer":
         return dataclasses.replace(self, zero_ratio=z, per_channel=None,
@@ -151,7 +156,10 @@ def make_feature_map(rng: np.random.Generator, N: int, layer: Layer) -> np.ndarr
         z = rng.uniform(lo, hi, size=(1, layer.C, 1, 1))  # same ratios for every image
     else:
         z = layer.zero_ratio
-    keep = rng.random(shape) >= z
+    if layer.structure == "clustered":
+        keep = _clustered_keep(rng, shape, float(layer.zero_ratio))
+    else:
+        keep = rng.random(shape) >= z
     if layer.magnitude == "uniform":
         mag = rng.random(shape)
     else:
@@ -160,6 +168,23 @@ def make_feature_map(rng: np.random.Generator, N: int, layer: Layer) -> np.ndarr
     # a drawn magnitude that rounds to exactly 0 would silently raise the zero ratio
     mag[mag == 0] = np.float32(0.5)
     return np.where(keep, mag, np.float32(0)).astype(np.float32)
+
+
+def _clustered_keep(rng: np.random.Generator, shape, z: float) -> np.ndarray:
+    """Nonzero mask with the structure ReLU maps tend to have and i.i.d. zeros lack: a share
+    0.3*z of the (image, channel) planes is entirely zero, and inside the other planes the zeros
+    form patches (a smooth field on a 4x4-coarser grid plus a little per-element noise, cut at the
+    quantile that gives the plane its share of zeros).  The overall zero ratio is z."""
+    N, C, H, W = shape
+    p_dead = 0.3 * z
+    z_alive = (z - p_dead) / (1.0 - p_dead) if p_dead < 1.0 else 1.0
+    dead = rng.random((N, C, 1, 1)) < p_dead
+    coarse = rng.standard_normal((N, C, (H + 3) // 4, (W + 3) // 4)).astype(np.float32)
+    field = np.repeat(np.repeat(coarse, 4, axis=2), 4, axis=3)[:, :, :H, :W]
+    field = field + 0.5 * rng.standard_normal(shape).astype(np.float32)
+    cut = np.quantile(field.reshape(N, C, -1), z_alive, axis=2).astype(np.float32)
+    keep = field > cut[:, :, None, None]
+    return keep & ~dead
 
 
 def make_filters(rng: np.random.Generator, layer: Layer) -> np.ndarray:
