@@ -124,8 +124,9 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  * Variants: "quad1x1" (1x1 / stride 1 / pad 0, channels per group a multiple of 64), "quad3x3"
  * (3x3 / stride 1 / pad 1, channels per group a multiple of 16), "wide3x3" (3x3 of any stride and
  * padding, channels per group a multiple of 8; also preferred for maps up to 14 wide with 128 or
- * more filters per group), "tap3x3" (3x3 / pad 1, stride 1 or 2, channels a multiple of 16; runs
- * only when pinned or when the others decline), "rows" (everything else).  The environment
+ * more filters per group), "tap3x3" (3x3 / pad 1, stride 1 or 2, channels a multiple of 16;
+ * preferred for maps up to 7x7 and for launches too small to fill the matrix kernels' tiles),
+ * "rows" (everything else).  The environment
  * variable SCONV_VARIANT ("rows", "tap", "quad", "wide" or unset) pins the choice for profiling.
  * Returns NULL for an invalid descriptor.  Host only.
  */

@@ -73,6 +73,9 @@ static Variant choose(const Problem& p, bool pooled)
     const bool wide_fills = wide_supported(p, pooled) &&
                             ((rows + 63) / 64) * ((p.Kg + 63) / 64) * p.G >= 128;
     if (quad_supported(p, pooled)) {
+        // Maps of 7x7 and below are one whole-map tile of the vector kernel (no halo, no ragged
+        // tiles); it measures 1.4-1.8x faster there than either matrix kernel.
+        if (p.H <= 7 && p.W <= 7 && tap_supported(p, pooled)) return V_TAP;
         // Small maps with many filters: the 16-row granule has no tile-geometry waste there and
         // measures faster; everywhere else the 4-row granule skips more and wins.
         if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
