@@ -17,6 +17,7 @@ bounded sample of the same workload.
   python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
   python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
   python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
+  python bench.py --graph --config resnet50   # a batch-1 step eagerly and as a HIP graph replay
 """
 from __future__ import annotations
 
@@ -371,6 +372,40 @@ def run_split(args) -> None:
             torch.cuda.empty_cache()
 
 
+def run_graph(args) -> None:
+    """One step (every layer of --config at --batch) captured in a HIP graph and replayed, next to
+    the same step launched eagerly: what the launch path costs on the small batch-1 layers.  The
+    library only enqueues on the caller's stream, so a capture needs nothing from it; the first
+    (uncaptured) calls do the one-time set-up (occupancy queries, LDS opt-in)."""
+    import torch
+    ci = [c["name"] for c in workloads.CONFIGS].index(args.config)
+    cfg = workloads.CONFIGS[ci]
+    N = args.batch if args.batch else min(cfg["batches"])
+    host = [workloads.make_layer_inputs(ci, li, N) for li in range(len(cfg["layers"]))]
+    dls = [DeviceLayer(layer, N, x, w, 1) for layer, x, w in host]
+
+    def step():
+        for dl in dls:
+            dl.run()
+
+    step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                       # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    t_eager = _time(step, args.steps, args.warmup)
+    t_graph = _time(graph.replay, args.steps, args.warmup)
+    print(json.dumps({"config": cfg["name"], "N": N, "layers": [l.name for l, _, _ in host],
+                      "variants": [dl.variant for dl in dls],
+                      "eager_ms_per_step": round(t_eager, 5), "graph_ms_per_step": round(t_graph, 5),
+                      "same_buffers_every_step": True}), flush=True)
+
+
 def run_copy_calibration(args) -> None:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -394,6 +429,8 @@ def main() -> None:
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="conversion-only and unfused-pooling timings beside the whole kernels")
+    ap.add_argument("--graph", action="store_true",
+                    help="one step of --config at --batch (default: its smallest) eagerly and as a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
@@ -422,6 +459,8 @@ def main() -> None:
         run_sweep(args)
     elif args.split:
         run_split(args)
+    elif args.graph:
+        run_graph(args)
     else:
         run_headline(args)
 

@@ -300,3 +300,52 @@ def test_runs_on_a_side_stream(device):
         got = sconv.sconv_forward(xd, wd, 1, 1, 1)
     s.synchronize()
     assert torch.equal(got, ref)
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed(device):
+    """The library only enqueues on the caller's stream.  A captured sequence of its calls is
+    replayed several times, with eager work and synchronisations in between, on fresh inputs
+    written into the captured buffers; every replay must equal the eager result."""
+    shapes = [(1, 64, 14, 14, 64, 3, 3, 1, 1, 1, (2, 2, 2)),      # tap3x3 (small launch)
+              (1, 64, 14, 14, 128, 1, 1, 1, 0, 1, (2, 2, 2)),     # quad1x1
+              (2, 16, 9, 9, 24, 3, 3, 2, 0, 1, None)]             # wide3x3
+    cases = [_mk(120 + i, shp) for i, shp in enumerate(shapes)]
+    bufs = []
+    for layer, x, w in cases:
+        xd, wd = to_dev(x), to_dev(w)
+        y = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
+        z = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups) if layer.pool else None
+        bufs.append((layer, xd, wd, y, z))
+    torch.cuda.synchronize()
+
+    def step():
+        for layer, xd, wd, y, z in bufs:
+            sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y)
+            if z is not None:
+                sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=z)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for i, (layer, xd, wd, y, z) in enumerate(bufs):          # fresh inputs in the captured buffers
+            _, xn, _ = _mk(130 + 10 * rep + i, shapes[i])
+            xd.copy_(torch.from_numpy(xn))
+            y.fill_(-1.0)
+            if z is not None:
+                z.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [(y.clone(), None if z is None else z.clone()) for _, _, _, y, z in bufs]
+        step()                                                     # the same work eagerly
+        torch.cuda.synchronize()
+        for (gy, gz), (_, _, _, y, z) in zip(got, bufs):
+            assert torch.equal(gy, y)
+            if z is not None:
+                assert torch.equal(gz, z)
