@@ -42,6 +42,10 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             from . import build as _build
             _build.build()
+        # torch first: its wheel carries its own HIP runtime, and the library must bind to the one the
+        # process's streams and tensors come from (loading the library first would bring in the
+        # system's copy as well, and launches on torch's streams then fail)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         P = ctypes.POINTER
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
