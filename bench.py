@@ -18,6 +18,7 @@ bounded sample of the same workload.
   python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
   python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
   python bench.py --graph --config resnet50   # a batch-1 step eagerly and as a HIP graph replay
+  python bench.py --axis batch | stride       # batch-size / stride sensitivity on one layer shape
 """
 from __future__ import annotations
 
@@ -372,6 +373,31 @@ def run_split(args) -> None:
             torch.cuda.empty_cache()
 
 
+def run_axis(args) -> None:
+    """The paper's two other sensitivity axes on one layer shape (Sections 8.4 and 8.5): batch size
+    1..32 and convolution stride 1..3, on the VGG-shaped 256->256 3x3 layer at 56x56 (pad 1)."""
+    import dataclasses
+    import torch
+    ci, li = 1, 0
+    base = workloads.CONFIGS[ci]["layers"][li]
+    cases = []
+    if args.axis == "batch":
+        cases = [(base, n) for n in (1, 2, 4, 8, 16, 32)]
+    else:
+        cases = [(dataclasses.replace(base, stride=st, name=f"{base.name}-s{st}"), 8) for st in (1, 2, 3)]
+    for layer, N in cases:
+        layer, x, w = workloads.make_layer_inputs(ci, li, N, layer)
+        wk = layer_work(layer, N, x)
+        dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+        ms = time_layer(dl, args.steps, args.warmup)
+        rec = layer_record(dl, wk, ms)
+        rec["config"] = f"vgg19-{args.axis}-sweep"
+        rec["stride"] = layer.stride
+        print(json.dumps(rec), flush=True)
+        del dl
+        torch.cuda.empty_cache()
+
+
 def run_graph(args) -> None:
     """One step (every layer of --config at --batch) captured in a HIP graph and replayed, next to
     the same step launched eagerly: what the launch path costs on the small batch-1 layers.  The
@@ -429,6 +455,8 @@ def main() -> None:
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="conversion-only and unfused-pooling timings beside the whole kernels")
+    ap.add_argument("--axis", default="", choices=["", "batch", "stride"],
+                    help="batch-size or stride sweep on the VGG-shaped 256-channel layer")
     ap.add_argument("--graph", action="store_true",
                     help="one step of --config at --batch (default: its smallest) eagerly and as a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -461,6 +489,8 @@ def main() -> None:
         run_split(args)
     elif args.graph:
         run_graph(args)
+    elif args.axis:
+        run_axis(args)
     else:
         run_headline(args)
 
