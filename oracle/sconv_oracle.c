@@ -14,7 +14,7 @@
  *   - oracle_encode: the conversion of Algorithm 1 (ECR) and Algorithm 3 (PECR), step by step
  *     in the paper's scan order, because an encoding is a representation with exactly one
  *     correct value.
- *   - oracle_spmv: Algorithm 2 / Algorithm 4 (lines 5-8) evaluated on an encoding.
+ *   - oracle_spmv: Algorithm 2 / the product part of Algorithm 4 evaluated on an encoding.
  *
  * Readings of the paper taken here (it is silent or inconsistent on these):
  *   - filter position of tap (i,j) is i*k_w + j, row-major (Algorithm 3 prints i*k_h+j and
@@ -83,7 +83,7 @@ void oracle_encode_sizes(const oracle_shape_t* s, int fmt, int64_t* rows, int64_
         *rows = (int64_t)s->N * s->groups * PH * PW * s->pool_h * s->pool_w;
 }
 
-/* One window (n, g, oh, ow): Algorithm 1 lines 1-11 / Algorithm 3 lines 2-14, with the
+/* One window (n, g, oh, ow): the scan of Algorithm 1 / Algorithm 3, with the
  * channel loop of Section 7 outside.  Returns the number of nonzeros written. */
 static int32_t encode_window(const float* x, const oracle_shape_t* s, int n, int g, int oh, int ow,
                              float* values, int32_t* index)
@@ -105,10 +105,10 @@ static int32_t encode_window(const float* x, const oracle_shape_t* s, int n, int
 
 /*
  * ECR rows in order (n, g, oh, ow): one block row per output row, one thread per output
- * column (Section 5.2); count is -1 for an empty window (Algorithm 1 lines 12-16).
+ * column (Section 5.2); count is -1 for an empty window (the end of Algorithm 1).
  * PECR rows in order (n, g, ph, pw, py, px): pooling-pack rows of pooling windows, the
  * convolution windows inside a pooling window left to right, top to bottom (Section 6.2);
- * count is the plain number of nonzeros (Algorithm 3 line 15).
+ * count is the plain number of nonzeros (the end of Algorithm 3).
  * values/index: [rows][L]; count: [rows].
  */
 void oracle_encode(const oracle_shape_t* s, int fmt, const float* x, float* values, int32_t* index,
@@ -147,7 +147,7 @@ void oracle_encode(const oracle_shape_t* s, int fmt, const float* x, float* valu
 }
 
 /*
- * Algorithm 2 (and lines 5-8 of Algorithm 4) on an encoding: for every row and every filter k
+ * Algorithm 2 (and the product part of Algorithm 4) on an encoding: for every row and every filter k
  * of the row's group, sum value[i] * w[k][index[i]] over the row's nonzeros; an empty row gives
  * 0.  out: [rows][K/groups] in fp64; row order is that of the encoding.
  */
