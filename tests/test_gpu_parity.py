@@ -278,6 +278,40 @@ def test_unfused_pooling_kernel(device, shp):
     assert (err <= TOL * scale).all()
 
 
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = S = int(rng.choice([1, 3, 3, 3, 5]))
+        if rng.random() < 0.15:
+            S = int(rng.choice([1, 2, 3]))
+        groups = int(rng.choice([1, 1, 1, 2, 4]))
+        Cg = int(rng.choice([3, 8, 16, 24, 32, 64, 128]))
+        Kg = int(rng.integers(1, 140))
+        stride = int(rng.choice([1, 1, 1, 2, 3]))
+        pad = int(rng.integers(0, min(R, S)))
+        H, W = int(rng.integers(max(R, 3), 36)), int(rng.integers(max(S, 3), 36))
+        N = int(rng.integers(1, 4))
+        OH, OW = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        if OH < 1 or OW < 1:
+            continue
+        pool = (2, 2, 2) if min(OH, OW) >= 2 and rng.random() < 0.8 else None
+        out.append((N, Cg * groups, H, W, Kg * groups, R, S, stride, pad, groups, pool))
+    return out
+
+
+@pytest.mark.parametrize("shp", _random_shapes(40, 2024))
+def test_random_shapes_through_the_default_dispatch(device, shp):
+    """Seeded random shapes (kernel sizes, strides, paddings, groups, channel counts that do and do
+    not fit the specialised kernels): whatever kernel the dispatch picks must meet the bars."""
+    layer, x, w = _mk(140, shp, z=0.6)
+    check_forward(layer, x, w, relu=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
+    layer, x, w = _mk(141, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)
