@@ -23,14 +23,13 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include "sconv_internal.h"
+#include "sconv_wide_common.h"
 
 namespace sconv {
 
 namespace {
 
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef float v4f __attribute__((ext_vector_type(4)));
+using namespace wide;
 
 template <int KPL_, int R_, int S_, bool POOL_>
 struct WGeom {
@@ -45,44 +44,6 @@ struct WGeom {
     static constexpr int BUF = ROWS * KBP;      // floats per buffer
     static constexpr int NACC = 64 * KPL;       // accumulator floats per lane
 };
-
-struct WideCfg {
-    int NT, NCS;        // wavefronts per workgroup = NT row tiles x NCS channel slices
-    int CPW;            // channels per wavefront per chunk = CCH / NCS
-    int ntiles;         // tiles of 64 window rows
-    int npos;           // window rows: N*OH*OW, or N*PH*PW*4 in PECR order
-    int vec4;           // plain epilogue may store four rows with one 16-byte store
-};
-
-// One tap of one channel: xv holds the 64 rows' elements, m their nonzero mask, wt the lane's
-// filter values.  Four blocks of 16 rows, each guarded by one scalar test.
-template <class G>
-__device__ __forceinline__ void tap_blocks(const float xv, const unsigned long long m,
-                                           const float (&wt)[G::KPL], v16f (&acc)[G::KPL][4])
-{
-    unsigned lo = (unsigned)m, hi = (unsigned)(m >> 32);
-    asm volatile("" : "+s"(lo), "+s"(hi));   // keep the four tests 32-bit scalar compares
-    if (lo & 0xFFFFu) {
-#pragma unroll
-        for (int i = 0; i < G::KPL; ++i)
-            acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][0], 2, 0, 0);
-    }
-    if (lo & 0xFFFF0000u) {
-#pragma unroll
-        for (int i = 0; i < G::KPL; ++i)
-            acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][1], 2, 1, 0);
-    }
-    if (hi & 0xFFFFu) {
-#pragma unroll
-        for (int i = 0; i < G::KPL; ++i)
-            acc[i][2] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][2], 2, 2, 0);
-    }
-    if (hi & 0xFFFF0000u) {
-#pragma unroll
-        for (int i = 0; i < G::KPL; ++i)
-            acc[i][3] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][3], 2, 3, 0);
-    }
-}
 
 template <class G, int NWV>
 __global__ __launch_bounds__(NWV * 64) void wide_kernel(Problem p, WideCfg cfg, const float* __restrict__ x,
@@ -203,7 +164,7 @@ __global__ __launch_bounds__(NWV * 64) void wide_kernel(Problem p, WideCfg cfg, 
         load_x(channel_at(knext), xq);
         if (any) {
 #pragma unroll
-            for (int t = 0; t < T; ++t) tap_blocks<G>(cur[t], m[t], wr[t], acc);
+            for (int t = 0; t < T; ++t) tap_blocks<G::KPL>(cur[t], m[t], wr[t], acc);
         }
     };
 
@@ -228,85 +189,7 @@ __global__ __launch_bounds__(NWV * 64) void wide_kernel(Problem p, WideCfg cfg, 
         }
     }
 
-    // Reduce the channel slices (NCS is 1, 2 or 4).  The four 16-row blocks of the tile are dealt
-    // out to the slices: a slice writes the partial sums of the blocks it does not own to LDS,
-    // then adds what the others wrote for its own blocks and stores those.
-    const int bps = 4 / cfg.NCS;                   // blocks per slice
-    if (cfg.NCS > 1) {
-        float* red = lds;  // [NT][4 blocks][NCS - 1 writers][KPL * 16][64]
-        __syncthreads();   // every wavefront is done with the filter buffers
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int owner = q / bps;
-            if (cs == owner) continue;
-            const int slot = cs - (cs > owner ? 1 : 0);
-            float* dst = red + (size_t)(((ts * 4 + q) * (cfg.NCS - 1) + slot) * (G::KPL * 16)) * 64 + lane;
-#pragma unroll
-            for (int i = 0; i < G::KPL; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) dst[(i * 16 + v) * 64] = acc[i][q][v];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (cs != q / bps) continue;
-            for (int slot = 0; slot < cfg.NCS - 1; ++slot) {
-                const float* src = red + (size_t)(((ts * 4 + q) * (cfg.NCS - 1) + slot) * (G::KPL * 16)) * 64 + lane;
-#pragma unroll
-                for (int i = 0; i < G::KPL; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[i][q][v] += src[(i * 16 + v) * 64];
-            }
-        }
-    }
-    if (!tile_ok) return;
-
-    // epilogue: element (q, 4*b + e) of the lane = filter 16*b + lane%16, window row
-    // 64*tile + 16*q + 4*(lane/16) + e
-    const int kf = lane & 15, rg = lane >> 4;
-#pragma unroll
-    for (int i = 0; i < G::KPL; ++i) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int k = 64 * i + 16 * b + kf;
-            if (k >= kvalid) continue;
-            const size_t kglob = (size_t)g * p.Kg + kb0 + k;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int P0 = tile * 64 + 16 * q + 4 * rg;
-                if (cs != q / bps || P0 >= cfg.npos) continue;
-                float v0 = acc[i][q][4 * b], v1 = acc[i][q][4 * b + 1], v2 = acc[i][q][4 * b + 2],
-                      v3 = acc[i][q][4 * b + 3];
-                if (G::POOL) {
-                    // four rows of one pooling window: ReLU, maximum, one pooled result
-                    const int pp = P0 >> 2;
-                    const int nn = pp / plane;
-                    const float mx = fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), 0.0f);
-                    y[((size_t)nn * p.K + kglob) * plane + (pp - nn * plane)] = mx;
-                } else {
-                    if (p.relu) {
-                        v0 = fmaxf(v0, 0.0f); v1 = fmaxf(v1, 0.0f); v2 = fmaxf(v2, 0.0f); v3 = fmaxf(v3, 0.0f);
-                    }
-                    if (cfg.vec4) {
-                        // plane % 4 == 0: the four rows lie in one image, 16-byte aligned
-                        const int nn = P0 / plane;
-                        float* dst = y + ((size_t)nn * p.K + kglob) * plane + (P0 - nn * plane);
-                        *reinterpret_cast<v4f*>(dst) = v4f{v0, v1, v2, v3};
-                    } else {
-                        const float vs[4] = {v0, v1, v2, v3};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int Pe = P0 + e;
-                            if (Pe < cfg.npos) {
-                                const int nn = Pe / plane;
-                                y[((size_t)nn * p.K + kglob) * plane + (Pe - nn * plane)] = vs[e];
-                            }
-                        }
-                    }
-                }
-            }
-        }
-    }
+    finish_tile<G::KPL, G::POOL>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane, y);
 }
 
 template <class G, int NWV>
