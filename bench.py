@@ -13,7 +13,7 @@ dominant kernel (timed live with events on the launch stream), and the CPU oracl
 bounded sample of the same workload.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config vgg19] [--batch 8]
-  python bench.py --table          # every layer of every config at both batch sizes -> JSON lines
+  python bench.py --table [--only single]   # every layer of every (or one) config at both batch sizes -> JSON lines
   python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
   python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
   python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
@@ -39,7 +39,7 @@ import workloads  # noqa: E402
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TF = 157.3  # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
 FP32_MFMA_PEAK_TF = 157.3    # dense fp32 matrix instructions, published
-MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3")
+MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3", "gen")
 # HBM/fabric bytes per launch from the rocprofv3 counter runs (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB,
 # scaled by the copy calibration); keyed by (variant, layer, batch); the summaries are in profiles/.
 MEASURED_TRAFFIC = {
@@ -253,6 +253,8 @@ def run_table(args) -> None:
     """Every layer of every config at each of its batch sizes; one JSON line per layer."""
     import torch
     for ci, cfg in enumerate(workloads.CONFIGS):
+        if args.only and cfg["name"] != args.only:
+            continue
         for N in cfg["batches"]:
             for li in range(len(cfg["layers"])):
                 layer, x, w = workloads.make_layer_inputs(ci, li, N)
@@ -452,6 +454,7 @@ def main() -> None:
     ap.add_argument("--config", default="vgg19", choices=[c["name"] for c in workloads.CONFIGS])
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--table", action="store_true")
+    ap.add_argument("--only", default="", help="--table: this config only")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--split", action="store_true",
                     help="conversion-only and unfused-pooling timings beside the whole kernels")

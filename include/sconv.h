@@ -85,8 +85,8 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  *   y[n][k][oh][ow] = sum over the window's nonzeros of value * w[k][column],
  * the window of group g = k / (K/G).  Which zeros are skipped depends on the kernel variant the
  * shape selects (sconv_variant_name): "rows" and "tap3x3" skip every zero element; "quad3x3",
- * "quad1x1" and "wide3x3" issue products of several adjacent elements at a time on the matrix pipe
- * (groups of 6, 8 and 16 elements) and skip a group only when all of its elements are zero, so a
+ * "quad1x1", "wide3x3" and "gen" issue products of several adjacent elements at a time on the matrix
+ * pipe (groups of 6, 8, 16 and 16 elements) and skip a group only when all of its elements are zero, so a
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
  *   x_dev device, in : [N][C][H][W]
@@ -126,8 +126,9 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  * padding, channels per group a multiple of 8; also preferred for maps up to 14 wide with 128 or
  * more filters per group), "tap3x3" (3x3 / pad 1, stride 1 or 2, channels a multiple of 16;
  * preferred for maps up to 7x7 and for launches too small to fill the matrix kernels' tiles),
- * "rows" (everything else).  The environment
- * variable SCONV_VARIANT ("rows", "tap", "quad", "wide" or unset) pins the choice for profiling.
+ * "gen" (every other shape with a kernel of at most 15x15 and, when pooling, a 2x2 / stride 2
+ * window), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
+ * "quad", "wide", "gen" or unset) pins the choice for profiling.
  * Returns NULL for an invalid descriptor.  Host only.
  */
 const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);

@@ -57,7 +57,7 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     return SCONV_OK;
 }
 
-enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW, V_WIDE };
+enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW, V_WIDE, V_GEN };
 
 static Variant choose(const Problem& p, bool pooled)
 {
@@ -66,6 +66,7 @@ static Variant choose(const Problem& p, bool pooled)
     if (pin && !strcmp(pin, "tap")) return tap_supported(p, pooled) ? V_TAP : V_ROWS;
     if (pin && !strcmp(pin, "wide")) return wide_supported(p, pooled) ? V_WIDE : V_ROWS;
     if (pin && !strcmp(pin, "quad")) return quad_supported(p, pooled) ? V_QUAD : V_ROWS;
+    if (pin && !strcmp(pin, "gen")) return gen_supported(p, pooled) ? V_GEN : V_ROWS;
     if (pw_supported(p, pooled)) return V_PW;
     // The 16-row granule needs many tile-wavefronts (64 window rows x 64 filters each) to fill the
     // chip: it splits the channels of a tile four ways at most.
@@ -91,6 +92,7 @@ static Variant choose(const Problem& p, bool pooled)
     }
     if (tap_supported(p, pooled)) return wide_fills ? V_WIDE : V_TAP;   // 3x3 / stride 2 / pad 1
     if (wide_supported(p, pooled)) return V_WIDE;     // 3x3 with another stride or padding
+    if (gen_supported(p, pooled)) return V_GEN;       // other kernel sizes, odd channel counts
     return V_ROWS;
 }
 
@@ -103,6 +105,7 @@ static int run(Variant v, const Problem& p, bool pooled, const float* x, const f
     std::lock_guard<std::mutex> lock(guard);
     int rc = SCONV_EUNSUPPORTED;
     if (v == V_PW) rc = launch_pointwise(p, pooled, x, w, y, s);
+    if (v == V_GEN) rc = launch_gen(p, pooled, x, w, y, s);
     if (v == V_WIDE) {
         rc = launch_wide(p, pooled, x, w, y, s);
         if (rc == SCONV_EUNSUPPORTED) v = quad_supported(p, pooled) ? V_QUAD : V_TAP;
@@ -209,6 +212,7 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
     case V_QUAD: return "quad3x3";
     case V_TAP: return "tap3x3";
     case V_WIDE: return "wide3x3";
+    case V_GEN: return "gen";
     default: return "rows";
     }
 }

@@ -1,0 +1,381 @@
+// General matrix-core kernel: any kernel size up to 15x15, any stride, padding and grouping, any
+// channel count; optional 2x2 / stride 2 max-pooling epilogue.
+//
+// Same arithmetic as the wide 3x3 kernel - 64 window rows per wavefront in format order (ECR
+// (n, oh, ow), or PECR (n, ph, pw, py, px) for the fused call, Section 6.2), one
+// v_mfma_f32_16x16x1 per 16-row block and column, a block skipped when its 16 elements under
+// that column are all zero - but the columns col = c*R*S + r*S + s of the window rows
+// (Algorithm 1's scan order with the channel loop of Section 7 outside) are walked as one linear
+// sequence in chunks of 64, so nothing depends on the kernel's shape at compile time:
+//   * the filter chunk w[k][col0 .. col0+63] is staged to LDS as [column][filter] (coalesced
+//     256-byte reads of a filter row, one padding word per LDS row against bank conflicts);
+//   * the position (c, r, s) of a column is wavefront-uniform and kept in scalar registers; a
+//     lane's element under it is one buffer load at lane offset + column offset.  Whether the tap
+//     lies inside the map is one AND + compare against two per-lane bit masks (valid rows r,
+//     valid columns s of the lane's window); a tap outside the map, a column past L or a lane
+//     past the last window row loads from an offset beyond the buffer's size, which the
+//     hardware answers with zero without touching memory;
+//   * elements are loaded one group of 8 columns ahead of the group being multiplied.
+// Channel slices split every chunk's columns between the wavefronts of a tile; the reduction and
+// the epilogue are the wide kernel's.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "sconv_wide_common.h"
+
+namespace sconv {
+
+namespace {
+
+using namespace wide;
+
+constexpr int CW = 64;   // columns per staged chunk
+constexpr int U = 8;     // columns per prefetch group
+
+struct GenCfg {
+    unsigned magicT, magicS;   // floor(2^32 / d) + 1 for d = R*S and d = S (exact quotients for our
+                               // ranges); 0 stands for d = 1
+    int nchunks;               // ceil(L / CW)
+};
+
+template <int KPL, bool POOL, int NWV>
+__global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, GenCfg gc,
+                                                       const float* __restrict__ x,
+                                                       const float* __restrict__ w, float* __restrict__ y)
+{
+    extern __shared__ __align__(16) float lds[];  // two filter buffers; reused for the reduction
+
+    constexpr int KB = 64 * KPL;       // filters per workgroup
+    constexpr int KBP = KB + 1;        // LDS row stride (floats)
+    constexpr int BUF = CW * KBP;      // floats per buffer
+    constexpr int FPT = KB / NWV;      // filters a thread stages per chunk (its column = its lane)
+    static_assert(FPT * NWV == KB, "staging must divide evenly");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ts = wave % cfg.NT;                  // tile slot
+    const int cs = wave / cfg.NT;                  // column slice
+    const int g = blockIdx.z;
+    const int kb0 = blockIdx.y * KB;
+    const int tile = blockIdx.x * cfg.NT + ts;
+    const bool tile_ok = tile < cfg.ntiles;
+    const int HWp = p.H * p.W;
+    const int plane = POOL ? p.PH * p.PW : p.OH * p.OW;
+    const unsigned T = (unsigned)(p.R * p.S);
+
+    // this lane's window row
+    const int P = tile * 64 + lane;
+    const bool pos_ok = tile_ok && P < cfg.npos;
+    int n = 0, oh = 0, ow = 0;
+    if (pos_ok) {
+        if (!POOL) {
+            n = P / plane;
+            const int rem = P - n * plane;
+            oh = rem / p.OW;
+            ow = rem - oh * p.OW;
+        } else {
+            const int pp = P >> 2, e = P & 3;      // pooling window, result inside it (py, px)
+            n = pp / plane;
+            const int rem = pp - n * plane;
+            const int ph = rem / p.PW, pw = rem - ph * p.PW;
+            oh = 2 * ph + (e >> 1);
+            ow = 2 * pw + (e & 1);
+        }
+    }
+    const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+    // bit r: row ih0 + r is inside the map; bit 16 + s: column iw0 + s is.  Bit 31 is never set.
+    unsigned rcmask = 0;
+    if (pos_ok) {
+        for (int r = 0; r < p.R; ++r)
+            if (ih0 + r >= 0 && ih0 + r < p.H) rcmask |= 1u << r;
+        for (int s = 0; s < p.S; ++s)
+            if (iw0 + s >= 0 && iw0 + s < p.W) rcmask |= 0x10000u << s;
+    }
+    // byte offset of the window's origin from the group's first channel; it wraps for windows that
+    // start in the padding and is only ever used together with a tap that lies inside the map
+    const unsigned boff0 = 4u * (unsigned)((n * p.C) * HWp + ih0 * p.W + iw0);
+
+    const float* xg = x + (size_t)g * p.Cg * HWp;
+    const unsigned xbytes = 4u * (unsigned)((p.N * p.C - g * p.Cg) * HWp);   // from xg to the tensor's end
+    const __amdgpu_buffer_rsrc_t xres =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xg), 0, (int)xbytes, 0x00020000);
+    const float* wg = w + ((size_t)g * p.Kg + kb0) * p.L;
+    const int kvalid = min(KB, p.Kg - kb0);
+
+    v16f acc[KPL][4];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][q][v] = 0.0f;
+
+    // Filter staging: wavefront wv moves filters wv, wv + NWV, ... of the block, lane l their column
+    // col0 + l.  A filter past the group's last one re-reads the last valid filter (its results are
+    // never stored); a column past L re-reads column L - 1 (its elements are loaded as zeros, so
+    // its instructions are skipped).
+    float stage[FPT];
+    auto fetch_chunk = [&](int ch) {
+        const int col = min(ch * CW + lane, p.L - 1);
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) {
+            const int k = min(wave + i * NWV, kvalid - 1);
+            stage[i] = wg[(size_t)k * p.L + col];
+        }
+    };
+    auto store_chunk = [&](float* buf) {
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) buf[lane * KBP + wave + i * NWV] = stage[i];
+    };
+
+    // Loads the elements of the U columns starting at column `jb` of the wavefront's share of
+    // chunk `ch`.  Everything about the column is scalar; per lane: AND, compare, add, select, load.
+    auto issue = [&](int ch, int jb, float (&dst)[U]) {
+        const unsigned col0 = (unsigned)(ch * CW + cs * cfg.CPW + jb);
+        const unsigned c = gc.magicT ? __umulhi(col0, gc.magicT) : col0;
+        const unsigned t = col0 - c * T;
+        unsigned r = gc.magicS ? __umulhi(t, gc.magicS) : t;
+        unsigned s = t - r * (unsigned)p.S;
+        unsigned off = 4u * (c * (unsigned)HWp + r * (unsigned)p.W + s);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned need = (col0 + u < (unsigned)p.L) ? ((1u << r) | (0x10000u << s)) : 0x80000000u;
+            const bool ok = (rcmask & need) == need;
+            const unsigned vo = ok ? boff0 + off : 0x80000000u;
+            dst[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xres, (int)vo, 0, 0));
+            ++s;
+            off += 4u;
+            if (s == (unsigned)p.S) {
+                s = 0;
+                ++r;
+                off += 4u * (unsigned)(p.W - p.S);
+                if (r == (unsigned)p.R) {
+                    r = 0;
+                    off += 4u * (unsigned)(HWp - p.R * p.W);
+                }
+            }
+        }
+    };
+
+    // Multiplies U columns: elements in xc, filter values from the staged chunk.
+    auto compute = [&](const float* buf, int jb, const float (&xc)[U]) {
+        unsigned long long m[U];
+        unsigned long long any = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            m[u] = __ballot(xc[u] != 0.0f);
+            any |= m[u];
+        }
+        if (!any) return;
+        const float* wl = buf + (cs * cfg.CPW + jb) * KBP + lane;
+        float wq[2][KPL];
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) wq[0][i] = wl[64 * i];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (u + 1 < U) {
+#pragma unroll
+                for (int i = 0; i < KPL; ++i) wq[(u + 1) & 1][i] = wl[(u + 1) * KBP + 64 * i];
+            }
+            tap_blocks<KPL>(xc[u], m[u], wq[u & 1], acc);
+        }
+    };
+
+    // the wavefront's groups in the order it walks them: CPW / U per chunk
+    int pch = 0, pjb = 0;   // the next group to load
+    auto advance = [&]() {
+        pjb += U;
+        if (pjb == cfg.CPW) {
+            pjb = 0;
+            ++pch;
+        }
+    };
+
+    fetch_chunk(0);
+    float xa[U], xb[U];
+    issue(pch, pjb, xa);
+    advance();
+    for (int ch = 0; ch < gc.nchunks; ++ch) {
+        float* buf = lds + (ch & 1) * BUF;
+        store_chunk(buf);
+        __syncthreads();
+        if (ch + 1 < gc.nchunks) fetch_chunk(ch + 1);
+        for (int jb = 0; jb < cfg.CPW; jb += 2 * U) {
+            issue(pch, pjb, xb);
+            advance();
+            compute(buf, jb, xa);
+            issue(pch, pjb, xa);   // past the last chunk: columns >= L, nothing is read
+            advance();
+            compute(buf, jb + U, xb);
+        }
+    }
+
+    finish_tile<KPL, POOL>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane, y);
+}
+
+struct Plan {
+    double cost = -1.0;   // model clocks; negative = not applicable
+    WideCfg cfg;
+    int nwv = 0;
+    int kblocks = 0;
+    size_t lds_bytes = 0;
+};
+
+template <int KPL, bool POOL, int NWV>
+int occupancy(size_t lds_bytes)
+{
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gen_kernel<KPL, POOL, NWV>, NWV * 64, lds_bytes) !=
+            hipSuccess || nb < 1)
+        nb = 1;
+    return nb;
+}
+
+// Decomposition of one launch, with the wide kernel's model: the matrix time of the most loaded
+// SIMD plus what does not overlap with it (slice reduction, half of the filter staging, a latency
+// penalty when a SIMD holds a single wavefront).
+template <int KPL, bool POOL>
+Plan plan_geom(const Problem& p)
+{
+    constexpr int KB = 64 * KPL;
+    Plan best;
+    WideCfg cfg;
+    cfg.npos = POOL ? p.N * p.PH * p.PW * 4 : p.N * p.OH * p.OW;
+    cfg.ntiles = (cfg.npos + 63) / 64;
+    cfg.vec4 = 0;
+    const int kblocks = (p.Kg + KB - 1) / KB;
+    const int nchunks = (p.L + CW - 1) / CW;
+    const double t_column = 4.0 * KPL * 34.0 + 30.0;
+    const double stage_clocks = (double)KB * nchunks * CW * 4.0 / 64.0;
+
+    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_GEN_SPLIT="nwv,ncs"
+    if (const char* pin = getenv("SCONV_GEN_SPLIT")) {
+        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
+    }
+    for (int nwv = 4; nwv <= 8; nwv *= 2) {
+        if (KPL == 2 && nwv == 4) continue;      // 32 staging registers per thread: not built
+        for (int ncs = 1; ncs <= 4; ncs *= 2) {
+            const int nt = nwv / ncs;
+            if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
+            if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
+            size_t lds_bytes = 2 * (size_t)CW * (KB + 1) * sizeof(float);
+            const size_t red_bytes = (size_t)nt * 4 * (ncs - 1) * KPL * 16 * 64 * sizeof(float);
+            if (red_bytes > lds_bytes) lds_bytes = red_bytes;
+            if (lds_bytes > 160 * 1024) continue;
+            const int occ = nwv == 4 ? occupancy<KPL, POOL, (KPL == 2 ? 8 : 4)>(lds_bytes)
+                                     : occupancy<KPL, POOL, 8>(lds_bytes);
+            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.G;
+            const long long per_cu = (wgs + 255) / 256;
+            const double per_simd = (double)per_cu * nwv / 4.0;
+            const double resident = (double)(per_cu < occ ? per_cu : occ) * nwv / 4.0;
+            const double wave = (double)nchunks * (CW / ncs) * t_column + (ncs > 1 ? 64.0 * KPL * 20.0 + 800.0 : 0.0);
+            double cost = per_simd * wave * (resident < 2.0 ? 1.25 : 1.0) + per_cu * stage_clocks * 0.5;
+            if (best.cost < 0.0 || cost < best.cost) {
+                best.cost = cost;
+                best.cfg = cfg;
+                best.cfg.NT = nt;
+                best.cfg.NCS = ncs;
+                best.cfg.CPW = CW / ncs;
+                best.nwv = nwv;
+                best.kblocks = kblocks;
+                best.lds_bytes = lds_bytes;
+            }
+        }
+    }
+    return best;
+}
+
+template <int KPL, bool POOL, int NWV>
+int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid, size_t lds_bytes,
+               const float* x, const float* w, float* y, hipStream_t stream)
+{
+    auto kern = gen_kernel<KPL, POOL, NWV>;
+    static size_t opted = 0;  // dynamic LDS above 48 KiB is opted into (largest request so far)
+    if (lds_bytes > opted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return SCONV_ELAUNCH;
+        opted = lds_bytes;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, gc, x, w, y);
+    return launch_status();
+}
+
+template <int KPL, bool POOL>
+int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+                hipStream_t stream)
+{
+    const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
+    if (p.G > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)p.G);
+    WideCfg cfg = pl.cfg;
+    const int plane = p.OH * p.OW;
+    cfg.vec4 = (!POOL && plane % 4 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0;
+    GenCfg gc;
+    gc.magicT = p.R * p.S > 1 ? (unsigned)((1ULL << 32) / (unsigned)(p.R * p.S)) + 1u : 0u;
+    gc.magicS = p.S > 1 ? (unsigned)((1ULL << 32) / (unsigned)p.S) + 1u : 0u;
+    gc.nchunks = (p.L + CW - 1) / CW;
+    if constexpr (KPL == 1) {
+        if (pl.nwv == 4) return launch_nwv<KPL, POOL, 4>(p, cfg, gc, grid, pl.lds_bytes, x, w, y, stream);
+    }
+    return launch_nwv<KPL, POOL, 8>(p, cfg, gc, grid, pl.lds_bytes, x, w, y, stream);
+}
+
+bool shape_ok(const Problem& p, bool pooled)
+{
+    if (p.R > 15 || p.S > 15) return false;            // one mask bit per kernel row and column
+    if (pooled && (p.ph != 2 || p.pw != 2 || p.ps != 2)) return false;
+    // 32-bit byte offsets into the input with the top bit free, 32-bit window row numbers
+    if ((long long)p.N * p.C * p.H * p.W >= (1LL << 29)) return false;
+    const long long npos = pooled ? (long long)p.N * p.PH * p.PW * 4 : (long long)p.N * p.OH * p.OW;
+    if (npos >= (1LL << 31) - 64) return false;
+    // the multiply-high quotients col / (R*S) and t / S are exact while dividend * divisor < 2^32
+    const long long T = (long long)p.R * p.S;
+    if (((long long)p.L + 2 * CW) * T >= (1LL << 32)) return false;
+    return true;
+}
+
+struct Candidate {
+    const char* name;
+    Plan (*plan)(const Problem&);
+    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    bool pooled;
+    int kpl;
+};
+
+const Candidate kCandidates[] = {
+    {"gk1", plan_geom<1, false>, launch_plan<1, false>, false, 1},
+    {"gk2", plan_geom<2, false>, launch_plan<2, false>, false, 2},
+    {"gpk1", plan_geom<1, true>, launch_plan<1, true>, true, 1},
+    {"gpk2", plan_geom<2, true>, launch_plan<2, true>, true, 2},
+};
+
+}  // namespace
+
+bool gen_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
+
+int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t stream)
+{
+    if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
+    const char* pin = getenv("SCONV_GEN_GEOM");   // tuning aid: candidate name
+    const Candidate* best = nullptr;
+    Plan best_plan;
+    for (const Candidate& c : kCandidates) {
+        if (c.pooled != pooled) continue;
+        if (p.Kg <= 64 * (c.kpl - 1)) continue;
+        if (pin && strcmp(pin, c.name) != 0) continue;
+        const Plan pl = c.plan(p);
+        if (pl.cost < 0.0) continue;
+        if (!best || pl.cost < best_plan.cost) {
+            best = &c;
+            best_plan = pl;
+        }
+    }
+    if (!best) return SCONV_EUNSUPPORTED;
+    return best->launch(best_plan, p, x, w, y, stream);
+}
+
+}  // namespace sconv

@@ -50,6 +50,12 @@ bool wide_supported(const Problem& p, bool pooled);
 int launch_wide(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream);
 
+// General matrix-core kernel: kernels up to 15x15, any stride, padding, grouping and channel count;
+// 16 window rows per instruction, columns walked linearly.
+bool gen_supported(const Problem& p, bool pooled);
+int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t stream);
+
 // Matrix-core kernel for 1x1 / stride 1 / pad 0 convolutions (optional 2x2 / stride 2 pooling).
 bool pw_supported(const Problem& p, bool pooled);
 int launch_pointwise(const Problem& p, bool pooled, const float* x, const float* w, float* y,

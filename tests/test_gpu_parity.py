@@ -118,7 +118,7 @@ def _layers(ci):
     return list(enumerate(workloads.CONFIGS[ci]["layers"]))
 
 
-@pytest.mark.parametrize("ci,li", [(ci, li) for ci in (1, 2, 3, 4) for li, _ in _layers(ci)])
+@pytest.mark.parametrize("ci,li", [(ci, li) for ci in (1, 2, 3, 4, 5) for li, _ in _layers(ci)])
 def test_benchmark_layers_batch1(device, ci, li):
     """Every layer shape of the benchmark configs at batch 1, whole tensor against the oracle."""
     layer, x, w = workloads.make_layer_inputs(ci, li, 1)
@@ -130,7 +130,7 @@ def test_benchmark_layers_batch1(device, ci, li):
 
 def _full_size_cases():
     out = []
-    for ci in (1, 2, 3, 4):
+    for ci in (1, 2, 3, 4, 5):
         N = max(workloads.CONFIGS[ci]["batches"])
         for li, _ in _layers(ci):
             out.append((ci, li, N))
@@ -183,7 +183,7 @@ def test_benchmark_layers_full_batch_sampled(device, ci, li, N):
     assert (err <= TOL * scale).all(), f"worst ratio {np.max(err / np.maximum(scale, 1e-300)):.3e}"
 
 
-@pytest.mark.parametrize("variant", ["rows", "tap", "quad", "wide", None])
+@pytest.mark.parametrize("variant", ["rows", "tap", "quad", "wide", "gen", None])
 @pytest.mark.parametrize("shp", [
     (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),
     (2, 48, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)),
@@ -218,6 +218,48 @@ WIDE = [
     (1, 16, 22, 22, 24, 3, 3, 3, 2, 1, (2, 2, 2)),      # stride 3, pad 2
     (1, 16, 3, 3, 5, 3, 3, 1, 1, 1, None),              # a single tile, mostly empty
 ]
+
+
+# any kernel size, stride, padding and channel count: the general matrix-core kernel
+GEN = [
+    (1, 16, 21, 21, 20, 7, 7, 2, 3, 1, (2, 2, 2)),      # 7x7 / stride 2 / pad 3
+    (2, 3, 31, 29, 70, 11, 11, 4, 2, 1, (2, 2, 2)),     # 3 channels, 11x11 / stride 4: L = 363, ragged chunk
+    (1, 6, 14, 14, 16, 5, 5, 1, 0, 1, (2, 2, 2)),       # 5x5 without padding
+    (2, 20, 12, 12, 50, 5, 5, 1, 2, 1, (2, 2, 2)),
+    (1, 4, 9, 8, 6, 3, 2, 2, 1, 2, None),               # non-square kernel, grouped
+    (2, 33, 17, 13, 130, 3, 3, 1, 1, 1, (2, 2, 2)),     # 3x3 with an odd channel count, two filters per lane
+    (2, 48, 9, 11, 200, 1, 1, 2, 0, 1, None),           # 1x1 / stride 2
+    (1, 2, 10, 11, 3, 5, 3, 3, 2, 1, None),             # stride 3, pad 2
+    (1, 5, 3, 3, 4, 5, 5, 1, 2, 1, None),               # kernel larger than the map
+    (3, 64, 7, 7, 128, 5, 5, 1, 2, 2, (2, 2, 2)),       # grouped, several images per 64-row tile
+    (1, 192, 14, 14, 96, 5, 5, 1, 2, 1, (2, 2, 2)),     # L = 4800: many chunks
+    (1, 1, 20, 20, 1, 15, 15, 1, 7, 1, None),           # largest kernel, one channel, one filter
+]
+
+
+@pytest.mark.parametrize("split", [None, "4,1", "8,2", "8,4"])
+@pytest.mark.parametrize("shp", GEN)
+def test_gen_variant(device, monkeypatch, shp, split):
+    """The general matrix-core kernel pinned, with its own choice of column slices and with each
+    split forced (the plan falls back to its own choice where a forced split does not apply)."""
+    monkeypatch.setenv("SCONV_VARIANT", "gen")
+    if split:
+        monkeypatch.setenv("SCONV_GEN_SPLIT", split)
+    layer, x, w = _mk(150, shp)
+    d = sconv.desc_for(to_dev(x), to_dev(w), layer.stride, layer.pad, layer.groups, layer.pool, True)
+    assert sconv.sconv_variant_name(d, False) == "gen"
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
+    layer, x, w = _mk(151, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w, integer_exact=True)
+    if split is None:
+        for z in (0.0, 0.97, 1.0):
+            layer, x, w = _mk(152, shp, z=z)
+            check_forward(layer, x, w, relu=False)
 
 
 QUAD = [s for s in SMALL if s[5:9] == (3, 3, 1, 1) and (s[1] // s[9]) % 16 == 0]

@@ -94,7 +94,10 @@ def test_strerror_and_variant_name():
     assert "invalid" in sconv.strerror(sconv.SCONV_EINVAL)
     assert sconv.strerror(-99).startswith("unknown")
     assert sconv.sconv_variant_name(sconv.make_desc(1, 256, 56, 56, 64, 1, 1)) == "quad1x1"
-    assert sconv.sconv_variant_name(sconv.make_desc(1, 250, 56, 56, 64, 1, 1)) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 250, 56, 56, 64, 1, 1)) == "gen"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2)) == "gen"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 17, 17, 1, 2)) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2, 1, (3, 3, 2)), True) == "rows"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 2, 1)) == "tap3x3"
@@ -105,7 +108,7 @@ def test_strerror_and_variant_name():
     assert sconv.sconv_variant_name(sconv.make_desc(32, 896, 14, 14, 896, 3, 3, 1, 1, 7)) == "wide3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 512, 14, 14, 512, 3, 3, 1, 1, pool=(2, 2, 2)), True) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 256, 28, 28, 256, 3, 3, 1, 1, pool=(2, 2, 2)), True) == "quad3x3"
-    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 5, 5, 1, 2)) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 5, 5, 1, 2)) == "gen"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1, pool=(3, 3, 2)), True) == "rows"
     assert sconv.sconv_variant_name(sconv.Desc()) is None
 

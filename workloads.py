@@ -139,6 +139,30 @@ CONFIGS: List[Dict] = [
             Layer("rx-2048x7-g16", C=2048, H=7, W=7, K=2048, R=3, S=3, pad=1, groups=16),
         ],
     },
+    {
+        # Single layers on small maps (Table 3 lists network, layer, map size and zero ratio but no
+        # channel counts or kernel sizes; those are the public architectures' for the named layer,
+        # with the map size as printed).
+        "name": "single",
+        "batches": (1, 32),
+        "layers": [
+            Layer("lenet-conv2-5x5-20to50x11", C=20, H=11, W=11, K=50, R=5, S=5, zero_ratio=0.95),
+            Layer("alexnet-conv3-256to384x6", C=256, H=6, W=6, K=384, R=3, S=3, pad=1, zero_ratio=0.9),
+            Layer("alexnet-conv4-384x5-g2", C=384, H=5, W=5, K=384, R=3, S=3, pad=1, groups=2,
+                  zero_ratio=0.9),
+            Layer("googlenet-4a-1x1-480to192x14", C=480, H=14, W=14, K=192, R=1, S=1, zero_ratio=0.9),
+            Layer("googlenet-4a-1x1-480to96x14", C=480, H=14, W=14, K=96, R=1, S=1, zero_ratio=0.9),
+            Layer("googlenet-4e-3x3-160to320x14", C=160, H=14, W=14, K=320, R=3, S=3, pad=1,
+                  zero_ratio=0.9),
+            Layer("googlenet-5a-1x1-832to256x7", C=832, H=7, W=7, K=256, R=1, S=1, zero_ratio=0.95),
+            Layer("googlenet-5a-1x1-832to160x7", C=832, H=7, W=7, K=160, R=1, S=1, zero_ratio=0.9),
+            Layer("googlenet-5b-3x3-192to384x7", C=192, H=7, W=7, K=384, R=3, S=3, pad=1,
+                  zero_ratio=0.95),
+            Layer("googlenet-5x5-48to128x7", C=48, H=7, W=7, K=128, R=5, S=5, pad=2, zero_ratio=0.95),
+            Layer("vgg-conv15-512x14", C=512, H=14, W=14, K=512, R=3, S=3, pad=1, zero_ratio=0.83),
+            Layer("resnet-conv42-256x14", C=256, H=14, W=14, K=256, R=3, S=3, pad=1, zero_ratio=0.86),
+        ],
+    },
 ]
 
 SWEEP_ZERO_RATIOS = tuple(round(0.05 * i, 2) for i in range(20))  # 0.00 .. 0.95
