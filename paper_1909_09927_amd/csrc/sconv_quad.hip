@@ -61,15 +61,20 @@ struct TapCfg {
     int tr;             // plain epilogue: transpose each output row through LDS (it fits)
 };
 
+// x[l] <- x[l + 1] over the whole wavefront (lane 63 gets 0)
+__device__ __forceinline__ float wave_shl1(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
+}
+
 // One accumulator quad's worth of input: row IHI of the tile, output quad CQ.  Its three tap
 // columns read lanes b0 .. b0 + 5 of input register Q (b0 on a block boundary); in the copy
 // shifted by s lanes the four elements of tap column s are block number b0 / 4.  One scalar test
 // of those six mask bits guards the up to nine matrix instructions (three tap columns times the
 // tap rows whose output row lies in the tile) of each of the lane's filters.
 template <class G, int IHI, int CQ>
-__device__ __forceinline__ void quad_group(const unsigned (&mask)[2 * G::NX],
-                                           const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
-                                           const float (&wr)[G::KPL][9])
+__device__ __forceinline__ void quad_group(const unsigned (&mask)[2 * G::NX], const float (&xs)[3],
+                                           v4f (&acc)[G::KPL][G::TH * G::NQ], const float (&wr)[G::KPL][9])
 {
     constexpr int P0 = IHI * G::RP + CQ * 4;     // lane position of the block in the tile
     constexpr int Q = P0 / 64, B0 = P0 % 64;
@@ -89,34 +94,33 @@ __device__ __forceinline__ void quad_group(const unsigned (&mask)[2 * G::NX],
 #pragma unroll
                 for (int i = 0; i < G::KPL; ++i)
                     acc[i][orow * G::NQ + CQ] = __builtin_amdgcn_mfma_f32_4x4x1f32(
-                        xs[s][Q], wr[i][r * 3 + s], acc[i][orow * G::NQ + CQ], 4, B0 / 4, 0);
+                        xs[s], wr[i][r * 3 + s], acc[i][orow * G::NQ + CQ], 4, B0 / 4, 0);
             }
         }
     }
 }
 
+// One input row of the tile.  The row's lanes sit in one input register; the copies shifted by one
+// and two lanes are made here, right before their use, so that only one register's copies are alive.
 template <class G, int IHI, int... CQs>
 __device__ __forceinline__ void quad_row(std::integer_sequence<int, CQs...>,
-                                         const unsigned (&mask)[2 * G::NX],
-                                         const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
-                                         const float (&wr)[G::KPL][9])
+                                         const unsigned (&mask)[2 * G::NX], const float (&x0)[G::NX],
+                                         v4f (&acc)[G::KPL][G::TH * G::NQ], const float (&wr)[G::KPL][9])
 {
+    constexpr int Q = IHI * G::RP / 64;
+    float xs[3];
+    xs[0] = x0[Q];
+    xs[1] = wave_shl1(xs[0]);
+    xs[2] = wave_shl1(xs[1]);
     (quad_group<G, IHI, CQs>(mask, xs, acc, wr), ...);
 }
 
 template <class G, int... IHIs>
 __device__ __forceinline__ void all_quads(std::integer_sequence<int, IHIs...>,
-                                          const unsigned (&mask)[2 * G::NX],
-                                          const float (&xs)[3][G::NX], v4f (&acc)[G::KPL][G::TH * G::NQ],
-                                          const float (&wr)[G::KPL][9])
+                                          const unsigned (&mask)[2 * G::NX], const float (&x0)[G::NX],
+                                          v4f (&acc)[G::KPL][G::TH * G::NQ], const float (&wr)[G::KPL][9])
 {
-    (quad_row<G, IHIs>(std::make_integer_sequence<int, G::NQ>{}, mask, xs, acc, wr), ...);
-}
-
-// x[l] <- x[l + 1] over the whole wavefront (lane 63 gets 0)
-__device__ __forceinline__ float wave_shl1(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
+    (quad_row<G, IHIs>(std::make_integer_sequence<int, G::NQ>{}, mask, x0, acc, wr), ...);
 }
 
 template <class G, int NWV>
@@ -204,12 +208,12 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
 
         const int cbase = ch * G::CCH + cs * cfg.CPW;   // this wavefront's channels of the chunk
         for (int cc = 0; cc < cfg.CPW; ++cc) {
-            float xs[3][G::NX];
+            float xs[G::NX];
             unsigned mask[2 * G::NX];
 #pragma unroll
             for (int q = 0; q < G::NX; ++q) {
-                xs[0][q] = xn[q];
-                const unsigned long long m = __ballot(xs[0][q] != 0.0f);
+                xs[q] = xn[q];
+                const unsigned long long m = __ballot(xs[q] != 0.0f);
                 mask[2 * q] = (unsigned)m;
                 mask[2 * q + 1] = (unsigned)(m >> 32);
             }
@@ -221,11 +225,6 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
 #pragma unroll
             for (int q = 0; q < 2 * G::NX; ++q) any |= mask[q];
             if (any) {
-#pragma unroll
-                for (int q = 0; q < G::NX; ++q) {
-                    xs[1][q] = wave_shl1(xs[0][q]);
-                    xs[2][q] = wave_shl1(xs[1][q]);
-                }
                 float wr[G::KPL][9];
                 const float* wl = buf + (cs * cfg.CPW + cc) * 9 * G::KBP + lane;
 #pragma unroll
@@ -344,17 +343,19 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
     }
 }
 
-// Workgroups of one kernel instantiation that fit on a compute unit (asked once).
+// Workgroups of one kernel instantiation that fit on a compute unit (asked once per LDS size).
 template <class G, int NWV>
 int occupancy(size_t lds_bytes)
 {
     static int occ = 0;
-    if (occ == 0) {
+    static size_t asked = 0;
+    if (occ == 0 || asked != lds_bytes) {
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, quad_kernel<G, NWV>, NWV * 64, lds_bytes) !=
                 hipSuccess || nb < 1)
             nb = 1;
         occ = nb;
+        asked = lds_bytes;
     }
     return occ;
 }
@@ -364,12 +365,12 @@ int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes,
                const float* w, float* y, hipStream_t stream)
 {
     auto kern = quad_kernel<G, NWV>;
-    static bool opted = false;  // dynamic LDS above 48 KiB is opted into once per kernel
-    if (!opted) {
+    static size_t opted = 0;  // dynamic LDS above 48 KiB is opted into (largest request so far)
+    if (lds_bytes > opted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return SCONV_ELAUNCH;
-        opted = true;
+        opted = lds_bytes;
     }
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, x, w, y);
     return launch_status();
@@ -381,6 +382,7 @@ struct Plan {
     TapCfg cfg;
     int nwv = 0;
     int kblocks = 0;
+    size_t lds_bytes = 0;
 };
 
 // Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
@@ -400,7 +402,7 @@ Plan plan_geom(const Problem& p)
     cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
     cfg.ntiles = cfg.tiles_x * cfg.tiles_y;
     const int kblocks = (p.Kg + G::KB - 1) / G::KB;
-    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t buf_bytes = 2 * (size_t)G::BUF * sizeof(float);
     const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
     // clocks of one wavefront on one channel: a test per input row and quad, and for the groups
     // with a nonzero (88 % at 30 % density) their share of the 9 * TH * NQ * KPL matrix
@@ -414,18 +416,26 @@ Plan plan_geom(const Problem& p)
         if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
     }
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
-        const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
-            if (ncs > 1 && nt * red_per_tile > lds_bytes) continue;
+            // the slice reduction reuses the filter buffers; a large tile's partial sums need more
+            size_t lds_bytes = buf_bytes;
+            if (ncs > 1 && nt * red_per_tile > lds_bytes) lds_bytes = nt * red_per_tile;
+            if (lds_bytes > 160 * 1024) continue;
             if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
+            // a 7-row tile's long reduction and epilogue need 32 channels per slice to pay off
+            if (!pin_nwv && G::TH >= 7 && ncs > 1 && p.Cg / ncs < 32) continue;
+            const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
             const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
             const long long slots = 256LL * occ;
             const long long rounds = (wgs + slots - 1) / slots;
             const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
             double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
-            if (r < 4.0) r = 4.0;
+            // below this many resident wavefronts a SIMD is not kept busy; a 7-row tile's wavefront
+            // issues 441 matrix instructions per channel and two of them are enough
+            const double r_min = G::TH >= 7 ? 2.0 : 4.0;
+            if (r < r_min) r = r_min;
             const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
                                 (ncs - 1) * 8000.0;   // reduction steps and barrier-bound short slices
             if (best.cost < 0.0 || cost < best.cost) {
@@ -437,6 +447,7 @@ Plan plan_geom(const Problem& p)
                 best.cfg.tr = (size_t)nt * 64 * (4 * G::NQ + 8) * sizeof(float) <= lds_bytes ? 1 : 0;
                 best.nwv = nwv;
                 best.kblocks = kblocks;
+                best.lds_bytes = lds_bytes;
             }
         }
     }
@@ -447,7 +458,7 @@ template <class G>
 int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
-    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t lds_bytes = pl.lds_bytes;
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
     const unsigned gz = (unsigned)(p.N * p.G);
     if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
@@ -463,6 +474,7 @@ int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w
 // the fourth quad are computed from the neighbouring row's lanes and never stored), 2 output rows.
 using Q32_1 = Geom<1, 2, 32, 7, 28, false>;
 using Q32_2 = Geom<2, 1, 32, 7, 28, false>;
+using Q32_T7 = Geom<1, 7, 32, 7, 28, false>;   // 7 output rows: heights that are multiples of 7
 using Q16_2 = Geom<2, 2, 16, 4, 14, false>;
 using QP32_1 = Geom<1, 2, 32, 7, 28, true>;
 using QP16_2 = Geom<2, 2, 16, 4, 14, true>;
@@ -487,6 +499,7 @@ struct Candidate {
 const Candidate kCandidates[] = {
     {"q32k1", plan_geom<Q32_1>, launch_plan<Q32_1>, false, 1, true},
     {"q32k2", plan_geom<Q32_2>, launch_plan<Q32_2>, false, 2, true},
+    {"q32t7", plan_geom<Q32_T7>, launch_plan<Q32_T7>, false, 1, true},
     {"q16k2", plan_geom<Q16_2>, launch_plan<Q16_2>, false, 2, false},
     {"qp32k1", plan_geom<QP32_1>, launch_plan<QP32_1>, true, 1, true},
     {"qp16k2", plan_geom<QP16_2>, launch_plan<QP16_2>, true, 2, false},
@@ -500,13 +513,15 @@ int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, f
                 hipStream_t stream)
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
-    const char* pin = getenv("SCONV_QUAD_GEOM");   // tuning aid: candidate name
+    const char* pin = getenv("SCONV_QUAD_GEOM");   // tuning aid: candidate name, or !name to exclude one
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {
         if (c.pooled != pooled) continue;
         if (p.Kg <= 64 * (c.kpl - 1)) continue;
-        if (pin ? strcmp(pin, c.name) != 0 : (c.wide != (p.W > 14))) continue;
+        if (pin ? (pin[0] == '!' ? strcmp(pin + 1, c.name) == 0 || c.wide != (p.W > 14) : strcmp(pin, c.name) != 0)
+                : (c.wide != (p.W > 14)))
+            continue;
         const Plan pl = c.plan(p);
         if (pl.cost < 0.0) continue;
         if (!best || pl.cost < best_plan.cost) {

@@ -281,6 +281,25 @@ def test_quad_variant(device, monkeypatch, shp):
     check_pool_forward(layer, x, w, integer_exact=True)
 
 
+@pytest.mark.parametrize("split", [None, "8,8", "8,2", "8,1"])
+@pytest.mark.parametrize("shp", [
+    (2, 32, 21, 56, 70, 3, 3, 1, 1, 1, None),           # three 7-row tiles, two column tiles, ragged filter block
+    (1, 64, 9, 30, 64, 3, 3, 1, 1, 2, None),            # ragged last tile row, grouped
+    (1, 128, 28, 28, 128, 3, 3, 1, 1, 1, None),
+])
+def test_quad_seven_row_tiles(device, monkeypatch, shp, split):
+    """The 7-row tile geometry of the matrix-core 3x3 kernel, pinned, with every channel split."""
+    monkeypatch.setenv("SCONV_VARIANT", "quad")
+    monkeypatch.setenv("SCONV_QUAD_GEOM", "q32t7")
+    if split:
+        monkeypatch.setenv("SCONV_QUAD_SPLIT", split)
+    layer, x, w = _mk(160, shp)
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    layer, x, w = _mk(161, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+
+
 @pytest.mark.parametrize("shp", WIDE)
 def test_wide_variant(device, monkeypatch, shp):
     monkeypatch.setenv("SCONV_VARIANT", "wide")
