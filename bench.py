@@ -46,6 +46,7 @@ MEASURED_TRAFFIC = {
     ("quad3x3", "vgg-256x56", 8): 147.1e6 + 25.7e6,      # profiles/quad3x3_vgg-256x56_n8.txt
 }
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
+TUNE = True                   # --no-tune: the static dispatch rules and cost models only
 CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
 
 
@@ -99,7 +100,13 @@ class DeviceLayer:
                 y = sconv.sconv_forward(xs, ws, layer.stride, layer.pad, layer.groups, relu=True)
             self.sets.append((xs, ws, y))
         d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+        if TUNE:
+            # set-up, outside every timed region: the library times its variants and decompositions on
+            # this layer's operands and remembers the fastest for this descriptor
+            xs, ws, y = self.sets[0]
+            sconv.sconv_tune(xs, ws, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, out=y)
         self.variant = sconv.sconv_variant_name(d, bool(layer.pool))
+        self.plan = sconv.sconv_plan_name(d, bool(layer.pool))
         self.i = 0
 
     def run(self):
@@ -132,7 +139,7 @@ def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
     t_hbm = work["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_valu = work["nz_flops"] / (FP32_VECTOR_PEAK_TF * 1e12)
     return {
-        "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "ms": round(ms, 5),
+        "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "plan": dl.plan, "ms": round(ms, 5),
         "zero_ratio": round(work["zero_ratio"], 4),
         "dense_equiv_gflops": round(work["dense_flops"] / t / 1e9, 1),
         "nonzero_mac_gflops": round(work["nz_flops"] / t / 1e9, 1),
@@ -463,6 +470,8 @@ def main() -> None:
     ap.add_argument("--graph", action="store_true",
                     help="one step of --config at --batch (default: its smallest) eagerly and as a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="skip sconv_tune at set-up: static dispatch rules and cost models only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
     ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
@@ -471,6 +480,8 @@ def main() -> None:
                     help="zero pattern of the input for --sweep / --layer: independent zeros, or dead "
                          "planes plus spatial patches at the same overall ratio")
     args = ap.parse_args()
+    global TUNE
+    TUNE = not args.no_tune and not os.environ.get("SCONV_VARIANT")
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part (images or filters would "
                  "simply be split across devices with no exchange); run with --gpus 1")

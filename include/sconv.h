@@ -128,10 +128,42 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  * preferred for maps up to 7x7 and for launches too small to fill the matrix kernels' tiles),
  * "gen" (every other shape with a kernel of at most 15x15 and, when pooling, a 2x2 / stride 2
  * window), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
- * "quad", "wide", "gen" or unset) pins the choice for profiling.
+ * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes
+ * before the static rules.
  * Returns NULL for an invalid descriptor.  Host only.
  */
 const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
+
+/*
+ * Run-time choice of the kernel.  Which variant and decomposition is fastest depends on the zero
+ * ratio of the map (Section 8's sparsity sweep: the vector kernel's time falls with the ratio, the
+ * matrix kernels' only once whole groups are zero), which the host does not know.  sconv_tune runs
+ * every variant and every decomposition that covers the descriptor on the caller's operands - each
+ * one untimed launch and three timed ones between two events on hip_stream - and remembers the
+ * fastest for this exact descriptor (and pooled flag) in a host-side table; later sconv_forward /
+ * sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
+ * models' choice.  The table is per process, guarded by the library's lock, and holds no device
+ * memory.
+ *   pooled != 0: tune sconv_pool_forward (y_dev is [N][K][PH][PW]), else sconv_forward.
+ *   x_dev, w_dev device, in; y_dev device, out: overwritten many times, left holding the result.
+ *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.
+ * Unlike every other call this one SYNCHRONISES with hip_stream (it reads event times), so it
+ * must not be called while the stream is being captured into a graph; call it once at set-up.
+ * The operands stay in the caches between its launches, so it ranks plans cache-warm.
+ * SCONV_VARIANT, when set, overrides the table.  Errors as sconv_forward.
+ */
+int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
+               float* y_dev, void* hip_stream, float* best_ms);
+
+/* Forgets every tuned plan.  Host only. */
+int sconv_tune_reset(void);
+
+/*
+ * Writes the plan the forward calls would launch for this descriptor into out (NUL-terminated,
+ * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices) for a
+ * tuned descriptor, "variant/model" otherwise.  Host only.
+ */
+int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size);
 
 /* Static description of an error code. */
 const char* sconv_strerror(int code);

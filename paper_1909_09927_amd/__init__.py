@@ -57,10 +57,13 @@ def lib() -> ctypes.CDLL:
         L.sconv_maxpool.argtypes = [P(Desc), vp, vp, vp]
         L.sconv_variant_name.argtypes = [P(Desc), ctypes.c_int]
         L.sconv_variant_name.restype = ctypes.c_char_p
+        L.sconv_tune.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, P(ctypes.c_float)]
+        L.sconv_tune_reset.argtypes = []
+        L.sconv_plan_name.argtypes = [P(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
         L.sconv_strerror.argtypes = [ctypes.c_int]
         L.sconv_strerror.restype = ctypes.c_char_p
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
-                  "sconv_pool_forward", "sconv_maxpool"):
+                  "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -103,6 +106,18 @@ def sconv_encode_sizes(desc: Desc, fmt: int) -> Tuple[int, int]:
 def sconv_variant_name(desc: Desc, pooled: bool = False) -> Optional[str]:
     s = lib().sconv_variant_name(ctypes.byref(desc), 1 if pooled else 0)
     return s.decode() if s is not None else None
+
+
+def sconv_plan_name(desc: Desc, pooled: bool = False) -> str:
+    buf = ctypes.create_string_buffer(64)
+    rc = lib().sconv_plan_name(ctypes.byref(desc), 1 if pooled else 0, buf, len(buf))
+    if rc:
+        raise SconvError(rc, "sconv_plan_name")
+    return buf.value.decode()
+
+
+def sconv_tune_reset() -> None:
+    lib().sconv_tune_reset()
 
 
 def _check_dev(t, dtype, what):
@@ -201,3 +216,28 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None):
     if rc:
         raise SconvError(rc, "sconv_pool_forward")
     return out
+
+
+def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None):
+    """Times every kernel variant and decomposition covering this call on x and w (synchronises)
+    and makes later identical calls use the fastest.  pool=None tunes sconv_forward (with this
+    relu flag), else sconv_pool_forward.  Returns (milliseconds of the chosen plan, plan name)."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    _check_dev(w, torch.float32, "w")
+    pooled = pool is not None
+    desc = desc_for(x, w, stride, pad, groups, pool, True if pooled else relu)
+    OH, OW, PH, PW = sconv_output_dims(desc)
+    shape = (desc.N, desc.K, PH, PW) if pooled else (desc.N, desc.K, OH, OW)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    else:
+        _check_dev(out, torch.float32, "out")
+        if tuple(out.shape) != shape:
+            raise ValueError("out has the wrong shape")
+    ms = ctypes.c_float(0.0)
+    rc = lib().sconv_tune(ctypes.byref(desc), 1 if pooled else 0, x.data_ptr(), w.data_ptr(), out.data_ptr(),
+                          _stream(), ctypes.byref(ms))
+    if rc:
+        raise SconvError(rc, "sconv_tune")
+    return float(ms.value), sconv_plan_name(desc, pooled)

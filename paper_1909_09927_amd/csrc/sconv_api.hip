@@ -1,12 +1,39 @@
 // Host side of libsconv: argument checks, size helpers, variant choice.  No device code here.
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
+#include <array>
+#include <map>
 #include <mutex>
 
 #include "sconv_internal.h"
 
 namespace sconv {
+
+// The pin of the launch in progress.  Written and read under the dispatcher's lock only.
+static const PlanPin* g_pin = nullptr;
+
+const PlanPin* current_pin() { return g_pin; }
+
+const char* pinned_geom(const char* env_name)
+{
+    if (g_pin) return g_pin->geom[0] ? g_pin->geom : nullptr;
+    return getenv(env_name);
+}
+
+void pinned_split(const char* env_name, int* nwv, int* ncs)
+{
+    *nwv = *ncs = 0;
+    if (g_pin) {
+        *nwv = g_pin->nwv;
+        *ncs = g_pin->ncs;
+        return;
+    }
+    if (const char* pin = getenv(env_name)) {
+        if (sscanf(pin, "%d,%d", nwv, ncs) != 2) *nwv = *ncs = 0;
+    }
+}
 
 static bool mul_fits_31(int64_t a, int64_t b, int64_t c, int64_t d)
 {
@@ -59,6 +86,44 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
 
 enum Variant { V_ROWS, V_TAP, V_QUAD, V_PW, V_WIDE, V_GEN };
 
+static const char* variant_name(Variant v)
+{
+    switch (v) {
+    case V_PW: return "quad1x1";
+    case V_QUAD: return "quad3x3";
+    case V_TAP: return "tap3x3";
+    case V_WIDE: return "wide3x3";
+    case V_GEN: return "gen";
+    default: return "rows";
+    }
+}
+
+// What sconv_tune found fastest for one descriptor: a variant and its decomposition.
+struct Tuned {
+    Variant v;
+    PlanPin pin;
+    float ms;
+    char name[48];
+};
+typedef std::array<int32_t, 15> TuneKey;   // the descriptor's fields and the pooled flag
+
+static std::mutex g_lock;                  // planning, enqueueing and the tuning cache
+static std::map<TuneKey, Tuned> g_tuned;
+
+static TuneKey tune_key(const Problem& p, bool pooled)
+{
+    return TuneKey{p.N, p.C, p.H, p.W, p.K, p.R, p.S, p.stride, p.pad, p.G,
+                   pooled ? p.ph : 0, pooled ? p.pw : 0, pooled ? p.ps : 0, p.relu, pooled ? 1 : 0};
+}
+
+// The tuned entry for this problem, unless SCONV_VARIANT pins the variant.  Caller holds g_lock.
+static const Tuned* tuned_for(const Problem& p, bool pooled)
+{
+    if (getenv("SCONV_VARIANT")) return nullptr;
+    auto it = g_tuned.find(tune_key(p, pooled));
+    return it == g_tuned.end() ? nullptr : &it->second;
+}
+
 static Variant choose(const Problem& p, bool pooled)
 {
     const char* pin = getenv("SCONV_VARIANT");
@@ -77,9 +142,15 @@ static Variant choose(const Problem& p, bool pooled)
         // Maps of 7x7 and below are one whole-map tile of the vector kernel (no halo, no ragged
         // tiles); it measures 1.4-1.8x faster there than either matrix kernel.
         if (p.H <= 7 && p.W <= 7 && tap_supported(p, pooled)) return V_TAP;
-        // Small maps with many filters: the 16-row granule has no tile-geometry waste there and
-        // measures faster; everywhere else the 4-row granule skips more and wins.
-        if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
+        // Maps up to 14 wide with 256 or more channels per group are the deep layers, whose zero
+        // ratio the paper puts above 0.7 (Fig. 2): there per-element skipping on the vector pipe
+        // measures 1.0-1.15x faster than the 6-element granule from 70 % zeros up (and 1.1x slower
+        // at 60 %).
+        if (p.W <= 14 && p.Cg >= 256 && tap_supported(p, pooled)) return V_TAP;
+        // Small maps with many filters and short channel loops: the 16-row granule has no
+        // tile-geometry waste there and measures faster up to 65 % zeros; with 256 or more
+        // channels the 6-element granule measures faster at every ratio from 60 % up.
+        if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills) return V_WIDE;
         // Few tile-wavefronts (2 output rows x 28 columns x 64 filters each): the vector kernel's
         // smaller tiles spread over more of the chip and measure faster at small batch.
         const long long quad_tiles = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
@@ -96,28 +167,146 @@ static Variant choose(const Problem& p, bool pooled)
     return V_ROWS;
 }
 
-static int run(Variant v, const Problem& p, bool pooled, const float* x, const float* w, float* y,
-               hipStream_t s)
+// One launch of variant v, with the cost models' decomposition or the pinned one.  No fall-through
+// to other variants.  Caller holds g_lock.
+static int launch_variant(Variant v, const PlanPin* pin, const Problem& p, bool pooled, const float* x,
+                          const float* w, float* y, hipStream_t s)
+{
+    g_pin = pin;
+    int rc = SCONV_EUNSUPPORTED;
+    switch (v) {
+    case V_PW: rc = launch_pointwise(p, pooled, x, w, y, s); break;
+    case V_GEN: rc = launch_gen(p, pooled, x, w, y, s); break;
+    case V_WIDE: rc = launch_wide(p, pooled, x, w, y, s); break;
+    case V_QUAD: rc = launch_quad(p, pooled, x, w, y, s); break;
+    case V_TAP: rc = tap_supported(p, pooled) ? launch_tap(p, pooled, x, w, y, s) : SCONV_EUNSUPPORTED; break;
+    case V_ROWS: rc = launch_rows(p, pooled, x, w, y, s); break;
+    }
+    g_pin = nullptr;
+    return rc;
+}
+
+static int run(const Problem& p, bool pooled, const float* x, const float* w, float* y, hipStream_t s)
 {
     // the launchers cache occupancy answers and attribute opt-ins in static variables: planning and
     // enqueueing are serialised across host threads (they take microseconds)
-    static std::mutex guard;
-    std::lock_guard<std::mutex> lock(guard);
+    std::lock_guard<std::mutex> lock(g_lock);
+    if (const Tuned* t = tuned_for(p, pooled)) {
+        const int rc = launch_variant(t->v, &t->pin, p, pooled, x, w, y, s);
+        if (rc != SCONV_EUNSUPPORTED) return rc;
+    }
+    Variant v = choose(p, pooled);
     int rc = SCONV_EUNSUPPORTED;
-    if (v == V_PW) rc = launch_pointwise(p, pooled, x, w, y, s);
-    if (v == V_GEN) rc = launch_gen(p, pooled, x, w, y, s);
+    if (v == V_PW) rc = launch_variant(V_PW, nullptr, p, pooled, x, w, y, s);
+    if (v == V_GEN) rc = launch_variant(V_GEN, nullptr, p, pooled, x, w, y, s);
     if (v == V_WIDE) {
-        rc = launch_wide(p, pooled, x, w, y, s);
+        rc = launch_variant(V_WIDE, nullptr, p, pooled, x, w, y, s);
         if (rc == SCONV_EUNSUPPORTED) v = quad_supported(p, pooled) ? V_QUAD : V_TAP;
     }
     if (v == V_QUAD) {
-        rc = launch_quad(p, pooled, x, w, y, s);
+        rc = launch_variant(V_QUAD, nullptr, p, pooled, x, w, y, s);
         if (rc == SCONV_EUNSUPPORTED) v = V_TAP;
     }
-    if (v == V_TAP && tap_supported(p, pooled)) rc = launch_tap(p, pooled, x, w, y, s);
+    if (v == V_TAP) rc = launch_variant(V_TAP, nullptr, p, pooled, x, w, y, s);
     // no applicable tile plan: the general kernel runs
-    if (rc == SCONV_EUNSUPPORTED) rc = launch_rows(p, pooled, x, w, y, s);
+    if (rc == SCONV_EUNSUPPORTED) rc = launch_variant(V_ROWS, nullptr, p, pooled, x, w, y, s);
     return rc;
+}
+
+// Times one candidate: one untimed launch (also tells whether the candidate applies), then `reps`
+// launches between two events on the stream.  Returns a negative time when it does not apply.
+static float time_candidate(Variant v, const PlanPin* pin, const Problem& p, bool pooled, const float* x,
+                            const float* w, float* y, hipStream_t s, hipEvent_t e0, hipEvent_t e1, int reps,
+                            int* err)
+{
+    int rc = launch_variant(v, pin, p, pooled, x, w, y, s);
+    if (rc == SCONV_EUNSUPPORTED) return -1.0f;
+    if (rc != SCONV_OK) { *err = rc; return -1.0f; }
+    if (hipEventRecord(e0, s) != hipSuccess) { *err = SCONV_ELAUNCH; return -1.0f; }
+    for (int i = 0; i < reps; ++i) {
+        rc = launch_variant(v, pin, p, pooled, x, w, y, s);
+        if (rc != SCONV_OK) { *err = rc; return -1.0f; }
+    }
+    float ms = 0.0f;
+    if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+        *err = SCONV_ELAUNCH;
+        return -1.0f;
+    }
+    return ms / reps;
+}
+
+static int tune(const Problem& p, bool pooled, const float* x, const float* w, float* y, hipStream_t s,
+                float* best_ms)
+{
+    std::lock_guard<std::mutex> lock(g_lock);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return SCONV_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SCONV_ELAUNCH; }
+    struct Family {
+        Variant v;
+        bool ok;
+        const char* const* geoms;
+        int nwv_lo, nwv_hi;
+    };
+    static const char* const no_geoms[] = {"", nullptr};
+    const Family fams[] = {
+        {V_PW, pw_supported(p, pooled), no_geoms, 8, 16},
+        {V_TAP, tap_supported(p, pooled), tap_geoms(), 8, 16},
+        {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16},
+        {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8},
+        {V_GEN, gen_supported(p, pooled), gen_geoms(), 4, 8},
+    };
+    Tuned best;
+    best.ms = -1.0f;
+    int err = SCONV_OK;
+    const int reps = 3;
+    auto consider = [&](Variant v, const PlanPin* pin, float ms) {
+        if (ms < 0.0f || (best.ms >= 0.0f && ms >= best.ms)) return;
+        best.v = v;
+        best.ms = ms;
+        if (pin) {
+            best.pin = *pin;
+            snprintf(best.name, sizeof(best.name), "%s/%s/%dx%d", variant_name(v), pin->geom[0] ? pin->geom : "-",
+                     pin->nwv, pin->ncs);
+        } else {
+            memset(&best.pin, 0, sizeof(best.pin));
+            snprintf(best.name, sizeof(best.name), "%s/model", variant_name(v));
+        }
+    };
+    for (const Family& f : fams) {
+        if (!f.ok || err != SCONV_OK) continue;
+        for (const char* const* g = f.geoms; *g && err == SCONV_OK; ++g) {
+            // the model's own split of this geometry first: a geometry that does not apply is
+            // dropped after one call
+            PlanPin pin;
+            memset(&pin, 0, sizeof(pin));
+            snprintf(pin.geom, sizeof(pin.geom), "%s", *g);
+            const float t_model = time_candidate(f.v, &pin, p, pooled, x, w, y, s, e0, e1, reps, &err);
+            if (t_model < 0.0f) continue;
+            consider(f.v, &pin, t_model);
+            for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
+                for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
+                    pin.nwv = nwv;
+                    pin.ncs = ncs;
+                    const float t = time_candidate(f.v, &pin, p, pooled, x, w, y, s, e0, e1, reps, &err);
+                    consider(f.v, &pin, t);
+                }
+            }
+        }
+    }
+    if (err == SCONV_OK && best.ms < 0.0f) {
+        // nothing but the general kernel covers this shape
+        const float t = time_candidate(V_ROWS, nullptr, p, pooled, x, w, y, s, e0, e1, reps, &err);
+        consider(V_ROWS, nullptr, t);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (err != SCONV_OK) return err;
+    if (best.ms < 0.0f) return SCONV_EUNSUPPORTED;
+    g_tuned[tune_key(p, pooled)] = best;
+    if (best_ms) *best_ms = best.ms;
+    return SCONV_OK;
 }
 
 }  // namespace sconv
@@ -179,7 +368,7 @@ extern "C" int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const
     Problem p;
     int rc = fill_problem(desc, false, &p);
     if (rc) return rc;
-    return run(choose(p, false), p, false, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
+    return run(p, false, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
 extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
@@ -190,7 +379,7 @@ extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, 
     int rc = fill_problem(desc, true, &p);
     if (rc) return rc;
     if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
-    return run(choose(p, true), p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
+    return run(p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
 extern "C" int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
@@ -207,14 +396,41 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
 {
     Problem p;
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
-    switch (choose(p, pooled != 0)) {
-    case V_PW: return "quad1x1";
-    case V_QUAD: return "quad3x3";
-    case V_TAP: return "tap3x3";
-    case V_WIDE: return "wide3x3";
-    case V_GEN: return "gen";
-    default: return "rows";
-    }
+    std::lock_guard<std::mutex> lock(g_lock);
+    if (const Tuned* t = tuned_for(p, pooled != 0)) return variant_name(t->v);
+    return variant_name(choose(p, pooled != 0));
+}
+
+extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
+                          float* y_dev, void* hip_stream, float* best_ms)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, pooled != 0, &p);
+    if (rc) return rc;
+    if (pooled && (int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    return tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, best_ms);
+}
+
+extern "C" int sconv_tune_reset(void)
+{
+    std::lock_guard<std::mutex> lock(g_lock);
+    g_tuned.clear();
+    return SCONV_OK;
+}
+
+extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size)
+{
+    if (!out || out_size <= 0) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, pooled != 0, &p);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lock(g_lock);
+    if (const Tuned* t = tuned_for(p, pooled != 0))
+        snprintf(out, (size_t)out_size, "%s", t->name);
+    else
+        snprintf(out, (size_t)out_size, "%s/model", variant_name(choose(p, pooled != 0)));
+    return SCONV_OK;
 }
 
 extern "C" const char* sconv_strerror(int code)

@@ -251,9 +251,7 @@ Plan plan_geom(const Problem& p)
     const double stage_clocks = (double)KB * nchunks * CW * 4.0 / 64.0;
 
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_GEN_SPLIT="nwv,ncs"
-    if (const char* pin = getenv("SCONV_GEN_SPLIT")) {
-        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
-    }
+    pinned_split("SCONV_GEN_SPLIT", &pin_nwv, &pin_ncs);
     for (int nwv = 4; nwv <= 8; nwv *= 2) {
         if (KPL == 2 && nwv == 4) continue;      // 32 staging registers per thread: not built
         for (int ncs = 1; ncs <= 4; ncs *= 2) {
@@ -354,13 +352,19 @@ const Candidate kCandidates[] = {
 
 }  // namespace
 
+const char* const* gen_geoms()
+{
+    static const char* const names[] = {"gk1", "gk2", "gpk1", "gpk2", nullptr};
+    return names;
+}
+
 bool gen_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
 int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t stream)
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
-    const char* pin = getenv("SCONV_GEN_GEOM");   // tuning aid: candidate name
+    const char* pin = pinned_geom("SCONV_GEN_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {

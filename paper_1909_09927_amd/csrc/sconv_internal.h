@@ -61,6 +61,27 @@ bool pw_supported(const Problem& p, bool pooled);
 int launch_pointwise(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                      hipStream_t stream);
 
+// A fixed decomposition in place of the cost models' choice: candidate geometry inside a kernel
+// variant, wavefronts per workgroup, channel slices.  Set by the dispatcher (under its lock) around
+// one launch - from the tuning cache or while sconv_tune tries the candidates; without one, the
+// tuning-aid environment variables apply.
+struct PlanPin {
+    char geom[16];       // "" = any geometry
+    int nwv, ncs;        // 0 = the model's choice
+};
+const PlanPin* current_pin();
+
+// Geometry pin for a launcher: the dispatcher's, else the named environment variable's.
+const char* pinned_geom(const char* env_name);
+// Split pin "nwv,ncs" likewise; both 0 when there is none.
+void pinned_split(const char* env_name, int* nwv, int* ncs);
+
+// Candidate geometry names of the variants (for sconv_tune); null-terminated arrays.
+const char* const* tap_geoms();
+const char* const* quad_geoms();
+const char* const* wide_geoms();
+const char* const* gen_geoms();
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? SCONV_OK : SCONV_ELAUNCH;

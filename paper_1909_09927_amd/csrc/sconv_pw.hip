@@ -329,9 +329,7 @@ int launch_pw(const Problem& p, const float* x, const float* w, float* y, hipStr
     const double stage_clocks = (double)KB * p.Cg * 4.0 / 64.0;
 
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_PW_SPLIT="nwv,ncs"
-    if (const char* pin = getenv("SCONV_PW_SPLIT")) {
-        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
-    }
+    pinned_split("SCONV_PW_SPLIT", &pin_nwv, &pin_ncs);
     double best = -1.0;
     int best_nwv = 0;
     size_t lds_bytes = stage_bytes;

@@ -412,9 +412,7 @@ Plan plan_geom(const Problem& p)
     const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_QUAD_SPLIT="nwv,ncs"
-    if (const char* pin = getenv("SCONV_QUAD_SPLIT")) {
-        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
-    }
+    pinned_split("SCONV_QUAD_SPLIT", &pin_nwv, &pin_ncs);
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
@@ -507,13 +505,19 @@ const Candidate kCandidates[] = {
 
 }  // namespace
 
+const char* const* quad_geoms()
+{
+    static const char* const names[] = {"q32k1", "q32k2", "q32t7", "q16k2", "qp32k1", "qp16k2", nullptr};
+    return names;
+}
+
 bool quad_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
 int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
-    const char* pin = getenv("SCONV_QUAD_GEOM");   // tuning aid: candidate name, or !name to exclude one
+    const char* pin = pinned_geom("SCONV_QUAD_GEOM");   // tuning aid: candidate name, or !name to exclude one
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {

@@ -91,14 +91,32 @@ __device__ __forceinline__ void position(const unsigned (&mask)[2 * G::NX],
     }
 }
 
-template <class G, int... Ps>
-__device__ __forceinline__ void all_positions(std::integer_sequence<int, Ps...>,
+// Four consecutive positions: one scalar test of their four mask bits first.  With 70 % zeros or
+// more a quarter or more of the groups is empty and costs one test instead of four.
+template <class G, int P4>
+__device__ __forceinline__ void position_group(const unsigned (&mask)[2 * G::NX],
+                                               const float (&xv)[G::NX], float (&acc)[G::KPL][G::ACC],
+                                               const float (&wr)[G::KPL][9])
+{
+    constexpr int P0 = 4 * P4;
+    constexpr int cnt = (P0 + 4 <= G::NPOS) ? 4 : G::NPOS - P0;
+    constexpr unsigned bits = ((1u << cnt) - 1u) << (P0 % 32);   // P0 % 4 == 0: one mask word
+    if (mask[P0 / 32] & bits) {
+        position<G, P0>(mask, xv, acc, wr);
+        if constexpr (cnt > 1) position<G, P0 + 1>(mask, xv, acc, wr);
+        if constexpr (cnt > 2) position<G, P0 + 2>(mask, xv, acc, wr);
+        if constexpr (cnt > 3) position<G, P0 + 3>(mask, xv, acc, wr);
+    }
+}
+
+template <class G, int... P4s>
+__device__ __forceinline__ void all_positions(std::integer_sequence<int, P4s...>,
                                               const unsigned (&mask)[2 * G::NX],
                                               const float (&xv)[G::NX],
                                               float (&acc)[G::KPL][G::ACC],
                                               const float (&wr)[G::KPL][9])
 {
-    (position<G, Ps>(mask, xv, acc, wr), ...);
+    (position_group<G, P4s>(mask, xv, acc, wr), ...);
 }
 
 template <class G, int NWV>
@@ -209,7 +227,7 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
                 for (int j = 0; j < 9; ++j)
 #pragma unroll
                     for (int i = 0; i < G::KPL; ++i) wr[i][j] = wl[j * G::KBP + 64 * i];
-                all_positions<G>(std::make_integer_sequence<int, G::NPOS>{}, mask, xv, acc, wr);
+                all_positions<G>(std::make_integer_sequence<int, (G::NPOS + 3) / 4>{}, mask, xv, acc, wr);
             }
         }
     }
@@ -344,9 +362,7 @@ Plan plan_geom(const Problem& p)
     const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_TAP_SPLIT="nwv,ncs"
-    if (const char* pin = getenv("SCONV_TAP_SPLIT")) {
-        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
-    }
+    pinned_split("SCONV_TAP_SPLIT", &pin_nwv, &pin_ncs);
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
@@ -439,13 +455,19 @@ const Candidate kCandidates[] = {
 
 }  // namespace
 
+const char* const* tap_geoms()
+{
+    static const char* const names[] = {"5x7k1", "5x7k2", "7x7k1", "7x7k2", "p4x14k1", "p4x14k2", "p4x6k1", "p4x6k2", "s2-3x4k1", "s2-3x4k2", nullptr};
+    return names;
+}
+
 bool tap_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
 int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t stream)
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
-    const char* pin = getenv("SCONV_TAP_GEOM");   // tuning aid: candidate name
+    const char* pin = pinned_geom("SCONV_TAP_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {

@@ -244,9 +244,7 @@ Plan plan_geom(const Problem& p)
     const double stage_clocks = (double)G::KB * p.Cg * G::T * 4.0 / 64.0;
 
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_WIDE_SPLIT="nwv,ncs"
-    if (const char* pin = getenv("SCONV_WIDE_SPLIT")) {
-        if (sscanf(pin, "%d,%d", &pin_nwv, &pin_ncs) != 2) pin_nwv = pin_ncs = 0;
-    }
+    pinned_split("SCONV_WIDE_SPLIT", &pin_nwv, &pin_ncs);
     for (int nwv = 4; nwv <= 8; nwv *= 2) {
         if (nwv * 64 < G::KB || G::ROWS % (nwv * 64 / G::KB)) continue;
         for (int ncs = 1; ncs <= 4 && 2 * ncs <= G::CCH; ncs *= 2) {   // an even number of channels per slice
@@ -329,6 +327,12 @@ const Candidate kCandidates[] = {
 
 }  // namespace
 
+const char* const* wide_geoms()
+{
+    static const char* const names[] = {"w33k1", "w33k2", "wp33k1", "wp33k2", nullptr};
+    return names;
+}
+
 bool wide_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
 int launch_wide(const Problem& p, bool pooled, const float* x, const float* w, float* y,
@@ -336,7 +340,7 @@ int launch_wide(const Problem& p, bool pooled, const float* x, const float* w, f
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
     if (reinterpret_cast<uintptr_t>(w) & 15) return SCONV_EUNSUPPORTED;   // filter staging loads 16 bytes
-    const char* pin = getenv("SCONV_WIDE_GEOM");   // tuning aid: candidate name
+    const char* pin = pinned_geom("SCONV_WIDE_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {

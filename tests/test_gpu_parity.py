@@ -373,6 +373,46 @@ def test_random_shapes_through_the_default_dispatch(device, shp):
     check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
+@pytest.mark.parametrize("shp", [
+    (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # tap / quad / wide / gen all apply
+    (1, 128, 28, 28, 128, 1, 1, 1, 0, 1, (2, 2, 2)),     # quad1x1 / gen
+    (2, 20, 12, 12, 50, 5, 5, 1, 2, 1, (2, 2, 2)),       # gen only
+    (2, 64, 30, 30, 96, 3, 3, 2, 1, 1, None),            # stride 2: tap / wide / gen
+    (1, 8, 40, 40, 16, 3, 3, 1, 1, 1, (7, 7, 3)),        # pooled: only the general kernel covers 7x7 windows
+])
+def test_tuned_plans_meet_the_same_bars(device, monkeypatch, shp):
+    """sconv_tune picks whichever variant and decomposition measures fastest on the operands; the
+    calls that follow launch it and must meet the parity bars; resetting brings the model back."""
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    sconv.sconv_tune_reset()
+    try:
+        layer, x, w = _mk(170, shp)
+        xd, wd = to_dev(x), to_dev(w)
+        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, None, True)
+        assert sconv.sconv_plan_name(d).endswith("/model")
+        ms, plan = sconv.sconv_tune(xd, wd, layer.stride, layer.pad, layer.groups, None, relu=True)
+        assert ms > 0 and plan == sconv.sconv_plan_name(d)
+        assert plan.split("/")[0] == sconv.sconv_variant_name(d)
+        check_forward(layer, x, w, relu=True)
+        # relu=False is another descriptor: untouched by the tuning above
+        d0 = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, None, False)
+        assert sconv.sconv_plan_name(d0).endswith("/model")
+        check_forward(layer, x, w, relu=False)
+        if layer.pool:
+            dp = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+            ms, plan = sconv.sconv_tune(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool)
+            assert ms > 0 and plan == sconv.sconv_plan_name(dp, True)
+            check_pool_forward(layer, x, w)
+        layer, x, w = _mk(171, shp, integer=True)
+        check_forward(layer, x, w, relu=True, integer_exact=False)
+        check_forward(layer, x, w, relu=False, integer_exact=True)
+        if layer.pool:
+            check_pool_forward(layer, x, w, integer_exact=True)
+    finally:
+        sconv.sconv_tune_reset()
+    assert sconv.sconv_plan_name(d).endswith("/model")
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)

@@ -17,7 +17,8 @@ def test_library_exports_every_declared_symbol():
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(sconv_[a-z_]+)\s*\(", text))
     assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
-            "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool"} <= names
+            "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool", "sconv_tune",
+            "sconv_tune_reset", "sconv_plan_name"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
@@ -111,6 +112,23 @@ def test_strerror_and_variant_name():
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 5, 5, 1, 2)) == "gen"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1, pool=(3, 3, 2)), True) == "rows"
     assert sconv.sconv_variant_name(sconv.Desc()) is None
+
+
+def test_tuning_calls_validate_on_the_host():
+    L = sconv.lib()
+    d = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1)
+    p = ctypes.c_void_p(16)
+    assert L.sconv_tune(ctypes.byref(d), 0, None, p, p, None, None) == sconv.SCONV_EINVAL
+    bad = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 0, 1)
+    assert L.sconv_tune(ctypes.byref(bad), 0, p, p, p, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_tune(ctypes.byref(d), 1, p, p, p, None, None) == sconv.SCONV_EINVAL   # no pooling fields
+    assert L.sconv_tune_reset() == 0
+    assert sconv.sconv_plan_name(d) == "tap3x3/model"
+    assert sconv.sconv_plan_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3/model"
+    buf = ctypes.create_string_buffer(4)
+    assert L.sconv_plan_name(ctypes.byref(d), 0, buf, 4) == 0 and buf.value == b"tap"
+    assert L.sconv_plan_name(ctypes.byref(d), 0, None, 4) == sconv.SCONV_EINVAL
+    assert L.sconv_plan_name(ctypes.byref(bad), 0, buf, 4) == sconv.SCONV_EINVAL
 
 
 def test_binding_refuses_host_tensors():
