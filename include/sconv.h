@@ -146,14 +146,18 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  * memory.
  *   pooled != 0: tune sconv_pool_forward (y_dev is [N][K][PH][PW]), else sconv_forward.
  *   x_dev, w_dev device, in; y_dev device, out: overwritten many times, left holding the result.
+ *   flush_dev device, scratch, optional (NULL with flush_bytes 0): when given, its flush_bytes
+ *            bytes are overwritten before every timed launch, so that no launch finds its operands
+ *            in the caches (give it at least twice the last-level cache, 512 MiB); without it the
+ *            launches run back to back and plans are ranked cache-warm.  The library never
+ *            allocates: the scratch is the caller's and only used during this call.
  *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.
  * Unlike every other call this one SYNCHRONISES with hip_stream (it reads event times), so it
  * must not be called while the stream is being captured into a graph; call it once at set-up.
- * The operands stay in the caches between its launches, so it ranks plans cache-warm.
  * SCONV_VARIANT, when set, overrides the table.  Errors as sconv_forward.
  */
 int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
-               float* y_dev, void* hip_stream, float* best_ms);
+               float* y_dev, void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms);
 
 /* Forgets every tuned plan.  Host only. */
 int sconv_tune_reset(void);

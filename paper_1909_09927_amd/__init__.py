@@ -57,7 +57,7 @@ def lib() -> ctypes.CDLL:
         L.sconv_maxpool.argtypes = [P(Desc), vp, vp, vp]
         L.sconv_variant_name.argtypes = [P(Desc), ctypes.c_int]
         L.sconv_variant_name.restype = ctypes.c_char_p
-        L.sconv_tune.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, P(ctypes.c_float)]
+        L.sconv_tune.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, ctypes.c_size_t, vp, P(ctypes.c_float)]
         L.sconv_tune_reset.argtypes = []
         L.sconv_plan_name.argtypes = [P(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
         L.sconv_strerror.argtypes = [ctypes.c_int]
@@ -218,10 +218,12 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None):
     return out
 
 
-def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None):
+def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None, flush=None):
     """Times every kernel variant and decomposition covering this call on x and w (synchronises)
     and makes later identical calls use the fastest.  pool=None tunes sconv_forward (with this
-    relu flag), else sconv_pool_forward.  Returns (milliseconds of the chosen plan, plan name)."""
+    relu flag), else sconv_pool_forward.  flush: a device tensor the library may overwrite to evict
+    the caches before every timed launch (cold ranking); None ranks cache-warm.
+    Returns (milliseconds of the chosen plan, plan name)."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -236,8 +238,13 @@ def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None)
         if tuple(out.shape) != shape:
             raise ValueError("out has the wrong shape")
     ms = ctypes.c_float(0.0)
+    fptr, fbytes = (None, 0)
+    if flush is not None:
+        if not (isinstance(flush, torch.Tensor) and flush.is_cuda and flush.is_contiguous()):
+            raise TypeError("flush must be a contiguous tensor in device memory")
+        fptr, fbytes = flush.data_ptr(), flush.numel() * flush.element_size()
     rc = lib().sconv_tune(ctypes.byref(desc), 1 if pooled else 0, x.data_ptr(), w.data_ptr(), out.data_ptr(),
-                          _stream(), ctypes.byref(ms))
+                          fptr, fbytes, _stream(), ctypes.byref(ms))
     if rc:
         raise SconvError(rc, "sconv_tune")
     return float(ms.value), sconv_plan_name(desc, pooled)

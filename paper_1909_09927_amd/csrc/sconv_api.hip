@@ -3,8 +3,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <array>
 #include <map>
+#include <vector>
 #include <mutex>
 
 #include "sconv_internal.h"
@@ -102,6 +104,7 @@ static const char* variant_name(Variant v)
 struct Tuned {
     Variant v;
     PlanPin pin;
+    bool pinned;          // false: the variant with its cost model's decomposition
     float ms;
     char name[48];
 };
@@ -192,7 +195,7 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
     // enqueueing are serialised across host threads (they take microseconds)
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled)) {
-        const int rc = launch_variant(t->v, &t->pin, p, pooled, x, w, y, s);
+        const int rc = launch_variant(t->v, t->pinned ? &t->pin : nullptr, p, pooled, x, w, y, s);
         if (rc != SCONV_EUNSUPPORTED) return rc;
     }
     Variant v = choose(p, pooled);
@@ -213,31 +216,45 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
     return rc;
 }
 
+// Scratch the caller lends to sconv_tune for evicting the caches between timed launches.
+struct Flush {
+    void* dev;
+    size_t bytes;
+};
+
 // Times one candidate: one untimed launch (also tells whether the candidate applies), then `reps`
-// launches between two events on the stream.  Returns a negative time when it does not apply.
+// launches.  Without a flush buffer they run back to back between two events (operands stay in the
+// caches); with one, the buffer is overwritten before every launch and each launch is timed on its
+// own.  Returns a negative time when the candidate does not apply.
 static float time_candidate(Variant v, const PlanPin* pin, const Problem& p, bool pooled, const float* x,
                             const float* w, float* y, hipStream_t s, hipEvent_t e0, hipEvent_t e1, int reps,
-                            int* err)
+                            const Flush& flush, int* err)
 {
     int rc = launch_variant(v, pin, p, pooled, x, w, y, s);
     if (rc == SCONV_EUNSUPPORTED) return -1.0f;
     if (rc != SCONV_OK) { *err = rc; return -1.0f; }
-    if (hipEventRecord(e0, s) != hipSuccess) { *err = SCONV_ELAUNCH; return -1.0f; }
-    for (int i = 0; i < reps; ++i) {
-        rc = launch_variant(v, pin, p, pooled, x, w, y, s);
-        if (rc != SCONV_OK) { *err = rc; return -1.0f; }
+    float total = 0.0f;
+    const int rounds = flush.dev ? reps : 1, per_round = flush.dev ? 1 : reps;
+    for (int r = 0; r < rounds; ++r) {
+        if (flush.dev && hipMemsetAsync(flush.dev, r & 1, flush.bytes, s) != hipSuccess) { *err = SCONV_ELAUNCH; return -1.0f; }
+        if (hipEventRecord(e0, s) != hipSuccess) { *err = SCONV_ELAUNCH; return -1.0f; }
+        for (int i = 0; i < per_round; ++i) {
+            rc = launch_variant(v, pin, p, pooled, x, w, y, s);
+            if (rc != SCONV_OK) { *err = rc; return -1.0f; }
+        }
+        float ms = 0.0f;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            *err = SCONV_ELAUNCH;
+            return -1.0f;
+        }
+        total += ms;
     }
-    float ms = 0.0f;
-    if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-        hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
-        *err = SCONV_ELAUNCH;
-        return -1.0f;
-    }
-    return ms / reps;
+    return total / reps;
 }
 
 static int tune(const Problem& p, bool pooled, const float* x, const float* w, float* y, hipStream_t s,
-                float* best_ms)
+                const Flush& flush, float* best_ms)
 {
     std::lock_guard<std::mutex> lock(g_lock);
     hipEvent_t e0, e1;
@@ -257,22 +274,25 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8},
         {V_GEN, gen_supported(p, pooled), gen_geoms(), 4, 8},
     };
-    Tuned best;
-    best.ms = -1.0f;
+    // every candidate that applies, with a first quick timing
+    struct Cand {
+        Variant v;
+        PlanPin pin;
+        bool pinned;
+        float ms;
+    };
+    std::vector<Cand> cands;
     int err = SCONV_OK;
-    const int reps = 3;
-    auto consider = [&](Variant v, const PlanPin* pin, float ms) {
-        if (ms < 0.0f || (best.ms >= 0.0f && ms >= best.ms)) return;
-        best.v = v;
-        best.ms = ms;
-        if (pin) {
-            best.pin = *pin;
-            snprintf(best.name, sizeof(best.name), "%s/%s/%dx%d", variant_name(v), pin->geom[0] ? pin->geom : "-",
-                     pin->nwv, pin->ncs);
-        } else {
-            memset(&best.pin, 0, sizeof(best.pin));
-            snprintf(best.name, sizeof(best.name), "%s/model", variant_name(v));
-        }
+    auto try_one = [&](Variant v, const PlanPin* pin) {
+        const float t = time_candidate(v, pin, p, pooled, x, w, y, s, e0, e1, 3, flush, &err);
+        if (t < 0.0f) return false;
+        Cand c;
+        c.v = v;
+        c.pinned = pin != nullptr;
+        if (pin) c.pin = *pin; else memset(&c.pin, 0, sizeof(c.pin));
+        c.ms = t;
+        cands.push_back(c);
+        return true;
     };
     for (const Family& f : fams) {
         if (!f.ok || err != SCONV_OK) continue;
@@ -282,23 +302,43 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
             PlanPin pin;
             memset(&pin, 0, sizeof(pin));
             snprintf(pin.geom, sizeof(pin.geom), "%s", *g);
-            const float t_model = time_candidate(f.v, &pin, p, pooled, x, w, y, s, e0, e1, reps, &err);
-            if (t_model < 0.0f) continue;
-            consider(f.v, &pin, t_model);
+            if (!try_one(f.v, &pin)) continue;
             for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
                 for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
                     pin.nwv = nwv;
                     pin.ncs = ncs;
-                    const float t = time_candidate(f.v, &pin, p, pooled, x, w, y, s, e0, e1, reps, &err);
-                    consider(f.v, &pin, t);
+                    try_one(f.v, &pin);
                 }
             }
         }
     }
-    if (err == SCONV_OK && best.ms < 0.0f) {
-        // nothing but the general kernel covers this shape
-        const float t = time_candidate(V_ROWS, nullptr, p, pooled, x, w, y, s, e0, e1, reps, &err);
-        consider(V_ROWS, nullptr, t);
+    if (err == SCONV_OK && cands.empty()) try_one(V_ROWS, nullptr);   // only the general kernel covers it
+    // the four fastest again, long enough for the timing to be trusted (about a millisecond each)
+    Tuned best;
+    best.ms = -1.0f;
+    std::sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) { return a.ms < b.ms; });
+    for (size_t i = 0; i < cands.size() && i < 4 && err == SCONV_OK; ++i) {
+        const Cand& c = cands[i];
+        int reps = (int)(1.0f / (c.ms > 1e-3f ? c.ms : 1e-3f));
+        reps = reps < 5 ? 5 : (reps > 100 ? 100 : reps);
+        if (flush.dev && reps > 10) reps = 10;
+        const float t = time_candidate(c.v, c.pinned ? &c.pin : nullptr, p, pooled, x, w, y, s, e0, e1, reps, flush,
+                                       &err);
+        if (t < 0.0f || (best.ms >= 0.0f && t >= best.ms)) continue;
+        best.v = c.v;
+        best.ms = t;
+        best.pin = c.pin;
+        best.pinned = c.pinned;
+        if (c.pinned)
+            snprintf(best.name, sizeof(best.name), "%s/%s/%dx%d", variant_name(c.v), c.pin.geom[0] ? c.pin.geom : "-",
+                     c.pin.nwv, c.pin.ncs);
+        else
+            snprintf(best.name, sizeof(best.name), "%s/model", variant_name(c.v));
+    }
+    if (err == SCONV_OK && best.ms >= 0.0f) {
+        // leave y holding the result of the plan that later calls will launch
+        const int rc = launch_variant(best.v, best.pinned ? &best.pin : nullptr, p, pooled, x, w, y, s);
+        if (rc != SCONV_OK) err = rc;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
@@ -402,14 +442,15 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
 }
 
 extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
-                          float* y_dev, void* hip_stream, float* best_ms)
+                          float* y_dev, void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms)
 {
     if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    if ((flush_dev == nullptr) != (flush_bytes == 0)) return SCONV_EINVAL;
     Problem p;
     int rc = fill_problem(desc, pooled != 0, &p);
     if (rc) return rc;
     if (pooled && (int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
-    return tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, best_ms);
+    return tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, Flush{flush_dev, flush_bytes}, best_ms);
 }
 
 extern "C" int sconv_tune_reset(void)

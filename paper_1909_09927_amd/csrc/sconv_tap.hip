@@ -297,12 +297,14 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     }
 }
 
-// Workgroups of one kernel instantiation that fit on a compute unit (asked once).
+// Workgroups of one kernel instantiation that fit on a compute unit (asked once per LDS size).
 template <class G, int NWV>
 int occupancy(size_t lds_bytes)
 {
     static int occ = 0;
-    if (occ == 0) {
+    static size_t asked = 0;
+    if (occ == 0 || asked != lds_bytes) {
+        asked = lds_bytes;
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, tap_kernel<G, NWV>, NWV * 64, lds_bytes) !=
                 hipSuccess || nb < 1)
@@ -317,12 +319,12 @@ int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes,
                const float* w, float* y, hipStream_t stream)
 {
     auto kern = tap_kernel<G, NWV>;
-    static bool opted = false;  // dynamic LDS above 48 KiB is opted into once per kernel
-    if (!opted) {
+    static size_t opted = 0;  // dynamic LDS above 48 KiB is opted into (largest request so far)
+    if (lds_bytes > opted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return SCONV_ELAUNCH;
-        opted = true;
+        opted = lds_bytes;
     }
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, x, w, y);
     return launch_status();
@@ -334,6 +336,7 @@ struct Plan {
     TapCfg cfg;
     int nwv = 0;
     int kblocks = 0;
+    size_t lds_bytes = 0;
 };
 
 // Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
@@ -353,7 +356,7 @@ Plan plan_geom(const Problem& p)
     cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
     cfg.ntiles = cfg.tiles_x * cfg.tiles_y;
     const int kblocks = (p.Kg + G::KB - 1) / G::KB;
-    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t buf_bytes = 2 * (size_t)G::BUF * sizeof(float);
     const size_t red_per_tile = (size_t)G::KPL * G::ACC * 64 * sizeof(float);
     // clocks of SIMD issue time for one wavefront on one channel: a bit test and branch per
     // position, and per nonzero a broadcast plus its share of the tile's 9*ACC*KPL FMAs
@@ -364,11 +367,14 @@ Plan plan_geom(const Problem& p)
     int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_TAP_SPLIT="nwv,ncs"
     pinned_split("SCONV_TAP_SPLIT", &pin_nwv, &pin_ncs);
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
-        const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
-            if (ncs > 1 && nt * red_per_tile > lds_bytes) continue;
+            // the slice reduction reuses the filter buffers; a large tile's partial sums need more
+            size_t lds_bytes = buf_bytes;
+            if (ncs > 1 && nt * red_per_tile > lds_bytes) lds_bytes = nt * red_per_tile;
+            if (lds_bytes > 160 * 1024) continue;
+            const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
             if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
             const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
             const long long slots = 256LL * occ;
@@ -386,6 +392,7 @@ Plan plan_geom(const Problem& p)
                 best.cfg.CPW = G::CCH / ncs;
                 best.nwv = nwv;
                 best.kblocks = kblocks;
+                best.lds_bytes = lds_bytes;
             }
         }
     }
@@ -396,7 +403,7 @@ template <class G>
 int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
-    const size_t lds_bytes = 2 * (size_t)G::BUF * sizeof(float);
+    const size_t lds_bytes = pl.lds_bytes;
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
     const unsigned gz = (unsigned)(p.N * p.G);
     if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
@@ -436,21 +443,23 @@ struct Candidate {
     int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
     bool pooled;
     int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
-    bool needs_7x7, needs_w14;
+    int need_h, need_w;   // map height / width the geometry is built for (0 = any)
     int stride;
+    bool by_model;        // false: only when pinned (sconv_tune tries it; the cost model was not
+                          // calibrated on it)
 };
 
 const Candidate kCandidates[] = {
-    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, 1, false, false, 1},
-    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, 2, false, false, 1},
-    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, 1, true, false, 1},
-    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, 2, true, false, 1},
-    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, 1, false, true, 1},
-    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, 2, false, true, 1},
-    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, false, false, 1},
-    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, false, false, 1},
-    {"s2-3x4k1", plan_geom<S34_1>, launch_plan<S34_1>, false, 1, false, false, 2},
-    {"s2-3x4k2", plan_geom<S34_2>, launch_plan<S34_2>, false, 2, false, false, 2},
+    {"5x7k1", plan_geom<G57_1>, launch_plan<G57_1>, false, 1, 0, 0, 1, true},
+    {"5x7k2", plan_geom<G57_2>, launch_plan<G57_2>, false, 2, 0, 0, 1, true},
+    {"7x7k1", plan_geom<G77_1>, launch_plan<G77_1>, false, 1, 7, 7, 1, true},
+    {"7x7k2", plan_geom<G77_2>, launch_plan<G77_2>, false, 2, 7, 7, 1, true},
+    {"p4x14k1", plan_geom<P414_1>, launch_plan<P414_1>, true, 1, 0, 14, 1, true},
+    {"p4x14k2", plan_geom<P414_2>, launch_plan<P414_2>, true, 2, 0, 14, 1, true},
+    {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, 0, 0, 1, true},
+    {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, 0, 0, 1, true},
+    {"s2-3x4k1", plan_geom<S34_1>, launch_plan<S34_1>, false, 1, 0, 0, 2, true},
+    {"s2-3x4k2", plan_geom<S34_2>, launch_plan<S34_2>, false, 2, 0, 0, 2, true},
 };
 
 }  // namespace
@@ -473,9 +482,9 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     for (const Candidate& c : kCandidates) {
         if (c.pooled != pooled || c.stride != p.stride) continue;
         if (p.Kg <= 64 * (c.kpl - 1)) continue;
-        if (c.needs_7x7 && !(p.H == 7 && p.W == 7)) continue;
-        if (c.needs_w14 && p.W != 14) continue;
-        if (pin && strcmp(pin, c.name)) continue;
+        if (c.need_h && p.H != c.need_h) continue;
+        if (c.need_w && p.W != c.need_w) continue;
+        if (pin ? strcmp(pin, c.name) != 0 : !c.by_model) continue;
         const Plan pl = c.plan(p);
         if (pl.cost < 0.0) continue;
         if (!best || pl.cost < best_plan.cost) {

@@ -118,10 +118,12 @@ def test_tuning_calls_validate_on_the_host():
     L = sconv.lib()
     d = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1)
     p = ctypes.c_void_p(16)
-    assert L.sconv_tune(ctypes.byref(d), 0, None, p, p, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_tune(ctypes.byref(d), 0, None, p, p, None, 0, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_tune(ctypes.byref(d), 0, p, p, p, p, 0, None, None) == sconv.SCONV_EINVAL    # scratch without a size
+    assert L.sconv_tune(ctypes.byref(d), 0, p, p, p, None, 64, None, None) == sconv.SCONV_EINVAL
     bad = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 0, 1)
-    assert L.sconv_tune(ctypes.byref(bad), 0, p, p, p, None, None) == sconv.SCONV_EINVAL
-    assert L.sconv_tune(ctypes.byref(d), 1, p, p, p, None, None) == sconv.SCONV_EINVAL   # no pooling fields
+    assert L.sconv_tune(ctypes.byref(bad), 0, p, p, p, None, 0, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_tune(ctypes.byref(d), 1, p, p, p, None, 0, None, None) == sconv.SCONV_EINVAL   # no pooling fields
     assert L.sconv_tune_reset() == 0
     assert sconv.sconv_plan_name(d) == "tap3x3/model"
     assert sconv.sconv_plan_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3/model"
