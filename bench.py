@@ -19,6 +19,7 @@ bounded sample of the same workload.
   python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
   python bench.py --graph --config resnet50   # a batch-1 step eagerly and as a HIP graph replay
   python bench.py --axis batch | stride       # batch-size / stride sensitivity on one layer shape
+  python bench.py --chain [--batch 8]         # VGG-shaped tail, each layer fed by the previous one's output
 """
 from __future__ import annotations
 
@@ -455,6 +456,59 @@ def run_graph(args) -> None:
                       "same_buffers_every_step": True}), flush=True)
 
 
+def run_chain(args) -> None:
+    """The VGG-19-shaped tail (28x28 stage to the end) as a chain: every layer consumes the previous
+    layer's output on the device, so from the second layer on the zeros are the ones ReLU and pooling
+    produced.  Each layer is tuned on the input it really gets.  One JSON line per layer (zero ratio
+    of its input, plan, time) and one for the whole chain."""
+    import torch
+    import paper_1909_09927_amd as sconv
+    N = args.batch or 8
+    x, ws = workloads.make_chain_inputs(N)
+    cur = torch.from_numpy(x).cuda()
+    wds = [torch.from_numpy(w).cuda() for w in ws]
+    outs, recs = [], []
+    flush = flush_buffer() if TUNE else None
+    for layer, wd in zip(workloads.CHAIN, wds):
+        if TUNE:
+            sconv.sconv_tune(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=flush)
+        if layer.pool:
+            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+        else:
+            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True)
+        d = sconv.desc_for(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+        recs.append({"layer": layer.name, "N": N, "plan": sconv.sconv_plan_name(d, bool(layer.pool)),
+                     "input_zero_ratio": round(float((cur == 0).float().mean()), 4),
+                     "dense_flops": 2.0 * N * layer.K * layer.OH * layer.OW * layer.Cg * 9})
+        outs.append((cur, wd, y))
+        cur = y
+    torch.cuda.synchronize()
+
+    def one(i):
+        layer = workloads.CHAIN[i]
+        xi, wd, y = outs[i]
+        if layer.pool:
+            sconv.sconv_pool_forward(xi, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=y)
+        else:
+            sconv.sconv_forward(xi, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y)
+
+    def step():
+        for i in range(len(outs)):
+            one(i)
+
+    total = 0.0
+    for i, rec in enumerate(recs):
+        ms = _time(lambda: one(i), args.steps, args.warmup)
+        rec["ms"] = round(ms, 5)
+        rec["dense_equiv_gflops"] = round(rec.pop("dense_flops") / ms / 1e6, 1)
+        total += rec["dense_equiv_gflops"] * ms
+        print(json.dumps(rec), flush=True)
+    ms = _time(step, args.steps, args.warmup)
+    print(json.dumps({"chain": [l.name for l in workloads.CHAIN], "N": N, "ms_per_pass": round(ms, 5),
+                      "dense_equiv_gflops": round(total / ms, 1),
+                      "output_zero_ratio": round(float((cur == 0).float().mean()), 4)}), flush=True)
+
+
 def run_copy_calibration(args) -> None:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -481,6 +535,8 @@ def main() -> None:
                     help="conversion-only and unfused-pooling timings beside the whole kernels")
     ap.add_argument("--axis", default="", choices=["", "batch", "stride"],
                     help="batch-size or stride sweep on the VGG-shaped 256-channel layer")
+    ap.add_argument("--chain", action="store_true",
+                    help="the VGG-19-shaped tail as a chain: each layer consumes the previous layer's output")
     ap.add_argument("--graph", action="store_true",
                     help="one step of --config at --batch (default: its smallest) eagerly and as a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -515,6 +571,8 @@ def main() -> None:
         run_sweep(args)
     elif args.split:
         run_split(args)
+    elif args.chain:
+        run_chain(args)
     elif args.graph:
         run_graph(args)
     elif args.axis:

@@ -414,6 +414,35 @@ def test_tuned_plans_meet_the_same_bars(device, monkeypatch, shp):
     assert sconv.sconv_plan_name(d).endswith("/model")
 
 
+def test_chained_layers_each_match_the_oracle_on_the_input_they_got(device):
+    """Layers chained on the device (each consumes the previous one's output, zeros as ReLU and
+    pooling left them): every layer is checked against the oracle applied to the very input the
+    HIP path gave it, so errors cannot hide behind, or pile up across, layers."""
+    import oracle
+    from parity import TOL
+    layers = [workloads.Layer("c0", C=32, H=20, W=20, K=64, R=3, S=3, pad=1, zero_ratio=0.6),
+              workloads.Layer("c1", C=64, H=20, W=20, K=64, R=3, S=3, pad=1, pool=(2, 2, 2)),
+              workloads.Layer("c2", C=64, H=10, W=10, K=48, R=1, S=1),
+              workloads.Layer("c3", C=48, H=10, W=10, K=40, R=5, S=5, pad=2, pool=(2, 2, 2))]
+    x, ws = workloads.make_chain_inputs(2, layers)
+    cur = to_dev(x)
+    for layer, w in zip(layers, ws):
+        wd = to_dev(w)
+        xin = cur.cpu().numpy()
+        if layer.pool:
+            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+            ref, scale = oracle.conv_pool(xin, w, layer.pool, layer.stride, layer.pad, layer.groups)
+        else:
+            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True)
+            ref, scale = oracle.conv(xin, w, layer.stride, layer.pad, layer.groups, relu=True)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().astype(np.float64)
+        assert got.shape == ref.shape
+        assert (np.abs(got - ref) <= TOL * scale).all(), layer.name
+        assert 0.3 < (got == 0).mean() < 0.999, "the chain should stay sparse but alive"
+        cur = y
+
+
 def test_outputs_are_overwritten_not_accumulated(device):
     shp = (1, 8, 12, 12, 16, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(108, shp)

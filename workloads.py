@@ -249,3 +249,34 @@ def make_random_case(seed: int, N: int, C: int, H: int, W: int, K: int, R: int, 
         x = make_feature_map(rng, N, layer)
         w = make_filters(rng, layer)
     return layer, x, w
+
+
+# A chain of layers in which every layer consumes the previous layer's output (the paper's
+# procedure keeps the result of one layer as the next layer's input, Section 5.1): the tail of a
+# VGG-19-shaped network from the 28x28 stage on.  Only the first input is drawn; every later map
+# is whatever ReLU (and pooling) left, so its zeros have the structure a network produces.
+# Trained filters and biases are what push real maps beyond 50 % zeros; as a stand-in the filters
+# get a small negative mean, CHAIN_W_SHIFT standard deviations, which leaves 70-90 % zeros.
+CHAIN_W_SHIFT = -0.03
+CHAIN = [
+    Layer("chain-256to512x28", C=256, H=28, W=28, K=512, R=3, S=3, pad=1, zero_ratio=0.6),
+    Layer("chain-512x28-a", C=512, H=28, W=28, K=512, R=3, S=3, pad=1),
+    Layer("chain-512x28-b", C=512, H=28, W=28, K=512, R=3, S=3, pad=1),
+    Layer("chain-512x28-pool", C=512, H=28, W=28, K=512, R=3, S=3, pad=1, pool=(2, 2, 2)),
+    Layer("chain-512x14-a", C=512, H=14, W=14, K=512, R=3, S=3, pad=1),
+    Layer("chain-512x14-b", C=512, H=14, W=14, K=512, R=3, S=3, pad=1),
+    Layer("chain-512x14-pool", C=512, H=14, W=14, K=512, R=3, S=3, pad=1, pool=(2, 2, 2)),
+]
+
+
+def make_chain_inputs(N: int, layers=None, shift: float = CHAIN_W_SHIFT):
+    """(first input x, [filters per layer]) for the chain at batch N, seeded."""
+    layers = CHAIN if layers is None else layers
+    rng = np.random.default_rng(BASE_SEED + 9000 + N)
+    x = make_feature_map(rng, N, layers[0])
+    ws = []
+    for layer in layers:
+        w = make_filters(rng, layer)
+        std = layer.w_std if layer.w_std is not None else math.sqrt(2.0 / (layer.Cg * layer.R * layer.S))
+        ws.append((w + np.float32(shift * std)).astype(np.float32))
+    return x, ws
