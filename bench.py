@@ -44,7 +44,7 @@ MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3", "gen")
 # HBM/fabric bytes per launch from the rocprofv3 counter runs (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB,
 # scaled by the copy calibration); keyed by (variant, layer, batch); the summaries are in profiles/.
 MEASURED_TRAFFIC = {
-    ("quad3x3", "vgg-256x56", 8): 147.1e6 + 25.7e6,      # profiles/quad3x3_vgg-256x56_n8.txt
+    ("quad3x3", "vgg-256x56", 8): 54.8e6 + 25.7e6,       # profiles/quad3x3_vgg-256x56_n8.txt (7-row tiles)
 }
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
 TUNE = True                   # --no-tune: the static dispatch rules and cost models only
@@ -135,18 +135,23 @@ class DeviceLayer:
 
 
 def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
-    """Average launch duration in ms, events on the launch stream (torch's current stream)."""
+    """Average launch duration in ms, events on the launch stream (torch's current stream): the
+    median of three back-to-back rounds of `iters` launches, so that one stall of the machine (seen
+    now and then on 20-us layers) does not pass for the kernel's time."""
     import torch
     for _ in range(warmup):
         dl.run()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        dl.run()
-    e1.record()
-    e1.synchronize()
-    return e0.elapsed_time(e1) / iters
+    rounds = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            dl.run()
+        e1.record()
+        e1.synchronize()
+        rounds.append(e0.elapsed_time(e1) / iters)
+    return sorted(rounds)[1]
 
 
 def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
