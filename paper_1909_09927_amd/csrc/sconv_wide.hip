@@ -347,8 +347,12 @@ int launch_wide(const Problem& p, bool pooled, const float* x, const float* w, f
         if (c.pooled != pooled) continue;
         if (p.Kg <= 64 * (c.kpl - 1)) continue;
         if (pin && strcmp(pin, c.name) != 0) continue;
-        const Plan pl = c.plan(p);
+        Plan pl = c.plan(p);
         if (pl.cost < 0.0) continue;
+        // measured on eight layer shapes: one filter per lane (twice the wavefronts, half the
+        // registers) is 3-45 % faster than two in seven of them and 3 % slower in one; the model's
+        // matrix and staging clocks alone price the two alike
+        if (c.kpl == 2) pl.cost *= 1.25;
         if (!best || pl.cost < best_plan.cost) {
             best = &c;
             best_plan = pl;
