@@ -414,6 +414,46 @@ def test_tuned_plans_meet_the_same_bars(device, monkeypatch, shp):
     assert sconv.sconv_plan_name(d).endswith("/model")
 
 
+def test_tuned_plan_is_replayed_from_a_graph_and_yields_to_a_pinned_variant(device, monkeypatch):
+    """A tuned descriptor's calls can be captured (tuning itself happened before the capture); and
+    SCONV_VARIANT, when set, comes before the tuned table."""
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    sconv.sconv_tune_reset()
+    try:
+        shp = (2, 64, 14, 14, 128, 3, 3, 1, 1, 1, None)
+        layer, x, w = _mk(175, shp)
+        xd, wd = to_dev(x), to_dev(w)
+        sconv.sconv_tune(xd, wd, 1, 1, 1, None, relu=True)
+        d = sconv.desc_for(xd, wd, 1, 1, 1, None, True)
+        assert not sconv.sconv_plan_name(d).endswith("/model")
+        y = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        out = torch.empty_like(y)
+        with torch.cuda.stream(side):
+            sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, out=out)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, out=out)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            _, xn, _ = _mk(176 + rep, shp)
+            xd.copy_(torch.from_numpy(xn))
+            out.fill_(-1.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ref = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref)
+        monkeypatch.setenv("SCONV_VARIANT", "rows")
+        assert sconv.sconv_variant_name(d) == "rows" and sconv.sconv_plan_name(d) == "rows/model"
+        check_forward(layer, x, w, relu=True)
+    finally:
+        sconv.sconv_tune_reset()
+
+
 def test_chained_layers_each_match_the_oracle_on_the_input_they_got(device):
     """Layers chained on the device (each consumes the previous one's output, zeros as ReLU and
     pooling left them): every layer is checked against the oracle applied to the very input the
