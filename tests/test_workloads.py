@@ -41,3 +41,31 @@ def test_integer_cases_are_integers():
     _, x, w = workloads.make_random_case(5, 2, 8, 6, 6, 4, 3, 3, 1, 1, 1, None, 0.5, True)
     assert np.array_equal(x, np.round(x)) and np.array_equal(w, np.round(w))
     assert x.max() <= 3 and np.abs(w).max() <= 2
+
+
+def test_single_layer_config_and_chain_are_consistent():
+    """Shapes of the stand-ins for the paper's single layers are valid, and in the chain every layer's
+    output is the next layer's input."""
+    for layer in workloads.CONFIGS[5]["layers"]:
+        assert layer.C % layer.groups == 0 and layer.K % layer.groups == 0
+        assert layer.OH >= 1 and layer.OW >= 1 and 0.8 <= layer.zero_ratio <= 0.95
+    h, c = workloads.CHAIN[0].H, workloads.CHAIN[0].C
+    for layer in workloads.CHAIN:
+        assert (layer.C, layer.H, layer.W) == (c, h, h)
+        c, h = layer.K, layer.OH
+        if layer.pool:
+            h = (h - layer.pool[0]) // layer.pool[2] + 1
+    x, ws = workloads.make_chain_inputs(1, workloads.CHAIN[:2])
+    x2, ws2 = workloads.make_chain_inputs(1, workloads.CHAIN[:2])
+    assert np.array_equal(x, x2) and all(np.array_equal(a, b) for a, b in zip(ws, ws2))
+    assert ws[0].mean() < 0                      # the stated negative shift of the filter mean
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
