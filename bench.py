@@ -16,6 +16,7 @@ bounded sample of the same workload.
   python bench.py --table [--only single]   # every layer of every (or one) config at both batch sizes -> JSON lines
   python bench.py --sweep          # zero-ratio sweep 0.00..0.95 on the RegNetX 896-channel layer
   python bench.py --layer vgg19:0 --batch 8   # one layer alone (profiling)
+  python bench.py --shape 32,64,28,28,128,5,5,1,2,1 --zero-ratio 0.7   # any shape alone
   python bench.py --split          # conversion alone vs. the whole kernel; fused vs. unfused pooling
   python bench.py --graph --config resnet50   # a batch-1 step eagerly and as a HIP graph replay
   python bench.py --axis batch | stride       # batch-size / stride sensitivity on one layer shape
@@ -338,6 +339,27 @@ def run_layer(args) -> None:
     print(json.dumps(rec), flush=True)
 
 
+def run_shape(args) -> None:
+    """Any layer shape: --shape N,C,H,W,K,R,S,stride,pad,groups[,ph,pw,ps] at --zero-ratio (default 0.7)."""
+    v = [int(t) for t in args.shape.split(",")]
+    if len(v) not in (10, 13):
+        sys.exit("--shape takes N,C,H,W,K,R,S,stride,pad,groups or the same plus ph,pw,ps")
+    N, C, H, W, K, R, S, stride, pad, groups = v[:10]
+    pool = tuple(v[10:13]) if len(v) == 13 else None
+    z = args.zero_ratio if args.zero_ratio >= 0 else 0.7
+    layer = workloads.Layer(f"shape-{args.shape}", C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad,
+                            groups=groups, pool=pool, zero_ratio=z, structure=args.structure)
+    rng = np.random.default_rng(workloads.BASE_SEED + 7777)
+    x = workloads.make_feature_map(rng, N, layer)
+    w = workloads.make_filters(rng, layer)
+    wk = layer_work(layer, N, x)
+    dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+    ms = time_layer(dl, args.steps, args.warmup)
+    rec = layer_record(dl, wk, ms)
+    rec["config"] = "shape"
+    print(json.dumps(rec), flush=True)
+
+
 def _time(fn, iters, warmup) -> float:
     import torch
     for _ in range(warmup):
@@ -550,6 +572,7 @@ def main() -> None:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
     ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
+    ap.add_argument("--shape", default="", help="N,C,H,W,K,R,S,stride,pad,groups[,ph,pw,ps]: time this shape alone")
     ap.add_argument("--zero-ratio", type=float, default=-1.0, help="override the layer's zero ratio (--layer)")
     ap.add_argument("--structure", default="iid", choices=["iid", "clustered"],
                     help="zero pattern of the input for --sweep / --layer: independent zeros, or dead "
@@ -568,6 +591,8 @@ def main() -> None:
         sys.exit("libsconv.so is not built; run python -m paper_1909_09927_amd.build")
     if args.copy_calibration:
         run_copy_calibration(args)
+    elif args.shape:
+        run_shape(args)
     elif args.layer:
         run_layer(args)
     elif args.table:
