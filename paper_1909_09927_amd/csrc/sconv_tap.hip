@@ -13,7 +13,8 @@
 //     processed (filter reuse = number of nonzeros of the channel inside the tile);
 //   - the input tile (output tile plus halo) is read from HBM/L2 with one coalesced load per
 //     64 positions, one element per lane; ballot(x != 0) gives the nonzero mask - the wavefront
-//     level compaction; zero elements cost one scalar bit test;
+//     level compaction; positions are tested four at a time first, then one by one inside a group
+//     that holds a nonzero, so a zero element costs between a quarter of and one scalar bit test;
 //   - for each set bit the value is broadcast from its lane (readlane -> scalar register) and
 //     the code for that position, which knows at compile time which accumulators and which
 //     filter taps the position touches, runs up to 9*KPL FMAs with a scalar operand.
