@@ -9,10 +9,11 @@
 // sequence in chunks of 64, so nothing depends on the kernel's shape at compile time:
 //   * the filter chunk w[k][col0 .. col0+63] is staged to LDS as [column][filter] (coalesced
 //     256-byte reads of a filter row, one padding word per LDS row against bank conflicts);
-//   * the position (c, r, s) of a column is wavefront-uniform and kept in scalar registers; a
-//     lane's element under it is one buffer load at lane offset + column offset.  Whether the tap
-//     lies inside the map is one AND + compare against two per-lane bit masks (valid rows r,
-//     valid columns s of the lane's window); a tap outside the map, a column past L or a lane
+//   * what a column (c, r, s) needs from a lane is the same for every window row: one wavefront
+//     computes, per chunk, each column's byte offset and the two mask bits of its kernel row and
+//     column into a small LDS table; a lane's element under the column is one buffer load at lane
+//     offset + column offset.  Whether the tap lies inside the map is one AND + compare of those
+//     bits against two per-lane bit masks (valid rows r, valid columns s of the lane's window); a tap outside the map, a column past L or a lane
 //     past the last window row loads from an offset beyond the buffer's size, which the
 //     hardware answers with zero without touching memory;
 //   * elements are loaded one group of 8 columns ahead of the group being multiplied.
@@ -130,32 +131,37 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
         for (int i = 0; i < FPT; ++i) buf[lane * KBP + wave + i * NWV] = stage[i];
     };
 
-    // Loads the elements of the U columns starting at column `jb` of the wavefront's share of
-    // chunk `ch`.  Everything about the column is scalar; per lane: AND, compare, add, select, load.
-    auto issue = [&](int ch, int jb, float (&dst)[U]) {
-        const unsigned col0 = (unsigned)(ch * CW + cs * cfg.CPW + jb);
-        const unsigned c = gc.magicT ? __umulhi(col0, gc.magicT) : col0;
-        const unsigned t = col0 - c * T;
-        unsigned r = gc.magicS ? __umulhi(t, gc.magicS) : t;
-        unsigned s = t - r * (unsigned)p.S;
-        unsigned off = 4u * (c * (unsigned)HWp + r * (unsigned)p.W + s);
+    // Column table.  What a column (c, r, s) needs from a lane - the two mask bits of its kernel row
+    // and column, and its byte offset from the window's origin - is the same for every window row,
+    // so one wavefront works it out per chunk (a lane per column, two multiply-high divisions) and
+    // leaves it in LDS, one chunk ahead of the loads that use it; three table buffers rotate, so
+    // the chunk being written is never one that a slower wavefront still reads.
+    uint2* tab = reinterpret_cast<uint2*>(lds + 2 * BUF);   // [3][CW]: (needed mask bits, byte offset)
+    auto write_table = [&](int ch) {
+        if (wave != 0) return;
+        const unsigned col = (unsigned)(ch * CW + lane);
+        const unsigned c = gc.magicT ? __umulhi(col, gc.magicT) : col;
+        const unsigned t = col - c * T;
+        const unsigned r = gc.magicS ? __umulhi(t, gc.magicS) : t;
+        const unsigned s = t - r * (unsigned)p.S;
+        uint2 e;
+        e.x = col < (unsigned)p.L ? ((1u << r) | (0x10000u << s)) : 0x80000000u;   // bit 31: no lane has it
+        e.y = 4u * (c * (unsigned)HWp + r * (unsigned)p.W + s);
+        tab[(ch % 3) * CW + lane] = e;
+    };
+
+    // Loads the elements of the U columns starting at column `jb` of the wavefront's share of the
+    // chunk whose table is buffer `tb`.  Per lane and column: AND, compare, add, select, load.
+    auto issue = [&](int tb, int jb, float (&dst)[U]) {
+        const uint2* te = tab + tb * CW + cs * cfg.CPW + jb;   // the same address in every lane
+        uint2 e[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) e[u] = te[u];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const unsigned need = (col0 + u < (unsigned)p.L) ? ((1u << r) | (0x10000u << s)) : 0x80000000u;
-            const bool ok = (rcmask & need) == need;
-            const unsigned vo = ok ? boff0 + off : 0x80000000u;
+            const bool ok = (rcmask & e[u].x) == e[u].x;
+            const unsigned vo = ok ? boff0 + e[u].y : 0x80000000u;
             dst[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xres, (int)vo, 0, 0));
-            ++s;
-            off += 4u;
-            if (s == (unsigned)p.S) {
-                s = 0;
-                ++r;
-                off += 4u * (unsigned)(p.W - p.S);
-                if (r == (unsigned)p.R) {
-                    r = 0;
-                    off += 4u * (unsigned)(HWp - p.R * p.W);
-                }
-            }
         }
     };
 
@@ -184,29 +190,32 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
     };
 
     // the wavefront's groups in the order it walks them: CPW / U per chunk
-    int pch = 0, pjb = 0;   // the next group to load
+    int ptb = 0, pjb = 0;   // the next group to load: table buffer of its chunk, column in the slice
     auto advance = [&]() {
         pjb += U;
         if (pjb == cfg.CPW) {
             pjb = 0;
-            ++pch;
+            ptb = ptb == 2 ? 0 : ptb + 1;
         }
     };
 
     fetch_chunk(0);
+    write_table(0);
+    __syncthreads();
     float xa[U], xb[U];
-    issue(pch, pjb, xa);
+    issue(ptb, pjb, xa);
     advance();
     for (int ch = 0; ch < gc.nchunks; ++ch) {
         float* buf = lds + (ch & 1) * BUF;
         store_chunk(buf);
+        write_table(ch + 1);   // past the last chunk: columns >= L, whose loads read nothing
         __syncthreads();
         if (ch + 1 < gc.nchunks) fetch_chunk(ch + 1);
         for (int jb = 0; jb < cfg.CPW; jb += 2 * U) {
-            issue(pch, pjb, xb);
+            issue(ptb, pjb, xb);
             advance();
             compute(buf, jb, xa);
-            issue(pch, pjb, xa);   // past the last chunk: columns >= L, nothing is read
+            issue(ptb, pjb, xa);
             advance();
             compute(buf, jb + U, xb);
         }
@@ -258,7 +267,7 @@ Plan plan_geom(const Problem& p)
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
             if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
-            size_t lds_bytes = 2 * (size_t)CW * (KB + 1) * sizeof(float);
+            size_t lds_bytes = 2 * (size_t)CW * (KB + 1) * sizeof(float) + 3 * CW * sizeof(uint2);
             const size_t red_bytes = (size_t)nt * 4 * (ncs - 1) * KPL * 16 * 64 * sizeof(float);
             if (red_bytes > lds_bytes) lds_bytes = red_bytes;
             if (lds_bytes > 160 * 1024) continue;
