@@ -32,8 +32,12 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-template <int KPL_, int TH_, int RP_, int NQ_, int TW_, bool POOL_>
+template <int KPL_, int TH_, int RP_, int NQ_, int TW_, bool POOL_, bool NOSKIP_ = false>
 struct Geom {
+    // NOSKIP: no zero tests at all - the dense form, for maps with so few zeros that hardly a
+    // 6-element group is empty (z^6: 5 % of the groups at 60 % zeros) and the tests with their
+    // branches cost more issue time than the skipped instructions save.
+    static constexpr bool NOSKIP = NOSKIP_;
     static constexpr int KPL = KPL_;            // filters per lane
     static constexpr int TH = TH_;              // output rows of the tile
     static constexpr int RP = RP_;              // lanes per input row
@@ -83,7 +87,7 @@ __device__ __forceinline__ void quad_group(const unsigned (&mask)[2 * G::NX], co
     unsigned hit = 0;
     if (lo) hit |= mask[2 * Q] & lo;
     if (hi) hit |= mask[2 * Q + 1] & hi;
-    if (hit) {
+    if (G::NOSKIP || hit) {
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
 #pragma unroll
@@ -473,6 +477,9 @@ int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w
 using Q32_1 = Geom<1, 2, 32, 7, 28, false>;
 using Q32_2 = Geom<2, 1, 32, 7, 28, false>;
 using Q32_T7 = Geom<1, 7, 32, 7, 28, false>;   // 7 output rows: heights that are multiples of 7
+using Q32_T7D = Geom<1, 7, 32, 7, 28, false, true>;   // the same without zero tests
+using Q32_1D = Geom<1, 2, 32, 7, 28, false, true>;
+using Q32_2D = Geom<2, 1, 32, 7, 28, false, true>;
 using Q16_2 = Geom<2, 2, 16, 4, 14, false>;
 using QP32_1 = Geom<1, 2, 32, 7, 28, true>;
 using QP16_2 = Geom<2, 2, 16, 4, 14, true>;
@@ -492,12 +499,16 @@ struct Candidate {
     bool pooled;
     int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
     bool wide;            // for maps wider than 14
+    bool by_model = true; // false: only when named (by the tuner's measurement or a pin)
 };
 
 const Candidate kCandidates[] = {
     {"q32k1", plan_geom<Q32_1>, launch_plan<Q32_1>, false, 1, true},
     {"q32k2", plan_geom<Q32_2>, launch_plan<Q32_2>, false, 2, true},
     {"q32t7", plan_geom<Q32_T7>, launch_plan<Q32_T7>, false, 1, true},
+    {"q32t7d", plan_geom<Q32_T7D>, launch_plan<Q32_T7D>, false, 1, true, false},
+    {"q32k1d", plan_geom<Q32_1D>, launch_plan<Q32_1D>, false, 1, true, false},
+    {"q32k2d", plan_geom<Q32_2D>, launch_plan<Q32_2D>, false, 2, true, false},
     {"q16k2", plan_geom<Q16_2>, launch_plan<Q16_2>, false, 2, false},
     {"qp32k1", plan_geom<QP32_1>, launch_plan<QP32_1>, true, 1, true},
     {"qp16k2", plan_geom<QP16_2>, launch_plan<QP16_2>, true, 2, false},
@@ -507,7 +518,7 @@ const Candidate kCandidates[] = {
 
 const char* const* quad_geoms()
 {
-    static const char* const names[] = {"q32k1", "q32k2", "q32t7", "q16k2", "qp32k1", "qp16k2", nullptr};
+    static const char* const names[] = {"q32k1", "q32k2", "q32t7", "q32t7d", "q32k1d", "q32k2d", "q16k2", "qp32k1", "qp16k2", nullptr};
     return names;
 }
 
@@ -526,6 +537,7 @@ int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, f
         if (pin ? (pin[0] == '!' ? strcmp(pin + 1, c.name) == 0 || c.wide != (p.W > 14) : strcmp(pin, c.name) != 0)
                 : (c.wide != (p.W > 14)))
             continue;
+        if (!c.by_model && !(pin && pin[0] != '!')) continue;
         const Plan pl = c.plan(p);
         if (pl.cost < 0.0) continue;
         if (!best || pl.cost < best_plan.cost) {

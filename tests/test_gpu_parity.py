@@ -300,6 +300,26 @@ def test_quad_seven_row_tiles(device, monkeypatch, shp, split):
     check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
+@pytest.mark.parametrize("geom", ["q32t7d", "q32k1d", "q32k2d"])
+@pytest.mark.parametrize("shp", [
+    (2, 32, 21, 56, 70, 3, 3, 1, 1, 1, None),
+    (1, 64, 9, 30, 64, 3, 3, 1, 1, 2, None),
+    (1, 24, 28, 28, 130, 3, 3, 1, 1, 1, None),
+])
+def test_quad_dense_geometries(device, monkeypatch, shp, geom):
+    """The matrix-core 3x3 tiles without zero tests (the dense form) give the same sums: the
+    skipped products were zeros."""
+    monkeypatch.setenv("SCONV_VARIANT", "quad")
+    monkeypatch.setenv("SCONV_QUAD_GEOM", geom)
+    layer, x, w = _mk(170, shp)
+    check_forward(layer, x, w, relu=True)
+    layer, x, w = _mk(171, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    layer, x, w = _mk(172, shp)
+    x[:] = 0                      # an all-zero map still leaves through the whole-channel test
+    check_forward(layer, x, w, relu=False)
+
+
 @pytest.mark.parametrize("shp", WIDE)
 def test_wide_variant(device, monkeypatch, shp):
     monkeypatch.setenv("SCONV_VARIANT", "wide")
