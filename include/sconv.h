@@ -2,10 +2,20 @@
  * sconv: zero-skipping direct convolution (+ fused ReLU / max-pooling) for AMD MI355X (gfx950).
  *
  * C ABI of the GPU library.  All tensors are fp32 and contiguous; every pointer marked
- * "device" is HIP device memory owned by the caller.  The library allocates, frees and keeps
- * no device memory.  Every entry point that launches work enqueues it on the given HIP stream
- * (a hipStream_t passed as void*; NULL = the default stream) and returns without synchronising.
- * Outputs are overwritten, never accumulated into.  Calls may come from several host threads
+ * "device" is HIP device memory owned by the caller.  Every entry point that launches work
+ * enqueues it on the given HIP stream (a hipStream_t passed as void*; NULL = the default stream)
+ * and returns without synchronising.  Outputs are overwritten, never accumulated into.
+ *
+ * Device memory of the library's own: one 64 MiB scratch buffer per device and stream, allocated
+ * (hipMalloc) by the first forward or tuning call on that stream whose launch is small enough to
+ * be split over more workgroups - the partial sums of the parts pass through it to a second,
+ * small kernel (see sconv_forward) - and kept until the process ends.  Nothing else is allocated,
+ * and nothing when no such launch occurs.  Consequences: launches enqueued on (or captured
+ * from) one stream must run in that stream's order, as they share its buffer - replaying a graph
+ * concurrently with other sconv work that was enqueued on the stream it was captured from is a
+ * race; and a stream that is being captured into a graph before any eager call has given it a
+ * buffer gets unsplit plans (correct, slower on batch-1 layers): make one eager call, or
+ * sconv_tune, on the stream first.  Calls may come from several host threads
  * (planning and enqueueing are serialised inside the library); the only state kept between calls
  * is cached launch information (occupancy answers) for the device the first calls ran on, so one
  * process should drive one device.
@@ -89,6 +99,11 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * pipe (groups of 6, 8, 16 and 16 elements) and skip a group only when all of its elements are zero, so a
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
+ * A launch of fewer than 128 workgroups ("tap3x3" and "gen": deep layers at batch 1) is split
+ * along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its
+ * channel range into the stream's scratch buffer, and a second kernel on the same stream adds
+ * them in a fixed order and applies ReLU (and the pooling of sconv_pool_forward).  Results stay
+ * deterministic; the association of the fp32 sums differs from the unsplit kernel's.
  *   x_dev device, in : [N][C][H][W]
  *   w_dev device, in : [K][C/G][R][S]
  *   y_dev device, out: [N][K][OH][OW]
@@ -164,8 +179,9 @@ int sconv_tune_reset(void);
 
 /*
  * Writes the plan the forward calls would launch for this descriptor into out (NUL-terminated,
- * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices) for a
- * tuned descriptor, "variant/model" otherwise.  Host only.
+ * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices), or
+ * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor;
+ * "variant/model" otherwise.  Host only.
  */
 int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size);
 

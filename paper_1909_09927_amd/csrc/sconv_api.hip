@@ -24,16 +24,21 @@ const char* pinned_geom(const char* env_name)
     return getenv(env_name);
 }
 
-void pinned_split(const char* env_name, int* nwv, int* ncs)
+void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss)
 {
-    *nwv = *ncs = 0;
+    int dummy = 0;
+    if (!nss) nss = &dummy;
+    *nwv = *ncs = *nss = 0;
     if (g_pin) {
         *nwv = g_pin->nwv;
         *ncs = g_pin->ncs;
+        *nss = g_pin->nwv ? (g_pin->nss > 1 ? g_pin->nss : 1) : 0;
         return;
     }
     if (const char* pin = getenv(env_name)) {
-        if (sscanf(pin, "%d,%d", nwv, ncs) != 2) *nwv = *ncs = 0;
+        const int got = sscanf(pin, "%d,%d,%d", nwv, ncs, nss);
+        if (got == 2) *nss = 1;
+        else if (got != 3) *nwv = *ncs = *nss = 0;
     }
 }
 
@@ -135,7 +140,14 @@ static Variant choose(const Problem& p, bool pooled)
     if (pin && !strcmp(pin, "wide")) return wide_supported(p, pooled) ? V_WIDE : V_ROWS;
     if (pin && !strcmp(pin, "quad")) return quad_supported(p, pooled) ? V_QUAD : V_ROWS;
     if (pin && !strcmp(pin, "gen")) return gen_supported(p, pooled) ? V_GEN : V_ROWS;
-    if (pw_supported(p, pooled)) return V_PW;
+    if (pw_supported(p, pooled)) {
+        // A 1x1 layer of a few dozen 32-position tiles walking 512 or more channels is one latency
+        // chain per workgroup: the general kernel, which splits such a launch's columns over
+        // workgroups, measures 1.2-1.6x faster there.
+        const long long pw_tiles = ((long long)p.N * p.H * p.W + 31) / 32 * ((p.Kg + 63) / 64) * p.G;
+        if (pw_tiles < 64 && p.Cg >= 512 && gen_supported(p, pooled)) return V_GEN;
+        return V_PW;
+    }
     // The 16-row granule needs many tile-wavefronts (64 window rows x 64 filters each) to fill the
     // chip: it splits the channels of a tile four ways at most.
     const long long rows = pooled ? (long long)p.N * p.PH * p.PW * 4 : (long long)p.N * p.OH * p.OW;
@@ -201,7 +213,10 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
     Variant v = choose(p, pooled);
     int rc = SCONV_EUNSUPPORTED;
     if (v == V_PW) rc = launch_variant(V_PW, nullptr, p, pooled, x, w, y, s);
-    if (v == V_GEN) rc = launch_variant(V_GEN, nullptr, p, pooled, x, w, y, s);
+    if (v == V_GEN) {
+        rc = launch_variant(V_GEN, nullptr, p, pooled, x, w, y, s);
+        if (rc == SCONV_EUNSUPPORTED && pw_supported(p, pooled)) rc = launch_variant(V_PW, nullptr, p, pooled, x, w, y, s);
+    }
     if (v == V_WIDE) {
         rc = launch_variant(V_WIDE, nullptr, p, pooled, x, w, y, s);
         if (rc == SCONV_EUNSUPPORTED) v = quad_supported(p, pooled) ? V_QUAD : V_TAP;
@@ -265,14 +280,15 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         bool ok;
         const char* const* geoms;
         int nwv_lo, nwv_hi;
+        int nss_hi;        // largest channel split across workgroups to try (1: the variant has none)
     };
     static const char* const no_geoms[] = {"", nullptr};
     const Family fams[] = {
-        {V_PW, pw_supported(p, pooled), no_geoms, 8, 16},
-        {V_TAP, tap_supported(p, pooled), tap_geoms(), 8, 16},
-        {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16},
-        {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8},
-        {V_GEN, gen_supported(p, pooled), gen_geoms(), 4, 8},
+        {V_PW, pw_supported(p, pooled), no_geoms, 8, 16, 1},
+        {V_TAP, tap_supported(p, pooled), tap_geoms(), 8, 16, 16},
+        {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16, 1},
+        {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8, 1},
+        {V_GEN, gen_supported(p, pooled), gen_geoms(), 4, 8, 16},
     };
     // every candidate that applies, with a first quick timing
     struct Cand {
@@ -303,12 +319,17 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
             memset(&pin, 0, sizeof(pin));
             snprintf(pin.geom, sizeof(pin.geom), "%s", *g);
             if (!try_one(f.v, &pin)) continue;
-            for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
-                for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
-                    pin.nwv = nwv;
-                    pin.ncs = ncs;
-                    try_one(f.v, &pin);
+            for (int nss = 1; nss <= f.nss_hi && err == SCONV_OK; nss *= 2) {
+                bool any = false;   // a split the launch is too large for applies with no nwv, ncs
+                for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
+                    for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
+                        pin.nwv = nwv;
+                        pin.ncs = ncs;
+                        pin.nss = nss;
+                        any |= try_one(f.v, &pin);
+                    }
                 }
+                if (!any) break;
             }
         }
     }
@@ -329,7 +350,10 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         best.ms = t;
         best.pin = c.pin;
         best.pinned = c.pinned;
-        if (c.pinned)
+        if (c.pinned && c.pin.nss > 1)
+            snprintf(best.name, sizeof(best.name), "%s/%s/%dx%dx%d", variant_name(c.v), c.pin.geom, c.pin.nwv,
+                     c.pin.ncs, c.pin.nss);
+        else if (c.pinned)
             snprintf(best.name, sizeof(best.name), "%s/%s/%dx%d", variant_name(c.v), c.pin.geom[0] ? c.pin.geom : "-",
                      c.pin.nwv, c.pin.ncs);
         else

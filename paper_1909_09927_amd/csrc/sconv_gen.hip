@@ -38,6 +38,8 @@ struct GenCfg {
     unsigned magicT, magicS;   // floor(2^32 / d) + 1 for d = R*S and d = S (exact quotients for our
                                // ranges); 0 stands for d = 1
     int nchunks;               // ceil(L / CW)
+    int nss;                   // workgroups splitting the chunks of a tile; above 1 the results are
+                               // raw partial sums, stored into slice blockIdx.z % nss of y
 };
 
 template <int KPL, bool POOL, int NWV>
@@ -58,7 +60,9 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ts = wave % cfg.NT;                  // tile slot
     const int cs = wave / cfg.NT;                  // column slice
-    const int g = blockIdx.z;
+    const int g = blockIdx.z / gc.nss;
+    const int ss = blockIdx.z - g * gc.nss;
+    const int ch0 = ss * gc.nchunks / gc.nss, ch1 = (ss + 1) * gc.nchunks / gc.nss;   // this workgroup's chunks
     const int kb0 = blockIdx.y * KB;
     const int tile = blockIdx.x * cfg.NT + ts;
     const bool tile_ok = tile < cfg.ntiles;
@@ -137,9 +141,9 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
     // leaves it in LDS, one chunk ahead of the loads that use it; three table buffers rotate, so
     // the chunk being written is never one that a slower wavefront still reads.
     uint2* tab = reinterpret_cast<uint2*>(lds + 2 * BUF);   // [3][CW]: (needed mask bits, byte offset)
-    auto write_table = [&](int ch) {
+    auto write_table = [&](int lc) {   // lc: chunk number counted from the workgroup's first
         if (wave != 0) return;
-        const unsigned col = (unsigned)(ch * CW + lane);
+        const unsigned col = (unsigned)((ch0 + lc) * CW + lane);
         const unsigned c = gc.magicT ? __umulhi(col, gc.magicT) : col;
         const unsigned t = col - c * T;
         const unsigned r = gc.magicS ? __umulhi(t, gc.magicS) : t;
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
         uint2 e;
         e.x = col < (unsigned)p.L ? ((1u << r) | (0x10000u << s)) : 0x80000000u;   // bit 31: no lane has it
         e.y = 4u * (c * (unsigned)HWp + r * (unsigned)p.W + s);
-        tab[(ch % 3) * CW + lane] = e;
+        tab[(lc % 3) * CW + lane] = e;
     };
 
     // Loads the elements of the U columns starting at column `jb` of the wavefront's share of the
@@ -199,18 +203,19 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
         }
     };
 
-    fetch_chunk(0);
+    fetch_chunk(ch0);
     write_table(0);
     __syncthreads();
     float xa[U], xb[U];
     issue(ptb, pjb, xa);
     advance();
-    for (int ch = 0; ch < gc.nchunks; ++ch) {
-        float* buf = lds + (ch & 1) * BUF;
+    for (int lc = 0; lc < ch1 - ch0; ++lc) {
+        float* buf = lds + (lc & 1) * BUF;
         store_chunk(buf);
-        write_table(ch + 1);   // past the last chunk: columns >= L, whose loads read nothing
+        write_table(lc + 1);   // past the last chunk: columns >= L, whose loads read nothing, or the
+                               // next workgroup's first columns, whose elements are loaded and dropped
         __syncthreads();
-        if (ch + 1 < gc.nchunks) fetch_chunk(ch + 1);
+        if (lc + 1 < ch1 - ch0) fetch_chunk(ch0 + lc + 1);
         for (int jb = 0; jb < cfg.CPW; jb += 2 * U) {
             issue(ptb, pjb, xb);
             advance();
@@ -221,7 +226,9 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
         }
     }
 
-    finish_tile<KPL, POOL>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane, y);
+    // split: slice ss of the partial sums (plain layout; the host switched ReLU off)
+    finish_tile<KPL, POOL>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane,
+                           y + (size_t)ss * p.N * p.K * plane);
 }
 
 struct Plan {
@@ -230,6 +237,8 @@ struct Plan {
     int nwv = 0;
     int kblocks = 0;
     size_t lds_bytes = 0;
+    int nss = 1;          // workgroups per tile along the columns (partial sums through scratch)
+    long long wgs1 = 0;   // workgroups of the launch before that split
 };
 
 template <int KPL, bool POOL, int NWV>
@@ -244,9 +253,13 @@ int occupancy(size_t lds_bytes)
 
 // Decomposition of one launch, with the wide kernel's model: the matrix time of the most loaded
 // SIMD plus what does not overlap with it (slice reduction, half of the filter staging, a latency
-// penalty when a SIMD holds a single wavefront).
+// penalty when a SIMD holds a single wavefront).  A launch of fewer than 128 tile-workgroups also
+// splits the chunks of a tile over NSS workgroups (split: 0 = not allowed, 1 = allowed, 2 =
+// required - the plain kernel serving a pooled layer): the smallest power of two that gives every
+// compute unit a workgroup and leaves each workgroup two chunks; a second, small kernel adds the
+// partial sums.
 template <int KPL, bool POOL>
-Plan plan_geom(const Problem& p)
+Plan plan_geom(const Problem& p, int split)
 {
     constexpr int KB = 64 * KPL;
     Plan best;
@@ -259,8 +272,19 @@ Plan plan_geom(const Problem& p)
     const double t_column = 4.0 * KPL * 34.0 + 30.0;
     const double stage_clocks = (double)KB * nchunks * CW * 4.0 / 64.0;
 
-    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_GEN_SPLIT="nwv,ncs"
-    pinned_split("SCONV_GEN_SPLIT", &pin_nwv, &pin_ncs);
+    int pin_nwv = 0, pin_ncs = 0, pin_nss = 0;   // tuning aid: SCONV_GEN_SPLIT="nwv,ncs[,nss]"
+    pinned_split("SCONV_GEN_SPLIT", &pin_nwv, &pin_ncs, &pin_nss);
+    const bool small = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.G < 128;
+    const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
+    auto split_fits = [&](int nss) {
+        return !POOL && nss <= nchunks && nss * part_bytes <= kSplitScratchBytes && (long long)p.G * nss <= 65535;
+    };
+    // a pinned decomposition is priced as it is; the model ranks the unsplit decompositions and
+    // splits the winner afterwards
+    const int nss = pin_nss ? pin_nss : 1;
+    if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
+    if (pin_nss == 1 && split == 2) return best;
+    if (!pin_nss && split == 2 && !small) return best;
     for (int nwv = 4; nwv <= 8; nwv *= 2) {
         if (KPL == 2 && nwv == 4) continue;      // 32 staging registers per thread: not built
         for (int ncs = 1; ncs <= 4; ncs *= 2) {
@@ -273,12 +297,16 @@ Plan plan_geom(const Problem& p)
             if (lds_bytes > 160 * 1024) continue;
             const int occ = nwv == 4 ? occupancy<KPL, POOL, (KPL == 2 ? 8 : 4)>(lds_bytes)
                                      : occupancy<KPL, POOL, 8>(lds_bytes);
-            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.G;
+            const long long wgs1 = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.G;
+            if (nss > 1 && wgs1 >= 512 && current_pin()) continue;   // sconv_tune: not worth a trial
+            const long long wgs = wgs1 * nss;
             const long long per_cu = (wgs + 255) / 256;
             const double per_simd = (double)per_cu * nwv / 4.0;
             const double resident = (double)(per_cu < occ ? per_cu : occ) * nwv / 4.0;
-            const double wave = (double)nchunks * (CW / ncs) * t_column + (ncs > 1 ? 64.0 * KPL * 20.0 + 800.0 : 0.0);
-            double cost = per_simd * wave * (resident < 2.0 ? 1.25 : 1.0) + per_cu * stage_clocks * 0.5;
+            const double wave = (double)nchunks / nss * (CW / ncs) * t_column +
+                                (ncs > 1 ? 64.0 * KPL * 20.0 + 800.0 : 0.0);
+            double cost = per_simd * wave * (resident < 2.0 ? 1.25 : 1.0) + per_cu * stage_clocks / nss * 0.5 +
+                          (nss > 1 ? 9000.0 : 0.0);                            // second kernel
             if (best.cost < 0.0 || cost < best.cost) {
                 best.cost = cost;
                 best.cfg = cfg;
@@ -288,8 +316,18 @@ Plan plan_geom(const Problem& p)
                 best.nwv = nwv;
                 best.kblocks = kblocks;
                 best.lds_bytes = lds_bytes;
+                best.nss = nss;
+                best.wgs1 = wgs1;
             }
         }
+    }
+    if (!pin_nss && split && small && best.cost >= 0.0) {
+        int want = split == 2 ? 2 : 1;
+        while (want < 16 && best.wgs1 * want < 256 && want * 4 <= nchunks) want *= 2;
+        if (want > 1 && !split_fits(want)) want = 1;
+        if (want == 1 && split == 2) return Plan();
+        best.nss = want;
+        if (want > 1) best.cost = best.cost / want + 9000.0;
     }
     return best;
 }
@@ -311,23 +349,42 @@ int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid
 }
 
 template <int KPL, bool POOL>
-int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
-    if (p.G > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
-    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)p.G);
-    WideCfg cfg = pl.cfg;
-    const int plane = p.OH * p.OW;
-    cfg.vec4 = (!POOL && plane % 4 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0;
+    const long long gz = (long long)p.G * pl.nss;
+    if (gz > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
     GenCfg gc;
     gc.magicT = p.R * p.S > 1 ? (unsigned)((1ULL << 32) / (unsigned)(p.R * p.S)) + 1u : 0u;
     gc.magicS = p.S > 1 ? (unsigned)((1ULL << 32) / (unsigned)p.S) + 1u : 0u;
     gc.nchunks = (p.L + CW - 1) / CW;
-    if constexpr (KPL == 1) {
-        if (pl.nwv == 4) return launch_nwv<KPL, POOL, 4>(p, cfg, gc, grid, pl.lds_bytes, x, w, y, stream);
+    gc.nss = pl.nss;
+    Problem q = p;
+    float* out = y;
+    if (pl.nss > 1) {
+        // raw partial sums of every chunk range into the scratch slices; the second kernel below
+        // adds them and applies the epilogue
+        if (POOL || pl.nss > gc.nchunks ||
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            return SCONV_EUNSUPPORTED;
+        out = split_scratch(stream);
+        if (!out) return SCONV_EUNSUPPORTED;
+        q.relu = 0;
+    } else if (pooled != POOL) {
+        return SCONV_EUNSUPPORTED;
     }
-    return launch_nwv<KPL, POOL, 8>(p, cfg, gc, grid, pl.lds_bytes, x, w, y, stream);
+    WideCfg cfg = pl.cfg;
+    const int plane = p.OH * p.OW;
+    cfg.vec4 = (!POOL && plane % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0) ? 1 : 0;
+    int rc;
+    if (KPL == 1 && pl.nwv == 4)
+        rc = launch_nwv<KPL, POOL, (KPL == 1 ? 4 : 8)>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
+    else
+        rc = launch_nwv<KPL, POOL, 8>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
+    if (rc != SCONV_OK || pl.nss == 1) return rc;
+    return launch_split_reduce(p, pooled, out, pl.nss, y, stream);
 }
 
 bool shape_ok(const Problem& p, bool pooled)
@@ -346,8 +403,8 @@ bool shape_ok(const Problem& p, bool pooled)
 
 struct Candidate {
     const char* name;
-    Plan (*plan)(const Problem&);
-    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    Plan (*plan)(const Problem&, int);
+    int (*launch)(const Plan&, const Problem&, bool, const float*, const float*, float*, hipStream_t);
     bool pooled;
     int kpl;
 };
@@ -376,19 +433,28 @@ int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, fl
     const char* pin = pinned_geom("SCONV_GEN_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
-    for (const Candidate& c : kCandidates) {
-        if (c.pooled != pooled) continue;
-        if (p.Kg <= 64 * (c.kpl - 1)) continue;
-        if (pin && strcmp(pin, c.name) != 0) continue;
-        const Plan pl = c.plan(p);
-        if (pl.cost < 0.0) continue;
-        if (!best || pl.cost < best_plan.cost) {
-            best = &c;
-            best_plan = pl;
+    // a split of the chunks across workgroups needs the stream's scratch buffer
+    const bool can_split = split_scratch(stream) != nullptr;
+    // A pooled layer: first the plain kernel with the split (the second kernel pools), which the
+    // model offers for small launches only; the pooled kernel when that does not apply.
+    for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {
+        for (const Candidate& c : kCandidates) {
+            if (c.pooled != (pooled && pass == 1)) continue;
+            if (p.Kg <= 64 * (c.kpl - 1)) continue;
+            if (pin && strcmp(pin, c.name) != 0) continue;
+            const Plan pl = c.plan(p, c.pooled != pooled ? 2 : (can_split && !c.pooled ? 1 : 0));
+            if (pl.cost < 0.0) continue;
+            if (!best || pl.cost < best_plan.cost) {
+                best = &c;
+                best_plan = pl;
+            }
         }
     }
     if (!best) return SCONV_EUNSUPPORTED;
-    return best->launch(best_plan, p, x, w, y, stream);
+    if (getenv("SCONV_TRACE_PLAN"))
+        fprintf(stderr, "sconv: gen %s nwv=%d ncs=%d nt=%d nss=%d cost=%.0f\n", best->name, best_plan.nwv,
+                best_plan.cfg.NCS, best_plan.cfg.NT, best_plan.nss, best_plan.cost);
+    return best->launch(best_plan, p, pooled, x, w, y, stream);
 }
 
 }  // namespace sconv

@@ -68,13 +68,25 @@ int launch_pointwise(const Problem& p, bool pooled, const float* x, const float*
 struct PlanPin {
     char geom[16];       // "" = any geometry
     int nwv, ncs;        // 0 = the model's choice
+    int nss;             // workgroups splitting the channels of a tile (with nwv, ncs); 0 or 1 = none
 };
 const PlanPin* current_pin();
 
 // Geometry pin for a launcher: the dispatcher's, else the named environment variable's.
 const char* pinned_geom(const char* env_name);
-// Split pin "nwv,ncs" likewise; both 0 when there is none.
-void pinned_split(const char* env_name, int* nwv, int* ncs);
+// Split pin "nwv,ncs" or "nwv,ncs,nss" likewise; all 0 when there is none.
+void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss = nullptr);
+
+// Channel split across workgroups: every workgroup stores the raw partial sums of its channel
+// range into slice ss of a scratch buffer laid out [nss][N][K][OH][OW]; launch_split_reduce adds
+// the slices in order and applies ReLU and, when pooled, the max over the pooling window.
+// split_scratch returns the stream's buffer of kSplitScratchBytes (allocated on first use, kept
+// until the process ends), or null when it cannot be had (the stream is recording a graph and has
+// no buffer yet, or the allocation failed): then the caller plans without a split.
+constexpr size_t kSplitScratchBytes = size_t(64) << 20;
+float* split_scratch(hipStream_t stream);
+int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y,
+                        hipStream_t stream);
 
 // Candidate geometry names of the variants (for sconv_tune); null-terminated arrays.
 const char* const* tap_geoms();

@@ -1,0 +1,101 @@
+// Channel split across workgroups, for launches too small to fill the chip.
+//
+// A deep layer at batch 1 (512 channels on a 7x7 or 14x14 map) has a handful of spatial tiles and
+// a few filter blocks: a dozen workgroups, each walking all the channels with one staged filter
+// chunk in flight, so the whole launch waits on memory latency, chunk after chunk, on a few compute
+// units.  Splitting the channel range over NSS workgroups per tile multiplies the workgroups (and
+// the filter fetches in flight) by NSS.  The sums of Section 5.4 are associative, so each
+// workgroup stores the raw partial sums of its channel range - the plain convolution layout,
+// no ReLU, no pooling - into slice number ss of a scratch buffer, and the small kernel below adds
+// the slices in a fixed order (slice 0 first: results do not depend on scheduling) and applies the
+// epilogue of Sections 5.5 / 6: ReLU, and the max over the pooling window when fused.
+//
+// The scratch buffer belongs to the library: one per device and stream, allocated on the first
+// split launch enqueued on that stream and kept until the process ends.
+#include <map>
+#include <utility>
+
+#include "sconv_internal.h"
+
+namespace sconv {
+
+namespace {
+
+__global__ __launch_bounds__(256) void split_sum_kernel(const float* __restrict__ part, float* __restrict__ y,
+                                                        int nss, long long slice, long long total, int relu)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    float v = part[i];
+    for (int s = 1; s < nss; ++s) v += part[s * slice + i];
+    if (relu) v = fmaxf(v, 0.0f);
+    y[i] = v;
+}
+
+// one thread per pooled result; the window's convolution results are summed over the slices first
+__global__ __launch_bounds__(256) void split_pool_kernel(Problem p, const float* __restrict__ part,
+                                                         float* __restrict__ y, int nss, long long slice,
+                                                         long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int pwi = (int)(i % p.PW);
+    long long q = i / p.PW;
+    const int phi = (int)(q % p.PH);
+    const long long nk = q / p.PH;
+    const float* src = part + (nk * p.OH + (long long)phi * p.ps) * p.OW + (long long)pwi * p.ps;
+    float m = 0.0f;   // ReLU: the maximum is taken over max(value, 0)
+    for (int py = 0; py < p.ph; ++py)
+        for (int px = 0; px < p.pw; ++px) {
+            const float* e = src + py * p.OW + px;
+            float v = e[0];
+            for (int s = 1; s < nss; ++s) v += e[s * slice];
+            m = fmaxf(m, v);
+        }
+    y[i] = m;
+}
+
+struct Scratch {
+    float* ptr;
+};
+std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;   // under the dispatcher's lock
+
+}  // namespace
+
+float* split_scratch(hipStream_t stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    const auto key = std::make_pair(dev, stream);
+    auto it = g_scratch.find(key);
+    if (it != g_scratch.end()) return it->second.ptr;
+    // an allocation is not allowed while the stream records a graph: the caller plans without a split
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess || st != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* ptr = nullptr;
+    if (hipMalloc(&ptr, kSplitScratchBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch[key] = Scratch{static_cast<float*>(ptr)};
+    return static_cast<float*>(ptr);
+}
+
+int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y, hipStream_t stream)
+{
+    const long long slice = (long long)p.N * p.K * p.OH * p.OW;
+    if (!pooled) {
+        hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((slice + 255) / 256)), dim3(256), 0, stream, part, y,
+                           nss, slice, slice, p.relu);
+    } else {
+        const long long total = (long long)p.N * p.K * p.PH * p.PW;
+        hipLaunchKernelGGL(split_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p, part,
+                           y, nss, slice, total);
+    }
+    return launch_status();
+}
+
+}  // namespace sconv

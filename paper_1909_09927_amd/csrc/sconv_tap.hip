@@ -61,6 +61,8 @@ struct TapCfg {
     int NT, NCS;        // wavefronts per workgroup = NT spatial tiles x NCS channel slices
     int CPW;            // channels per wavefront per chunk = CCH / NCS
     int tiles_x, tiles_y, ntiles;
+    int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
+                        // partial sums, stored into slice blockIdx.z % NSS of y
 };
 
 // One input position P of the tile: test its mask bit, broadcast the value, run its products.
@@ -132,8 +134,10 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: scalar registers
     const int ts = wave % cfg.NT;                  // spatial tile slot
     const int cs = wave / cfg.NT;                  // channel slice
-    const int n = blockIdx.z / p.G;
-    const int g = blockIdx.z - n * p.G;
+    const int ss = blockIdx.z % cfg.NSS;           // channel range of the workgroup
+    const int ng = blockIdx.z / cfg.NSS;
+    const int n = ng / p.G;
+    const int g = ng - n * p.G;
     const int kb0 = blockIdx.y * G::KB;            // first filter of the block inside the group
     const int tile = blockIdx.x * cfg.NT + ts;
     const bool tile_ok = tile < cfg.ntiles;
@@ -193,15 +197,16 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     };
 
     const int nchunks = (p.Cg + G::CCH - 1) / G::CCH;
-    fetch_chunk(0);
+    const int ch0 = ss * nchunks / cfg.NSS, ch1 = (ss + 1) * nchunks / cfg.NSS;   // this workgroup's chunks
+    fetch_chunk(ch0 * G::CCH);
     float xn[G::NX];
-    load_x(cs * cfg.CPW, xn);
+    load_x(ch0 * G::CCH + cs * cfg.CPW, xn);
 
-    for (int ch = 0; ch < nchunks; ++ch) {
+    for (int ch = ch0; ch < ch1; ++ch) {
         float* buf = lds + (ch & 1) * G::BUF;
         store_chunk(buf);
         __syncthreads();
-        if (ch + 1 < nchunks) fetch_chunk((ch + 1) * G::CCH);
+        if (ch + 1 < ch1) fetch_chunk((ch + 1) * G::CCH);
 
         const int cbase = ch * G::CCH + cs * cfg.CPW;   // this wavefront's channels of the chunk
         for (int cc = 0; cc < cfg.CPW; ++cc) {
@@ -260,6 +265,7 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
     // epilogue: lane owns filters kb0 + lane + 64*i
     if (!G::POOL) {
         const int plane = p.OH * p.OW;
+        y += (size_t)ss * p.N * p.K * plane;       // split: slice ss of the partial sums (p.relu is off)
 #pragma unroll
         for (int i = 0; i < G::KPL; ++i) {
             const int k = lane + 64 * i;
@@ -338,6 +344,8 @@ struct Plan {
     int nwv = 0;
     int kblocks = 0;
     size_t lds_bytes = 0;
+    int nss = 1;          // workgroups per tile along the channels (partial sums through scratch)
+    long long wgs1 = 0;   // workgroups of the launch before that split
 };
 
 // Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
@@ -348,8 +356,16 @@ struct Plan {
 // saturating at about four resident wavefronts, one scalar test per input position and channel,
 // filter staging at 64 bytes per clock per compute unit - and the cheapest is launched.  The
 // density of the input is not known on the host; the model assumes 30 % nonzeros.
+//
+// Third knob, for small launches only: NSS workgroups split the channels of a tile (split: 0 = not
+// allowed, 1 = allowed, 2 = required - a plain tile serving a pooled layer).  A workgroup has one
+// filter chunk in flight, so a launch of fewer workgroups than compute units waits on the memory
+// latency chunk after chunk; the split divides that chain, for the price of the second, small
+// kernel that adds the partial sums.  The model splits launches of fewer than 128 tile-workgroups
+// (measured 1.4-3.5x faster there; around 200 workgroups the split measures between 1.2x faster
+// and 1.5x slower); sconv_tune tries splits of launches up to 512.
 template <class G>
-Plan plan_geom(const Problem& p)
+Plan plan_geom(const Problem& p, int split)
 {
     Plan best;
     TapCfg cfg;
@@ -365,8 +381,23 @@ Plan plan_geom(const Problem& p)
     const double t_channel = 60.0 + 6.0 * G::NPOS + nnz * (14.0 + 4.5 * 9.0 * G::ACC * G::KPL / G::NPOS);
     const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
-    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_TAP_SPLIT="nwv,ncs"
-    pinned_split("SCONV_TAP_SPLIT", &pin_nwv, &pin_ncs);
+    int pin_nwv = 0, pin_ncs = 0, pin_nss = 0;   // tuning aid: SCONV_TAP_SPLIT="nwv,ncs[,nss]"
+    pinned_split("SCONV_TAP_SPLIT", &pin_nwv, &pin_ncs, &pin_nss);
+    const int nchunks = p.Cg / G::CCH;
+    // a launch that leaves half of the compute units idle even with one tile and 64 filters per
+    // workgroup
+    const bool small = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.N * p.G < 128;
+    const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
+    auto split_fits = [&](int nss) {
+        return !G::POOL && nss <= nchunks && nss * part_bytes <= kSplitScratchBytes &&
+               (long long)p.N * p.G * nss <= 65535;
+    };
+    // a pinned decomposition is priced as it is; the model ranks the unsplit decompositions and
+    // splits the winner afterwards
+    const int nss = pin_nss ? pin_nss : 1;
+    if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
+    if (pin_nss == 1 && split == 2) return best;
+    if (!pin_nss && split == 2 && !small) return best;
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
@@ -377,14 +408,17 @@ Plan plan_geom(const Problem& p)
             if (lds_bytes > 160 * 1024) continue;
             const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
             if (!pin_nwv && nt > 1 && nt / 2 >= cfg.ntiles) continue;   // half of the tile slots empty
-            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            const long long wgs1 = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            if (nss > 1 && wgs1 >= 512 && current_pin()) continue;   // sconv_tune: not worth a trial
+            const long long wgs = wgs1 * nss;
             const long long slots = 256LL * occ;
             const long long rounds = (wgs + slots - 1) / slots;
             const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
             double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
             if (r < 4.0) r = 4.0;
-            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
-                                (ncs - 1) * 2000.0;                              // reduction steps
+            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) / nss +
+                                (ncs - 1) * 2000.0 +                             // reduction steps
+                                (nss > 1 ? 9000.0 : 0.0);                        // second kernel
             if (best.cost < 0.0 || cost < best.cost) {
                 best.cost = cost;
                 best.cfg = cfg;
@@ -394,25 +428,55 @@ Plan plan_geom(const Problem& p)
                 best.nwv = nwv;
                 best.kblocks = kblocks;
                 best.lds_bytes = lds_bytes;
+                best.nss = nss;
+                best.cfg.NSS = nss;
+                best.wgs1 = wgs1;
             }
         }
+    }
+    if (!pin_nss && split && small && best.cost >= 0.0) {
+        // the model's split: the smallest power of two that gives every compute unit a workgroup
+        // and leaves each workgroup two chunks or more
+        int want = split == 2 ? 2 : 1;
+        while (want < 16 && best.wgs1 * want < 256 && want * 4 <= nchunks) want *= 2;
+        if (want > 1 && !split_fits(want)) want = 1;
+        if (want == 1 && split == 2) return Plan();
+        best.nss = best.cfg.NSS = want;
+        if (want > 1) best.cost = best.cost / want + 9000.0;
     }
     return best;
 }
 
 template <class G>
-int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
     const size_t lds_bytes = pl.lds_bytes;
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
-    const unsigned gz = (unsigned)(p.N * p.G);
-    if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
-    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, gz);
-    if constexpr (G::MAXW == 16) {
-        if (pl.nwv == 16) return launch_nwv<G, 16>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+    const long long gz = (long long)p.N * p.G * pl.nss;
+    if (gz > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
+    Problem q = p;
+    float* out = y;
+    if (pl.nss > 1) {
+        // raw partial sums of every channel range into the scratch slices; the second kernel below
+        // adds them and applies the epilogue
+        if (G::POOL || pl.nss > p.Cg / G::CCH ||
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            return SCONV_EUNSUPPORTED;
+        out = split_scratch(stream);
+        if (!out) return SCONV_EUNSUPPORTED;
+        q.relu = 0;
+    } else if (pooled != G::POOL) {
+        return SCONV_EUNSUPPORTED;
     }
-    return launch_nwv<G, 8>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+    int rc;
+    if (G::MAXW == 16 && pl.nwv == 16)
+        rc = launch_nwv<G, G::MAXW>(q, pl.cfg, grid, lds_bytes, x, w, out, stream);
+    else
+        rc = launch_nwv<G, 8>(q, pl.cfg, grid, lds_bytes, x, w, out, stream);
+    if (rc != SCONV_OK || pl.nss == 1) return rc;
+    return launch_split_reduce(p, pooled, out, pl.nss, y, stream);
 }
 
 // Geometries.  Generic: 5x7 output tiles with halo (63 input positions, one register).  Maps
@@ -440,8 +504,8 @@ bool shape_ok(const Problem& p, bool pooled)
 
 struct Candidate {
     const char* name;
-    Plan (*plan)(const Problem&);
-    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    Plan (*plan)(const Problem&, int);
+    int (*launch)(const Plan&, const Problem&, bool, const float*, const float*, float*, hipStream_t);
     bool pooled;
     int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
     int need_h, need_w;   // map height / width the geometry is built for (0 = any)
@@ -480,21 +544,31 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     const char* pin = pinned_geom("SCONV_TAP_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
-    for (const Candidate& c : kCandidates) {
-        if (c.pooled != pooled || c.stride != p.stride) continue;
-        if (p.Kg <= 64 * (c.kpl - 1)) continue;
-        if (c.need_h && p.H != c.need_h) continue;
-        if (c.need_w && p.W != c.need_w) continue;
-        if (pin ? strcmp(pin, c.name) != 0 : !c.by_model) continue;
-        const Plan pl = c.plan(p);
-        if (pl.cost < 0.0) continue;
-        if (!best || pl.cost < best_plan.cost) {
-            best = &c;
-            best_plan = pl;
+    // a channel split across workgroups needs the stream's scratch buffer
+    const bool can_split = split_scratch(stream) != nullptr;
+    // A pooled layer: first the plain tiles with the split (the second kernel pools), which the
+    // model offers for small launches only; the pooled tiles when none applies.
+    for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {
+        for (const Candidate& c : kCandidates) {
+            if (c.stride != p.stride) continue;
+            if (c.pooled != (pooled && pass == 1)) continue;
+            if (p.Kg <= 64 * (c.kpl - 1)) continue;
+            if (c.need_h && p.H != c.need_h) continue;
+            if (c.need_w && p.W != c.need_w) continue;
+            if (pin ? strcmp(pin, c.name) != 0 : !c.by_model) continue;
+            const Plan pl = c.plan(p, c.pooled != pooled ? 2 : (can_split && !c.pooled ? 1 : 0));
+            if (pl.cost < 0.0) continue;
+            if (!best || pl.cost < best_plan.cost) {
+                best = &c;
+                best_plan = pl;
+            }
         }
     }
     if (!best) return SCONV_EUNSUPPORTED;
-    return best->launch(best_plan, p, x, w, y, stream);
+    if (getenv("SCONV_TRACE_PLAN"))
+        fprintf(stderr, "sconv: tap3x3 %s nwv=%d ncs=%d nt=%d nss=%d cost=%.0f\n", best->name, best_plan.nwv,
+                best_plan.cfg.NCS, best_plan.cfg.NT, best_plan.nss, best_plan.cost);
+    return best->launch(best_plan, p, pooled, x, w, y, stream);
 }
 
 }  // namespace sconv

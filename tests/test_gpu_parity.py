@@ -300,6 +300,80 @@ def test_quad_seven_row_tiles(device, monkeypatch, shp, split):
     check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
+SPLIT = [
+    (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, (2, 2, 2)),      # the deep batch-1 layer the split is for
+    (1, 64, 14, 14, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # ragged filter block
+    (2, 96, 9, 11, 130, 3, 3, 1, 1, 2, (2, 2, 1)),      # grouped, 3 chunks per group: uneven ranges
+    (1, 128, 13, 13, 64, 3, 3, 2, 1, 1, None),          # stride 2
+]
+
+
+@pytest.mark.parametrize("split", ["16,4,2", "8,8,4", "16,16,8", "8,1,2", "16,2,16"])
+@pytest.mark.parametrize("shp", SPLIT)
+def test_tap_channel_split_across_workgroups(device, monkeypatch, shp, split):
+    """Partial sums of channel ranges through the scratch buffer, then the adding kernel with its
+    ReLU / pooling epilogue: same bars as the one-kernel path (a split the shape has too few chunks
+    for falls back to another kernel, which must match just the same)."""
+    monkeypatch.setenv("SCONV_VARIANT", "tap")
+    monkeypatch.setenv("SCONV_TAP_SPLIT", split)
+    layer, x, w = _mk(180, shp)
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
+    layer, x, w = _mk(181, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w, integer_exact=True)
+
+
+GEN_SPLIT = [
+    (1, 20, 11, 11, 50, 5, 5, 1, 0, 1, (2, 2, 2)),      # 500 columns: 8 chunks, the last one ragged
+    (1, 480, 14, 14, 192, 1, 1, 1, 0, 1, (2, 2, 2)),    # 1x1 with a channel count off the 64 grid
+    (2, 48, 7, 7, 130, 5, 5, 1, 2, 2, (2, 2, 1)),       # grouped, two filters per lane possible
+    (1, 30, 9, 13, 40, 3, 4, 2, 1, 1, None),            # odd kernel, stride 2
+]
+
+
+@pytest.mark.parametrize("split", ["4,1,2", "8,2,4", "8,4,8", "4,4,2"])
+@pytest.mark.parametrize("shp", GEN_SPLIT)
+def test_gen_chunk_split_across_workgroups(device, monkeypatch, shp, split):
+    """The general matrix-core kernel with its chunks split over workgroups: partial sums through
+    the scratch buffer, epilogue (ReLU, any pooling window) in the adding kernel."""
+    monkeypatch.setenv("SCONV_VARIANT", "gen")
+    monkeypatch.setenv("SCONV_GEN_SPLIT", split)
+    layer, x, w = _mk(183, shp)
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
+    layer, x, w = _mk(184, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w, integer_exact=True)
+
+
+def test_split_plan_is_left_out_while_a_fresh_stream_records_a_graph(device):
+    """The scratch buffer of a split plan is allocated per stream on first use, which cannot happen
+    during graph capture: a capture on a stream that has none must still give the right result."""
+    shp = (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(182, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    import oracle
+    ref, scale = oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
+    eager = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)   # default stream
+    torch.cuda.synchronize()
+    out = torch.empty_like(eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True, out=out)
+    for _ in range(3):
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert (np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
 @pytest.mark.parametrize("geom", ["q32t7d", "q32k1d", "q32k2d"])
 @pytest.mark.parametrize("shp", [
     (2, 32, 21, 56, 70, 3, 3, 1, 1, 1, None),
