@@ -154,8 +154,9 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  * ratio of the map (Section 8's sparsity sweep: the vector kernel's time falls with the ratio, the
  * matrix kernels' only once whole groups are zero), which the host does not know.  sconv_tune runs
  * every variant and every decomposition that covers the descriptor on the caller's operands - each
- * one untimed launch and three timed ones between two events on hip_stream - and remembers the
- * fastest for this exact descriptor (and pooled flag) in a host-side table; later sconv_forward /
+ * one untimed launch and three timed ones between two events on hip_stream, the static choice and
+ * the four fastest then again for about a millisecond each - and remembers the fastest (the static
+ * choice unless another measures 3 % faster) for this exact descriptor (and pooled flag) in a host-side table; later sconv_forward /
  * sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
  * models' choice.  The table is per process, guarded by the library's lock, and holds no device
  * memory.
@@ -180,8 +181,9 @@ int sconv_tune_reset(void);
 /*
  * Writes the plan the forward calls would launch for this descriptor into out (NUL-terminated,
  * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices), or
- * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor;
- * "variant/model" otherwise.  Host only.
+ * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor
+ * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice);
+ * "variant/model" for a descriptor that was not tuned.  Host only.
  */
 int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size);
 

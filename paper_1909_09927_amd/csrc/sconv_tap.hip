@@ -63,6 +63,7 @@ struct TapCfg {
     int tiles_x, tiles_y, ntiles;
     int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
                         // partial sums, stored into slice blockIdx.z % NSS of y
+    int RW;             // slices whose sums fit into LDS side by side during the slice reduction
 };
 
 // One input position P of the tile: test its mask bit, broadcast the value, run its products.
@@ -238,26 +239,34 @@ __global__ __launch_bounds__(NWV * 64) void tap_kernel(Problem p, TapCfg cfg, co
         }
     }
 
-    // reduce the channel slices: slice r hands its partial sums to slice 0 through LDS
+    // Reduce the channel slices through LDS.  Of the `active` slices still holding sums, the top
+    // nw hand theirs to the bottom nw, as many at a time as the buffer has room for (cfg.RW slices
+    // of NT tiles): a tree of log2(NCS) steps when half of the slices fit, one slice per step when
+    // only one does.  The pairing depends on the decomposition alone, so results are reproducible.
     if (cfg.NCS > 1) {
-        float* red = lds;  // [NT][KPL*ACC][64]
-        for (int r = 1; r < cfg.NCS; ++r) {
+        float* red = lds;  // [RW][NT][KPL*ACC][64]
+        constexpr int NACC = G::KPL * G::ACC;
+        int active = cfg.NCS;
+        while (active > 1) {
+            const int nw = min(cfg.RW, active / 2);
+            const int first = active - nw;   // first writing slice
             __syncthreads();
-            if (cs == r) {
+            if (cs >= first && cs < active) {
+                float* dst = red + (size_t)((cs - first) * cfg.NT + ts) * NACC * 64 + lane;
 #pragma unroll
                 for (int i = 0; i < G::KPL; ++i)
 #pragma unroll
-                    for (int a = 0; a < G::ACC; ++a)
-                        red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane] = acc[i][a];
+                    for (int a = 0; a < G::ACC; ++a) dst[(i * G::ACC + a) * 64] = acc[i][a];
             }
             __syncthreads();
-            if (cs == 0) {
+            if (cs < nw) {
+                const float* src = red + (size_t)(cs * cfg.NT + ts) * NACC * 64 + lane;
 #pragma unroll
                 for (int i = 0; i < G::KPL; ++i)
 #pragma unroll
-                    for (int a = 0; a < G::ACC; ++a)
-                        acc[i][a] += red[(ts * G::KPL * G::ACC + i * G::ACC + a) * 64 + lane];
+                    for (int a = 0; a < G::ACC; ++a) acc[i][a] += src[(i * G::ACC + a) * 64];
             }
+            active = first;
         }
     }
     if (cs != 0 || !tile_ok) return;
@@ -411,13 +420,16 @@ Plan plan_geom(const Problem& p, int split)
             const long long wgs1 = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
             if (nss > 1 && wgs1 >= 512 && current_pin()) continue;   // sconv_tune: not worth a trial
             const long long wgs = wgs1 * nss;
+            const int rw = ncs > 1 ? (int)(lds_bytes / (nt * red_per_tile)) : 1;
+            int red_steps = 0;   // of the slice reduction: the kernel's own loop
+            for (int active = ncs; active > 1; ++red_steps) active -= rw < active / 2 ? rw : active / 2;
             const long long slots = 256LL * occ;
             const long long rounds = (wgs + slots - 1) / slots;
             const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
             double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
             if (r < 4.0) r = 4.0;
             const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) / nss +
-                                (ncs - 1) * 2000.0 +                             // reduction steps
+                                red_steps * 2000.0 +                             // reduction steps
                                 (nss > 1 ? 9000.0 : 0.0);                        // second kernel
             if (best.cost < 0.0 || cost < best.cost) {
                 best.cost = cost;
@@ -430,6 +442,7 @@ Plan plan_geom(const Problem& p, int split)
                 best.lds_bytes = lds_bytes;
                 best.nss = nss;
                 best.cfg.NSS = nss;
+                best.cfg.RW = rw;
                 best.wgs1 = wgs1;
             }
         }
