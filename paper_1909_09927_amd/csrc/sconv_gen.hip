@@ -42,7 +42,7 @@ struct GenCfg {
                                // raw partial sums, stored into slice blockIdx.z % nss of y
 };
 
-template <int KPL, bool POOL, int NWV>
+template <int KPL, bool POOL, int NWV, bool DENSE>
 __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, GenCfg gc,
                                                        const float* __restrict__ x,
                                                        const float* __restrict__ w, float* __restrict__ y)
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
 #pragma unroll
                 for (int i = 0; i < KPL; ++i) wq[(u + 1) & 1][i] = wl[(u + 1) * KBP + 64 * i];
             }
-            tap_blocks<KPL>(xc[u], m[u], wq[u & 1], acc);
+            tap_blocks<KPL, DENSE>(xc[u], m[u], wq[u & 1], acc);
         }
     };
 
@@ -245,7 +245,7 @@ template <int KPL, bool POOL, int NWV>
 int occupancy(size_t lds_bytes)
 {
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gen_kernel<KPL, POOL, NWV>, NWV * 64, lds_bytes) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gen_kernel<KPL, POOL, NWV, false>, NWV * 64, lds_bytes) !=
             hipSuccess || nb < 1)
         nb = 1;
     return nb;
@@ -332,11 +332,11 @@ Plan plan_geom(const Problem& p, int split)
     return best;
 }
 
-template <int KPL, bool POOL, int NWV>
+template <int KPL, bool POOL, int NWV, bool DENSE>
 int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid, size_t lds_bytes,
                const float* x, const float* w, float* y, hipStream_t stream)
 {
-    auto kern = gen_kernel<KPL, POOL, NWV>;
+    auto kern = gen_kernel<KPL, POOL, NWV, DENSE>;
     static size_t opted = 0;  // dynamic LDS above 48 KiB is opted into (largest request so far)
     if (lds_bytes > opted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -348,7 +348,7 @@ int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid
     return launch_status();
 }
 
-template <int KPL, bool POOL>
+template <int KPL, bool POOL, bool DENSE>
 int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
@@ -380,9 +380,9 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
     cfg.vec4 = (!POOL && plane % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0) ? 1 : 0;
     int rc;
     if (KPL == 1 && pl.nwv == 4)
-        rc = launch_nwv<KPL, POOL, (KPL == 1 ? 4 : 8)>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
+        rc = launch_nwv<KPL, POOL, (KPL == 1 ? 4 : 8), DENSE>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
     else
-        rc = launch_nwv<KPL, POOL, 8>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
+        rc = launch_nwv<KPL, POOL, 8, DENSE>(q, cfg, gc, grid, pl.lds_bytes, x, w, out, stream);
     if (rc != SCONV_OK || pl.nss == 1) return rc;
     return launch_split_reduce(p, pooled, out, pl.nss, y, stream);
 }
@@ -407,20 +407,26 @@ struct Candidate {
     int (*launch)(const Plan&, const Problem&, bool, const float*, const float*, float*, hipStream_t);
     bool pooled;
     int kpl;
+    bool by_model;
 };
 
 const Candidate kCandidates[] = {
-    {"gk1", plan_geom<1, false>, launch_plan<1, false>, false, 1},
-    {"gk2", plan_geom<2, false>, launch_plan<2, false>, false, 2},
-    {"gpk1", plan_geom<1, true>, launch_plan<1, true>, true, 1},
-    {"gpk2", plan_geom<2, true>, launch_plan<2, true>, true, 2},
+    {"gk1", plan_geom<1, false>, launch_plan<1, false, false>, false, 1, true},
+    {"gk2", plan_geom<2, false>, launch_plan<2, false, false>, false, 2, true},
+    {"gpk1", plan_geom<1, true>, launch_plan<1, true, false>, true, 1, true},
+    {"gpk2", plan_geom<2, true>, launch_plan<2, true, false>, true, 2, true},
+    // the same without zero tests: only when named (sconv_tune's measurement, or a pin)
+    {"gk1d", plan_geom<1, false>, launch_plan<1, false, true>, false, 1, false},
+    {"gk2d", plan_geom<2, false>, launch_plan<2, false, true>, false, 2, false},
+    {"gpk1d", plan_geom<1, true>, launch_plan<1, true, true>, true, 1, false},
+    {"gpk2d", plan_geom<2, true>, launch_plan<2, true, true>, true, 2, false},
 };
 
 }  // namespace
 
 const char* const* gen_geoms()
 {
-    static const char* const names[] = {"gk1", "gk2", "gpk1", "gpk2", nullptr};
+    static const char* const names[] = {"gk1", "gk2", "gpk1", "gpk2", "gk1d", "gk2d", "gpk1d", "gpk2d", nullptr};
     return names;
 }
 
@@ -441,7 +447,7 @@ int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, fl
         for (const Candidate& c : kCandidates) {
             if (c.pooled != (pooled && pass == 1)) continue;
             if (p.Kg <= 64 * (c.kpl - 1)) continue;
-            if (pin && strcmp(pin, c.name) != 0) continue;
+            if (pin ? strcmp(pin, c.name) != 0 : !c.by_model) continue;
             const Plan pl = c.plan(p, c.pooled != pooled ? 2 : (can_split && !c.pooled ? 1 : 0));
             if (pl.cost < 0.0) continue;
             if (!best || pl.cost < best_plan.cost) {

@@ -20,29 +20,30 @@ struct WideCfg {
 };
 
 // One tap of one channel: xv holds the 64 rows' elements, m their nonzero mask, wt the lane's
-// filter values.  Four blocks of 16 rows, each guarded by one scalar test.
-template <int KPL>
+// filter values.  Four blocks of 16 rows, each guarded by one scalar test (DENSE: no tests, for maps
+// with so few zeros that hardly a 16-row block is empty).
+template <int KPL, bool DENSE = false>
 __device__ __forceinline__ void tap_blocks(const float xv, const unsigned long long m,
                                            const float (&wt)[KPL], v16f (&acc)[KPL][4])
 {
     unsigned lo = (unsigned)m, hi = (unsigned)(m >> 32);
     asm volatile("" : "+s"(lo), "+s"(hi));   // keep the four tests 32-bit scalar compares
-    if (lo & 0xFFFFu) {
+    if (DENSE || (lo & 0xFFFFu)) {
 #pragma unroll
         for (int i = 0; i < KPL; ++i)
             acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][0], 2, 0, 0);
     }
-    if (lo & 0xFFFF0000u) {
+    if (DENSE || (lo & 0xFFFF0000u)) {
 #pragma unroll
         for (int i = 0; i < KPL; ++i)
             acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][1], 2, 1, 0);
     }
-    if (hi & 0xFFFFu) {
+    if (DENSE || (hi & 0xFFFFu)) {
 #pragma unroll
         for (int i = 0; i < KPL; ++i)
             acc[i][2] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][2], 2, 2, 0);
     }
-    if (hi & 0xFFFF0000u) {
+    if (DENSE || (hi & 0xFFFF0000u)) {
 #pragma unroll
         for (int i = 0; i < KPL; ++i)
             acc[i][3] = __builtin_amdgcn_mfma_f32_16x16x1f32(xv, wt[i], acc[i][3], 2, 3, 0);

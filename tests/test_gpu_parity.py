@@ -353,6 +353,31 @@ def test_gen_chunk_split_across_workgroups(device, monkeypatch, shp, split):
         check_pool_forward(layer, x, w, integer_exact=True)
 
 
+def test_split_launches_on_two_streams_do_not_share_scratch(device):
+    """Every stream has its own scratch buffer for the partial sums: split launches of different
+    layers enqueued on two streams at the same time give what each gives alone."""
+    shp_a = (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None)
+    shp_b = (1, 256, 14, 14, 256, 3, 3, 1, 1, 1, None)
+    la, xa, wa = _mk(185, shp_a)
+    lb, xb, wb = _mk(186, shp_b)
+    xad, wad, xbd, wbd = to_dev(xa), to_dev(wa), to_dev(xb), to_dev(wb)
+    ref_a = sconv.sconv_forward(xad, wad, 1, 1, 1, relu=True)
+    ref_b = sconv.sconv_forward(xbd, wbd, 1, 1, 1, relu=True)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a = [torch.empty_like(ref_a) for _ in range(20)]
+    outs_b = [torch.empty_like(ref_b) for _ in range(20)]
+    for oa, ob in zip(outs_a, outs_b):
+        with torch.cuda.stream(s1):
+            sconv.sconv_forward(xad, wad, 1, 1, 1, relu=True, out=oa)
+        with torch.cuda.stream(s2):
+            sconv.sconv_forward(xbd, wbd, 1, 1, 1, relu=True, out=ob)
+    torch.cuda.synchronize()
+    for oa, ob in zip(outs_a, outs_b):
+        assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b)
+    check_forward(la, xa, wa, relu=True)
+
+
 def test_split_plan_is_left_out_while_a_fresh_stream_records_a_graph(device):
     """The scratch buffer of a split plan is allocated per stream on first use, which cannot happen
     during graph capture: a capture on a stream that has none must still give the right result."""
@@ -372,6 +397,27 @@ def test_split_plan_is_left_out_while_a_fresh_stream_records_a_graph(device):
         g.replay()
         torch.cuda.synchronize()
         assert (np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
+@pytest.mark.parametrize("geom", ["gk1d", "gk2d", "gpk1d", "gpk2d"])
+@pytest.mark.parametrize("shp", [
+    (2, 20, 11, 11, 70, 5, 5, 1, 0, 1, (2, 2, 2)),
+    (1, 30, 9, 13, 130, 3, 4, 2, 1, 1, (2, 2, 2)),
+])
+def test_gen_dense_candidates(device, monkeypatch, shp, geom):
+    """The general matrix-core kernel without zero tests gives the same sums."""
+    monkeypatch.setenv("SCONV_VARIANT", "gen")
+    monkeypatch.setenv("SCONV_GEN_GEOM", geom)
+    if geom.startswith("gp"):
+        layer, x, w = _mk(190, shp)
+        check_pool_forward(layer, x, w)
+        layer, x, w = _mk(191, shp, integer=True)
+        check_pool_forward(layer, x, w, integer_exact=True)
+    else:
+        layer, x, w = _mk(192, shp)
+        check_forward(layer, x, w, relu=True)
+        layer, x, w = _mk(193, shp, integer=True)
+        check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
 @pytest.mark.parametrize("geom", ["q32t7d", "q32k1d", "q32k2d"])
