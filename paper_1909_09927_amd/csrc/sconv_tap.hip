@@ -395,7 +395,9 @@ Plan plan_geom(const Problem& p, int split)
     const int nchunks = p.Cg / G::CCH;
     // a launch that leaves half of the compute units idle even with one tile and 64 filters per
     // workgroup
-    const bool small = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.N * p.G < 128;
+    const long long tile_wgs = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.N * p.G;
+    const bool small = tile_wgs < 128;
+    const bool large = tile_wgs >= 512;   // several rounds of workgroups
     const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     auto split_fits = [&](int nss) {
         return !G::POOL && nss <= nchunks && nss * part_bytes <= kSplitScratchBytes &&
@@ -424,11 +426,31 @@ Plan plan_geom(const Problem& p, int split)
             int red_steps = 0;   // of the slice reduction: the kernel's own loop
             for (int active = ncs; active > 1; ++red_steps) active -= rw < active / 2 ? rw : active / 2;
             const long long slots = 256LL * occ;
-            const long long rounds = (wgs + slots - 1) / slots;
             const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
-            double r = per_cu * nwv / 4.0;                                         // wavefronts per SIMD
-            if (r < 4.0) r = 4.0;
-            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) / nss +
+            double rounds, r, t_chunk;
+            if (large) {
+                // Launches of several rounds, fitted to measured times.  Rounds as a fraction: in a
+                // last, partly filled round the resident workgroups run faster.  r: time for the wv
+                // wavefronts of a SIMD to get through one channel each, in units of t_channel - a
+                // wavefront's test - broadcast - multiply chain waits on itself, so resident
+                // wavefronts overlap (2.9 at four per SIMD, 4.7 at eight).  The barrier and staging
+                // wait per chunk shows at low residency (2900 clocks at four per SIMD) and hides at
+                // high (400 at eight).
+                rounds = wgs >= slots ? (double)wgs / slots : 1.0;
+                double wv = per_cu * nwv / 4.0;
+                if (wv < 2.0) wv = 2.0;
+                r = 1.2 + 0.44 * wv;
+                t_chunk = 2900.0 - 625.0 * (wv - 4.0);
+                t_chunk = t_chunk > 2900.0 ? 2900.0 : (t_chunk < 400.0 ? 400.0 : t_chunk);
+            } else {
+                // up to a round or two: whole rounds, SIMDs saturating at four resident wavefronts
+                rounds = (double)((wgs + slots - 1) / slots);
+                r = per_cu * nwv / 4.0;
+                if (r < 4.0) r = 4.0;
+                t_chunk = 0.0;
+            }
+            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + nchunks * t_chunk +
+                                          per_cu * stage_clocks) / nss +
                                 red_steps * 2000.0 +                             // reduction steps
                                 (nss > 1 ? 9000.0 : 0.0);                        // second kernel
             if (best.cost < 0.0 || cost < best.cost) {
