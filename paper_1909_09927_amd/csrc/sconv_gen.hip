@@ -440,7 +440,7 @@ int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, fl
     const Candidate* best = nullptr;
     Plan best_plan;
     // a split of the chunks across workgroups needs the stream's scratch buffer
-    const bool can_split = split_scratch(stream) != nullptr;
+    const bool can_split = split_scratch_possible(stream);
     // A pooled layer: first the plain kernel with the split (the second kernel pools), which the
     // model offers for small launches only; the pooled kernel when that does not apply.
     for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {

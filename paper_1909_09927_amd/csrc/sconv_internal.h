@@ -85,6 +85,9 @@ void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss = nullptr);
 // no buffer yet, or the allocation failed): then the caller plans without a split.
 constexpr size_t kSplitScratchBytes = size_t(64) << 20;
 float* split_scratch(hipStream_t stream);
+// Whether split_scratch can succeed (the buffer exists, or the stream is not recording a graph):
+// asked while planning, so that the buffer is only allocated for a launch that is really split.
+bool split_scratch_possible(hipStream_t stream);
 int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y,
                         hipStream_t stream);
 

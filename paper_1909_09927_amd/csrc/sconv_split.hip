@@ -62,6 +62,19 @@ std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;   // under the dispatc
 
 }  // namespace
 
+bool split_scratch_possible(hipStream_t stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (g_scratch.count(std::make_pair(dev, stream))) return true;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess || st != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return true;
+}
+
 float* split_scratch(hipStream_t stream)
 {
     int dev = 0;

@@ -580,7 +580,7 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     const Candidate* best = nullptr;
     Plan best_plan;
     // a channel split across workgroups needs the stream's scratch buffer
-    const bool can_split = split_scratch(stream) != nullptr;
+    const bool can_split = split_scratch_possible(stream);
     // A pooled layer: first the plain tiles with the split (the second kernel pools), which the
     // model offers for small launches only; the pooled tiles when none applies.
     for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {
