@@ -63,32 +63,60 @@ __global__ __launch_bounds__(kEncodeBlock) void encode_kernel(Problem p, int pec
 
     float* vrow = values + row * p.L;
     int32_t* irow = index + row * p.L;
-    int cnt = 0;
-    for (int col0 = 0; col0 < p.L; col0 += 64) {
-        const int col = col0 + lane;
-        float v = 0.0f;
-        if (col < p.L) {
-            const int ih = ih0 + r, iw = iw0 + s;
-            if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
-                v = xg[((long long)c * p.H + ih) * p.W + iw];
+
+    // The compacted (value, column) pairs pass through a 128-slot ring in LDS (one per wavefront)
+    // and leave it 64 at a time, so every store to HBM is one whole run of 64 consecutive slots
+    // of the row instead of a ragged piece per 64 columns.
+    __shared__ float ring_v[kEncodeBlock / 64][128];
+    __shared__ int32_t ring_i[kEncodeBlock / 64][128];
+    float* rv = ring_v[threadIdx.x >> 6];
+    int32_t* ri = ring_i[threadIdx.x >> 6];
+
+    int cnt = 0;       // nonzeros found so far (wavefront-uniform)
+    int flushed = 0;   // slots of the row already stored (a multiple of 64)
+    constexpr int UN = 4;   // column groups loaded together before any of them is ranked
+    for (int col0 = 0; col0 < p.L; col0 += 64 * UN) {
+        float v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int col = col0 + 64 * u + lane;
+            v[u] = 0.0f;
+            if (col < p.L) {
+                const int ih = ih0 + r, iw = iw0 + s;
+                if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
+                    v[u] = xg[((long long)c * p.H + ih) * p.W + iw];
+            }
+            s += ds;
+            if (s >= p.S) { s -= p.S; r += 1; }
+            r += dr;
+            if (r >= p.R) { r -= p.R; c += 1; }
+            c += dc;
         }
-        const bool nz = v != 0.0f;  // +0, -0 dropped; denormals, negatives kept
-        const unsigned long long mask = __ballot(nz);
-        if (nz) {
-            const int slot = cnt + lanes_below(mask, lane);
-            vrow[slot] = v;
-            irow[slot] = col;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const bool nz = v[u] != 0.0f;  // +0, -0 dropped; denormals, negatives kept
+            const unsigned long long mask = __ballot(nz);
+            if (nz) {
+                const int slot = (cnt + lanes_below(mask, lane)) & 127;
+                rv[slot] = v[u];
+                ri[slot] = col0 + 64 * u + lane;
+            }
+            cnt += __popcll(mask);
+            __builtin_amdgcn_wave_barrier();
+            if (cnt - flushed >= 64) {   // at most 127 pairs are pending: one run leaves
+                const int slot = (flushed + lane) & 127;
+                vrow[flushed + lane] = rv[slot];
+                irow[flushed + lane] = ri[slot];
+                flushed += 64;
+                __builtin_amdgcn_wave_barrier();
+            }
         }
-        cnt += __popcll(mask);
-        s += ds;
-        if (s >= p.S) { s -= p.S; r += 1; }
-        r += dr;
-        if (r >= p.R) { r -= p.R; c += 1; }
-        c += dc;
     }
-    for (int slot = cnt + lane; slot < p.L; slot += 64) {
-        vrow[slot] = 0.0f;
-        irow[slot] = 0;
+    // what is left in the ring, then zeros up to the end of the row
+    for (int slot = flushed + lane; slot < p.L; slot += 64) {
+        const bool live = slot < cnt;
+        vrow[slot] = live ? rv[slot & 127] : 0.0f;
+        irow[slot] = live ? ri[slot & 127] : 0;
     }
     if (lane == 0) count[row] = (!pecr && cnt == 0) ? -1 : cnt;
 }
