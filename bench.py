@@ -135,11 +135,25 @@ class DeviceLayer:
             self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y)
 
 
+def ramp_up(fn, seconds: float = 0.03) -> None:
+    """Untimed set-up before a timed region: keeps the GPU busy with the workload itself for
+    `seconds`.  An idle GPU runs its first milliseconds at lower clocks - the same 50-us layer measured
+    54, 50, 48 us in three successive 2-ms rounds - and a handful of warm-up launches does not get past
+    that."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+
+
 def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
     """Average launch duration in ms, events on the launch stream (torch's current stream): the
     median of three back-to-back rounds of `iters` launches, so that one stall of the machine (seen
     now and then on 20-us layers) does not pass for the kernel's time."""
     import torch
+    ramp_up(dl.run)
     for _ in range(warmup):
         dl.run()
     torch.cuda.synchronize()
@@ -220,6 +234,7 @@ def run_headline(args) -> None:
         for dl in dls:
             dl.run()
 
+    ramp_up(step, 0.1)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -362,6 +377,7 @@ def run_shape(args) -> None:
 
 def _time(fn, iters, warmup) -> float:
     import torch
+    ramp_up(fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
