@@ -138,10 +138,11 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  * string, for benchmark records and profiles).  pooled != 0 asks about sconv_pool_forward.
  * Variants: "quad1x1" (1x1 / stride 1 / pad 0, channels per group a multiple of 64), "quad3x3"
  * (3x3 / stride 1 / pad 1, channels per group a multiple of 16), "wide3x3" (3x3 of any stride and
- * padding, channels per group a multiple of 8), "tap3x3" (3x3 / pad 1, stride 1 or 2, channels a
- * multiple of 16; preferred for the deep layers - maps up to 14 wide with 128 or more filters or
- * 256 or more channels per group, maps up to 28 wide with 512 or more channels - and for launches
- * too small to fill the matrix kernels' tiles),
+ * padding, channels per group a multiple of 8; also preferred for maps up to 14 wide with 128 or
+ * more filters and fewer than 256 channels per group), "tap3x3" (3x3 / pad 1, stride 1 or 2,
+ * channels a multiple of 16; preferred for the deep layers - maps up to 14 wide with 256 or more
+ * channels per group, maps up to 28 wide with 512 or more - and for launches too small to fill the
+ * matrix kernels' tiles),
  * "gen" (every other shape with a kernel of at most 15x15 and, when pooling, a 2x2 / stride 2
  * window), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes

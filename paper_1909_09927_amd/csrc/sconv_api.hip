@@ -165,9 +165,11 @@ static Variant choose(const Problem& p, bool pooled)
         // The same one stage earlier, 512 channels on maps up to 28 wide: 1.14x faster at 75 % zeros.
         if (p.W <= 28 && p.Cg >= 512 && !pooled && tap_supported(p, pooled)) return V_TAP;
         // Maps up to 14 wide with 128 or more filters per group and shorter channel loops: the
-        // 16-row granule (no tile-geometry waste) measures fastest up to 65 % zeros, the vector
-        // kernel from 70 % up (1.1x at 70 %, 1.5x at 90 %) - and these are deep layers.
-        if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills && tap_supported(p, pooled)) return V_TAP;
+        // 16-row granule has no tile-geometry waste there and its time is flat in the zero ratio;
+        // the vector kernel is level with it at 70 % zeros, 1.15x faster at 90 % and 2x slower on
+        // a dense map, so the choice that cannot go badly wrong is made here and sconv_tune
+        // takes the rest.
+        if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills) return V_WIDE;
         // Few tile-wavefronts (2 output rows x 28 columns x 64 filters each): the vector kernel's
         // smaller tiles spread over more of the chip and measure faster at small batch.
         const long long quad_tiles = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *

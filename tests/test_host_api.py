@@ -106,7 +106,7 @@ def test_strerror_and_variant_name():
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 2, 0)) == "wide3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 512, 7, 7, 512, 3, 3, 1, 1)) == "tap3x3"
-    assert sconv.sconv_variant_name(sconv.make_desc(32, 896, 14, 14, 896, 3, 3, 1, 1, 7)) == "tap3x3"
+    assert sconv.sconv_variant_name(sconv.make_desc(32, 896, 14, 14, 896, 3, 3, 1, 1, 7)) == "wide3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(8, 512, 28, 28, 512, 3, 3, 1, 1)) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(8, 256, 28, 28, 256, 3, 3, 1, 1)) == "quad3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 512, 14, 14, 512, 3, 3, 1, 1, pool=(2, 2, 2)), True) == "tap3x3"
