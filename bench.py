@@ -211,6 +211,23 @@ def cpu_baseline(config_index: int, batch: int = 2) -> dict:
                       f"{secs:.2f} s wall, about {secs * oracle.threads():.0f} core-seconds)"}
 
 
+def cpu_sparse_baseline(config_index: int) -> dict:
+    """The oracle's zero-skipping path as it stands (Algorithm 1 into the materialised format, then
+    Algorithm 2 over it; one thread, fp64 sums) on the config's first layer at batch 1."""
+    import oracle
+    layer, x, w = workloads.make_layer_inputs(config_index, 0, 1)
+    t0 = time.perf_counter()
+    values, index, count = oracle.encode(x, w.shape, 0, layer.stride, layer.pad, layer.groups)
+    t1 = time.perf_counter()
+    oracle.spmv(values, index, count, w, x.shape, layer.stride, layer.pad, layer.groups)
+    t2 = time.perf_counter()
+    dense = 2.0 * layer.K * layer.OH * layer.OW * layer.Cg * layer.R * layer.S
+    nz = 2.0 * float(np.maximum(count, 0).sum()) * (layer.K // layer.groups)
+    return {"value": round(dense / (t2 - t0) / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
+            "nonzero_mac_gflops": round(nz / (t2 - t0) / 1e9, 2), "cores": 1, "kind": "oracle, zero-skipping path",
+            "sample": f"{layer.name} at batch 1: encode {t1 - t0:.2f} s + sparse products {t2 - t1:.2f} s"}
+
+
 def paper_context() -> dict:
     return {"hardware": "NVIDIA GeForce RTX 2080Ti, CUDA 10.2, cuDNN 7.6.5 (paper, Table 2)",
             "note": "relative speedups only; context, not a target",
@@ -289,6 +306,7 @@ def run_headline(args) -> None:
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ci)
+        out["cpu_sparse_oracle"] = cpu_sparse_baseline(ci)
     print(json.dumps(out), flush=True)
 
 
