@@ -166,6 +166,18 @@ def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
         e1.record()
         e1.synchronize()
         rounds.append(e0.elapsed_time(e1) / iters)
+    # one launch on its own (the stream idle before and after): the latency of a single call,
+    # median of five
+    singles = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dl.run()
+        e1.record()
+        e1.synchronize()
+        singles.append(e0.elapsed_time(e1))
+    dl.single_launch_ms = sorted(singles)[2]
     return sorted(rounds)[1]
 
 
@@ -175,6 +187,7 @@ def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
     t_valu = work["nz_flops"] / (FP32_VECTOR_PEAK_TF * 1e12)
     return {
         "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "plan": dl.plan, "ms": round(ms, 5),
+        "single_launch_ms": round(getattr(dl, "single_launch_ms", float("nan")), 5),
         "zero_ratio": round(work["zero_ratio"], 4),
         "dense_equiv_gflops": round(work["dense_flops"] / t / 1e9, 1),
         "nonzero_mac_gflops": round(work["nz_flops"] / t / 1e9, 1),
