@@ -59,6 +59,36 @@ def test_encode_ecr_bit_exact(device, shp):
     check_encode(layer, x, w.shape, sconv.FMT_ECR)
 
 
+ENCODE_LARGE = [
+    (1, 5, 60, 61, 4, 3, 3, 1, 1, 1, (2, 2, 2)),        # a map above the tiled kernel's threshold, ragged last tile
+    (2, 8, 50, 47, 4, 5, 3, 2, 2, 2, (3, 3, 2)),        # stride 2, grouped, overlapping 3x3 pooling windows
+    (1, 400, 15, 15, 8, 1, 1, 1, 0, 1, (2, 2, 1)),      # long 1x1 channel loop: several staged chunks
+    (1, 3, 70, 9, 2, 7, 7, 3, 3, 1, (2, 1, 1)),         # tall narrow map, large kernel, stride 3
+]
+
+
+@pytest.mark.parametrize("which", ["tile", "rows"])
+@pytest.mark.parametrize("shp", SMALL + ENCODE_LARGE)
+def test_encode_both_kernels_bit_exact(device, monkeypatch, shp, which):
+    """The tiled conversion kernel (input box staged in LDS) and the window-per-wavefront one, each
+    forced on every shape (a box too large for the staging buffer falls back to the latter)."""
+    monkeypatch.setenv("SCONV_ENCODE", which)
+    layer, x, w = _mk(120, shp)
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    check_encode(layer, x, w.shape, sconv.FMT_PECR)
+    layer, x, w = _mk(121, shp, z=0.0)
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    layer, x, w = _mk(122, shp, z=1.0)
+    check_encode(layer, x, w.shape, sconv.FMT_PECR)
+
+
+@pytest.mark.parametrize("shp", ENCODE_LARGE)
+def test_encode_large_maps_bit_exact(device, shp):
+    layer, x, w = _mk(123, shp)
+    check_encode(layer, x, w.shape, sconv.FMT_ECR)
+    check_encode(layer, x, w.shape, sconv.FMT_PECR)
+
+
 @pytest.mark.parametrize("shp", SMALL)
 def test_encode_pecr_bit_exact(device, shp):
     layer, x, w = _mk(102, shp)
