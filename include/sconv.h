@@ -158,8 +158,8 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  * every variant and every decomposition that covers the descriptor on the caller's operands - each
  * one untimed launch and three timed ones between two events on hip_stream, the static choice and
  * the four fastest then again for about a millisecond each - and remembers the fastest (the static
- * choice unless another measures 3 % faster) for this exact descriptor (and pooled flag) in a host-side table; later sconv_forward /
- * sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
+ * choice unless another measures 3 % faster) for this exact descriptor (and pooled flag) in a
+ * host-side table; later sconv_forward / sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
  * models' choice.  The table is per process, guarded by the library's lock, and holds no device
  * memory.
  *   pooled != 0: tune sconv_pool_forward (y_dev is [N][K][PH][PW]), else sconv_forward.
@@ -167,8 +167,9 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  *   flush_dev device, scratch, optional (NULL with flush_bytes 0): when given, its flush_bytes
  *            bytes are overwritten before every timed launch, so that no launch finds its operands
  *            in the caches (give it at least twice the last-level cache, 512 MiB); without it the
- *            launches run back to back and plans are ranked cache-warm.  The library never
- *            allocates: the scratch is the caller's and only used during this call.
+ *            launches run back to back and plans are ranked cache-warm.  This buffer is
+ *            the caller's and only used during this call (the library's own scratch, see the
+ *            top of this file, is allocated here if a split plan is tried and the stream has none).
  *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.
  * Unlike every other call this one SYNCHRONISES with hip_stream (it reads event times), so it
  * must not be called while the stream is being captured into a graph; call it once at set-up.
