@@ -290,7 +290,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     const Family fams[] = {
         {V_PW, pw_supported(p, pooled), no_geoms, 8, 16, 1},
         {V_TAP, tap_supported(p, pooled), tap_geoms(), 8, 16, 16},
-        {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16, 1},
+        {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16, 16},
         {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8, 1},
         {V_GEN, gen_supported(p, pooled), gen_geoms(), 4, 8, 16},
     };

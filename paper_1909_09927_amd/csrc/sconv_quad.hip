@@ -63,6 +63,8 @@ struct TapCfg {
     int CPW;            // channels per wavefront per chunk = CCH / NCS
     int tiles_x, tiles_y, ntiles;
     int tr;             // plain epilogue: transpose each output row through LDS (it fits)
+    int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
+                        // partial sums, stored into slice blockIdx.z % NSS of y
 };
 
 // x[l] <- x[l + 1] over the whole wavefront (lane 63 gets 0)
@@ -139,8 +141,11 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: scalar registers
     const int ts = wave % cfg.NT;                  // spatial tile slot
     const int cs = wave / cfg.NT;                  // channel slice
-    const int n = blockIdx.z / p.G;
-    const int g = blockIdx.z - n * p.G;
+    const int ss = blockIdx.z % cfg.NSS;           // channel range of the workgroup
+    const int ng = blockIdx.z / cfg.NSS;
+    const int n = ng / p.G;
+    const int g = ng - n * p.G;
+    if (!G::POOL) y += (size_t)ss * p.N * p.K * p.OH * p.OW;   // split: slice ss of the partial sums
     const int kb0 = blockIdx.y * G::KB;            // first filter of the block inside the group
     const int tile = blockIdx.x * cfg.NT + ts;
     const bool tile_ok = tile < cfg.ntiles;
@@ -200,15 +205,16 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
     };
 
     const int nchunks = (p.Cg + G::CCH - 1) / G::CCH;
-    fetch_chunk(0);
+    const int ch0 = ss * nchunks / cfg.NSS, ch1 = (ss + 1) * nchunks / cfg.NSS;   // this workgroup's chunks
+    fetch_chunk(ch0 * G::CCH);
     float xn[G::NX];
-    load_x(cs * cfg.CPW, xn);
+    load_x(ch0 * G::CCH + cs * cfg.CPW, xn);
 
-    for (int ch = 0; ch < nchunks; ++ch) {
+    for (int ch = ch0; ch < ch1; ++ch) {
         float* buf = lds + (ch & 1) * G::BUF;
         store_chunk(buf);
         __syncthreads();
-        if (ch + 1 < nchunks) fetch_chunk((ch + 1) * G::CCH);
+        if (ch + 1 < ch1) fetch_chunk((ch + 1) * G::CCH);
 
         const int cbase = ch * G::CCH + cs * cfg.CPW;   // this wavefront's channels of the chunk
         for (int cc = 0; cc < cfg.CPW; ++cc) {
@@ -387,6 +393,7 @@ struct Plan {
     int nwv = 0;
     int kblocks = 0;
     size_t lds_bytes = 0;
+    int nss = 1;          // workgroups per tile along the channels (partial sums through scratch)
 };
 
 // Decomposition of one launch.  The work is ntiles x kblocks x images x groups tile-wavefronts,
@@ -415,8 +422,14 @@ Plan plan_geom(const Problem& p)
     const double t_channel = 200.0 + 9.0 * groups + 0.88 * 9.0 * G::TH * G::NQ * G::KPL * 9.2;
     const double stage_clocks = (double)G::KB * p.Cg * 36.0 / 64.0;
 
-    int pin_nwv = 0, pin_ncs = 0;   // tuning aid: SCONV_QUAD_SPLIT="nwv,ncs"
-    pinned_split("SCONV_QUAD_SPLIT", &pin_nwv, &pin_ncs);
+    int pin_nwv = 0, pin_ncs = 0, pin_nss = 0;   // tuning aid: SCONV_QUAD_SPLIT="nwv,ncs[,nss]"
+    pinned_split("SCONV_QUAD_SPLIT", &pin_nwv, &pin_ncs, &pin_nss);
+    // The channel split across workgroups (see sconv_split.hip) is only ever pinned here - by
+    // sconv_tune or the environment: the static rules send small launches to the vector kernel.
+    const int nss = pin_nss > 1 ? pin_nss : 1;
+    if (nss > 1 && (G::POOL || nss > p.Cg / G::CCH || (long long)p.N * p.G * nss > 65535 ||
+                    (size_t)nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes))
+        return best;
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
@@ -429,7 +442,9 @@ Plan plan_geom(const Problem& p)
             // a 7-row tile's long reduction and epilogue need 32 channels per slice to pay off
             if (!pin_nwv && G::TH >= 7 && ncs > 1 && p.Cg / ncs < 32) continue;
             const int occ = nwv == 16 ? occupancy<G, G::MAXW>(lds_bytes) : occupancy<G, 8>(lds_bytes);
-            const long long wgs = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            const long long wgs1 = (long long)((cfg.ntiles + nt - 1) / nt) * kblocks * p.N * p.G;
+            if (nss > 1 && wgs1 >= 512 && current_pin()) continue;   // sconv_tune: not worth a trial
+            const long long wgs = wgs1 * nss;
             const long long slots = 256LL * occ;
             const long long rounds = (wgs + slots - 1) / slots;
             const double per_cu = wgs >= slots ? occ : (double)((wgs + 255) / 256);  // resident workgroups
@@ -438,8 +453,9 @@ Plan plan_geom(const Problem& p)
             // issues 441 matrix instructions per channel and two of them are enough
             const double r_min = G::TH >= 7 ? 2.0 : 4.0;
             if (r < r_min) r = r_min;
-            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) +
-                                (ncs - 1) * 8000.0;   // reduction steps and barrier-bound short slices
+            const double cost = rounds * ((double)p.Cg / ncs * t_channel * r + per_cu * stage_clocks) / nss +
+                                (ncs - 1) * 8000.0 +  // reduction steps and barrier-bound short slices
+                                (nss > 1 ? 9000.0 : 0.0);
             if (best.cost < 0.0 || cost < best.cost) {
                 best.cost = cost;
                 best.cfg = cfg;
@@ -450,6 +466,8 @@ Plan plan_geom(const Problem& p)
                 best.nwv = nwv;
                 best.kblocks = kblocks;
                 best.lds_bytes = lds_bytes;
+                best.nss = nss;
+                best.cfg.NSS = nss;
             }
         }
     }
@@ -462,13 +480,28 @@ int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w
 {
     const size_t lds_bytes = pl.lds_bytes;
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
-    const unsigned gz = (unsigned)(p.N * p.G);
-    if (gz > 65535u || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
-    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, gz);
-    if constexpr (G::MAXW == 16) {
-        if (pl.nwv == 16) return launch_nwv<G, 16>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+    const long long gz = (long long)p.N * p.G * pl.nss;
+    if (gz > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
+    const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
+    Problem q = p;
+    float* out = y;
+    if (pl.nss > 1) {
+        // raw partial sums of every channel range into the scratch slices; the second kernel below
+        // adds them and applies ReLU
+        if (G::POOL || pl.nss > p.Cg / G::CCH ||
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            return SCONV_EUNSUPPORTED;
+        out = split_scratch(stream);
+        if (!out) return SCONV_EUNSUPPORTED;
+        q.relu = 0;
     }
-    return launch_nwv<G, 8>(p, pl.cfg, grid, lds_bytes, x, w, y, stream);
+    int rc;
+    if (G::MAXW == 16 && pl.nwv == 16)
+        rc = launch_nwv<G, G::MAXW>(q, pl.cfg, grid, lds_bytes, x, w, out, stream);
+    else
+        rc = launch_nwv<G, 8>(q, pl.cfg, grid, lds_bytes, x, w, out, stream);
+    if (rc != SCONV_OK || pl.nss == 1) return rc;
+    return launch_split_reduce(p, false, out, pl.nss, y, stream);
 }
 
 // Geometries.  Maps wider than 14: rows of 32 lanes, 28 output columns (7 quads), 2 output rows.

@@ -357,6 +357,25 @@ def test_tap_channel_split_across_workgroups(device, monkeypatch, shp, split):
         check_pool_forward(layer, x, w, integer_exact=True)
 
 
+@pytest.mark.parametrize("geom,split", [("q32k1", "8,4,2"), ("q32k1d", "16,4,4"), ("q32t7", "8,2,2"),
+                                        ("q16k2", "16,2,4"), ("q32k2", "8,8,2")])
+@pytest.mark.parametrize("shp", [
+    (1, 64, 28, 30, 130, 3, 3, 1, 1, 1, None),          # wide map, ragged filter block
+    (2, 128, 14, 14, 140, 3, 3, 1, 1, 2, None),         # map up to 14 wide, grouped
+])
+def test_quad_channel_split_across_workgroups(device, monkeypatch, shp, geom, split):
+    """The matrix-core 3x3 kernel with a tile's channels split over workgroups (a pinned plan: a
+    geometry that does not fit the map's width falls back to another kernel, which must match too)."""
+    monkeypatch.setenv("SCONV_VARIANT", "quad")
+    monkeypatch.setenv("SCONV_QUAD_GEOM", geom)
+    monkeypatch.setenv("SCONV_QUAD_SPLIT", split)
+    layer, x, w = _mk(187, shp)
+    check_forward(layer, x, w, relu=True)
+    check_forward(layer, x, w, relu=False)
+    layer, x, w = _mk(188, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+
+
 GEN_SPLIT = [
     (1, 20, 11, 11, 50, 5, 5, 1, 0, 1, (2, 2, 2)),      # 500 columns: 8 chunks, the last one ragged
     (1, 480, 14, 14, 192, 1, 1, 1, 0, 1, (2, 2, 2)),    # 1x1 with a channel count off the 64 grid
