@@ -31,6 +31,7 @@
 #ifndef SCONV_H
 #define SCONV_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus

@@ -24,6 +24,18 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
 
 
+def test_header_is_self_contained_c_and_cpp(tmp_path):
+    """include/sconv.h compiles on its own as C99 and as C++ (a C caller needs nothing else)."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "sconv.h")
+    if shutil.which("gcc"):
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                       check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+
+
 def test_output_dims_and_sizes():
     d = sconv.make_desc(2, 16, 28, 28, 32, 3, 3, 1, 1)
     assert sconv.sconv_output_dims(d) == (28, 28, 0, 0)
