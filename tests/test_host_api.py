@@ -36,6 +36,38 @@ def test_header_is_self_contained_c_and_cpp(tmp_path):
         subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
 
 
+def test_a_plain_c_program_links_and_calls_the_library(tmp_path):
+    """The boundary is a C ABI: a C99 program with only sconv.h links libsconv.so and calls it."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    src = tmp_path / "client.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "sconv.h"
+int main(void) {
+    sconv_desc_t d;
+    memset(&d, 0, sizeof d);
+    d.N = 2; d.C = 16; d.H = 28; d.W = 28; d.K = 32; d.R = 3; d.S = 3; d.stride = 1; d.pad = 1; d.groups = 1;
+    d.pool_h = 2; d.pool_w = 2; d.pool_stride = 2;
+    int32_t oh, ow, ph, pw;
+    if (sconv_output_dims(&d, &oh, &ow, &ph, &pw) != SCONV_OK) return 1;
+    d.stride = 0;
+    int rc = sconv_forward(&d, (const float*)16, (const float*)16, (float*)16, NULL);
+    printf("%d %d %d %d %d %s\n", oh, ow, ph, pw, rc, sconv_strerror(rc));
+    return 0;
+}
+''')
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(sconv.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:libsconv.so", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 5)
+    assert out[:5] == ["28", "28", "14", "14", str(sconv.SCONV_EINVAL)] and "invalid" in out[5]
+
+
 def test_output_dims_and_sizes():
     d = sconv.make_desc(2, 16, 28, 28, 32, 3, 3, 1, 1)
     assert sconv.sconv_output_dims(d) == (28, 28, 0, 0)
