@@ -95,6 +95,20 @@ def flush_buffer():
     return _flush
 
 
+_workspaces = {}
+
+
+def lend_workspace() -> None:
+    """The optional workspace of the library (sconv_set_workspace), lent once per stream: 64 MiB, the
+    most sconv_workspace_size ever asks for.  With it small launches are split across workgroups."""
+    import torch
+    import paper_1909_09927_amd as sconv
+    key = torch.cuda.current_stream().cuda_stream
+    if key not in _workspaces:
+        _workspaces[key] = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        sconv.sconv_set_workspace(_workspaces[key])
+
+
 class DeviceLayer:
     """One layer's operands on the device, in `copies` rotating sets."""
 
@@ -103,6 +117,7 @@ class DeviceLayer:
         import paper_1909_09927_amd as sconv
         self.layer, self.N = layer, N
         self.sconv = sconv
+        lend_workspace()
         xd = torch.from_numpy(x).cuda()
         wd = torch.from_numpy(w).cuda()
         self.sets = []
@@ -517,6 +532,7 @@ def run_graph(args) -> None:
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
+        lend_workspace()             # the capture stream's own workspace: split plans in the graph too
         step()                       # warm-up on the capture stream
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
@@ -543,6 +559,7 @@ def run_chain(args) -> None:
     wds = [torch.from_numpy(w).cuda() for w in ws]
     outs, recs = [], []
     flush = flush_buffer() if TUNE else None
+    lend_workspace()
     for layer, wd in zip(workloads.CHAIN, wds):
         if TUNE:
             sconv.sconv_tune(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=flush)

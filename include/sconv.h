@@ -2,23 +2,14 @@
  * sconv: zero-skipping direct convolution (+ fused ReLU / max-pooling) for AMD MI355X (gfx950).
  *
  * C ABI of the GPU library.  All tensors are fp32 and contiguous; every pointer marked
- * "device" is HIP device memory owned by the caller.  Every entry point that launches work
- * enqueues it on the given HIP stream (a hipStream_t passed as void*; NULL = the default stream)
- * and returns without synchronising.  Outputs are overwritten, never accumulated into.
- *
- * Device memory of the library's own: one 64 MiB scratch buffer per device and stream, allocated
- * (hipMalloc) by the first forward or tuning call on that stream whose launch is small enough to
- * be split over more workgroups - the partial sums of the parts pass through it to a second,
- * small kernel (see sconv_forward) - and kept until the process ends.  Nothing else is allocated,
- * and nothing when no such launch occurs.  Consequences: launches enqueued on (or captured
- * from) one stream must run in that stream's order, as they share its buffer - replaying a graph
- * concurrently with other sconv work that was enqueued on the stream it was captured from is a
- * race; and a stream that is being captured into a graph before any eager call has given it a
- * buffer gets unsplit plans (correct, slower on batch-1 layers): make one eager call, or
- * sconv_tune, on the stream first.  Calls may come from several host threads
+ * "device" is HIP device memory owned by the caller.  The library allocates, frees and keeps
+ * no device memory.  Every entry point that launches work enqueues it on the given HIP stream
+ * (a hipStream_t passed as void*; NULL = the default stream) and returns without synchronising.
+ * Outputs are overwritten, never accumulated into.  Calls may come from several host threads
  * (planning and enqueueing are serialised inside the library); the only state kept between calls
- * is cached launch information (occupancy answers) for the device the first calls ran on, so one
- * process should drive one device.
+ * is cached launch information (occupancy answers) for the device the first calls ran on - so one
+ * process should drive one device -, the plans sconv_tune found and the workspaces lent with
+ * sconv_set_workspace.
  *
  * Notation follows Table 1 of the paper: feature map i_h x i_w (H x W here), kernel k_h x k_w
  * (R x S), pooling window p_h x p_w, convolution stride c_s, pooling stride p_s.  Several input
@@ -100,11 +91,12 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * pipe (groups of 6, 8, 16 and 16 elements) and skip a group only when all of its elements are zero, so a
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
- * A launch of fewer than 128 workgroups ("tap3x3" and "gen": deep layers at batch 1) is split
- * along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its
- * channel range into the stream's scratch buffer, and a second kernel on the same stream adds
- * them in a fixed order and applies ReLU (and the pooling of sconv_pool_forward).  Results stay
- * deterministic; the association of the fp32 sums differs from the unsplit kernel's.
+ * With a workspace lent for the stream (sconv_set_workspace), a launch of fewer than 128
+ * workgroups ("tap3x3" and "gen": deep layers at batch 1) is split along the channels over up to 16
+ * workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
+ * and a second kernel on the same stream adds them in a fixed order and applies ReLU (and the
+ * pooling of sconv_pool_forward).  Results stay deterministic; the association of the fp32 sums
+ * differs from the unsplit kernel's.
  *   x_dev device, in : [N][C][H][W]
  *   w_dev device, in : [K][C/G][R][S]
  *   y_dev device, out: [N][K][OH][OW]
@@ -133,6 +125,24 @@ int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float
  *   y_dev    device, out: [N][K][PH][PW]
  */
 int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev, void* hip_stream);
+
+/*
+ * Optional workspace.  Small launches (deep layers at batch 1: a handful of tiles) run 1.3-3.5x
+ * faster when the channels of a tile are split over several workgroups, whose partial sums pass
+ * through device scratch to a second kernel (see sconv_forward).  That scratch is the caller's:
+ *   sconv_workspace_size: bytes such a plan can use for this descriptor (0: none would; at most
+ *            64 MiB).  Host only.
+ *   sconv_set_workspace: lends ws_dev (bytes long, 16-byte aligned) to every later forward or tuning
+ *            call on hip_stream of the current device, until it is replaced or withdrawn
+ *            (ws_dev NULL, bytes 0).  A launch whose plan needs more than was lent, and every
+ *            launch on a stream without a workspace, runs unsplit (correct, slower on batch-1
+ *            layers).  The caller keeps the memory alive while such launches - or graphs captured
+ *            from them - can still run, and runs the launches that share a workspace in stream
+ *            order: concurrent launches on one workspace race.  Contents need no initialisation.
+ *            Host only; nothing is enqueued.
+ */
+int sconv_workspace_size(const sconv_desc_t* desc, int pooled, size_t* bytes);
+int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
 
 /*
  * Name of the kernel variant the two forward calls would pick for this descriptor (a static
@@ -169,8 +179,8 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  *            bytes are overwritten before every timed launch, so that no launch finds its operands
  *            in the caches (give it at least twice the last-level cache, 512 MiB); without it the
  *            launches run back to back and plans are ranked cache-warm.  This buffer is
- *            the caller's and only used during this call (the library's own scratch, see the
- *            top of this file, is allocated here if a split plan is tried and the stream has none).
+ *            the caller's and only used during this call.  Split plans are tried only when a
+ *            workspace is lent for hip_stream (sconv_set_workspace) - lend it first.
  *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.
  * Unlike every other call this one SYNCHRONISES with hip_stream (it reads event times), so it
  * must not be called while the stream is being captured into a graph; call it once at set-up.

@@ -62,8 +62,11 @@ def lib() -> ctypes.CDLL:
         L.sconv_plan_name.argtypes = [P(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
         L.sconv_strerror.argtypes = [ctypes.c_int]
         L.sconv_strerror.restype = ctypes.c_char_p
+        L.sconv_workspace_size.argtypes = [P(Desc), ctypes.c_int, P(ctypes.c_size_t)]
+        L.sconv_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
-                  "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name"):
+                  "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
+                  "sconv_workspace_size", "sconv_set_workspace"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -118,6 +121,28 @@ def sconv_plan_name(desc: Desc, pooled: bool = False) -> str:
 
 def sconv_tune_reset() -> None:
     lib().sconv_tune_reset()
+
+
+def sconv_workspace_size(desc: Desc, pooled: bool = False) -> int:
+    n = ctypes.c_size_t()
+    rc = lib().sconv_workspace_size(ctypes.byref(desc), 1 if pooled else 0, ctypes.byref(n))
+    if rc:
+        raise ValueError(f"sconv_workspace_size: {strerror(rc)}")
+    return int(n.value)
+
+
+def sconv_set_workspace(ws) -> None:
+    """Lends the device tensor `ws` (any dtype, contiguous) as the workspace of launches on torch's
+    current stream; None withdraws it.  The caller keeps the tensor alive."""
+    import torch
+    if ws is None:
+        rc = lib().sconv_set_workspace(None, 0, _stream())
+    else:
+        if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.is_contiguous()):
+            raise TypeError("ws must be a contiguous tensor in device memory")
+        rc = lib().sconv_set_workspace(ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
+    if rc:
+        raise RuntimeError(f"sconv_set_workspace: {strerror(rc)}")
 
 
 def _check_dev(t, dtype, what):

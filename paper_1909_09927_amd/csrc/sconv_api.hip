@@ -192,6 +192,7 @@ static int launch_variant(Variant v, const PlanPin* pin, const Problem& p, bool 
                           const float* w, float* y, hipStream_t s)
 {
     g_pin = pin;
+    split_scratch_select(s);   // the workspace lent for this stream, if any
     int rc = SCONV_EUNSUPPORTED;
     switch (v) {
     case V_PW: rc = launch_pointwise(p, pooled, x, w, y, s); break;
@@ -487,6 +488,32 @@ extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_d
     if (rc) return rc;
     if (pooled && (int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
     return tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, Flush{flush_dev, flush_bytes}, best_ms);
+}
+
+extern "C" int sconv_workspace_size(const sconv_desc_t* desc, int pooled, size_t* bytes)
+{
+    if (!bytes) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, pooled != 0, &p);
+    if (rc) return rc;
+    *bytes = 0;
+    // only the kernels that can split a launch use it, and only for launches of a few hundred
+    // workgroups: up to 16 slices of the convolution tensor, never more than the cap
+    if (!tap_supported(p, pooled != 0) && !gen_supported(p, pooled != 0) && !quad_supported(p, pooled != 0))
+        return SCONV_OK;
+    const size_t slice = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
+    size_t need = 16 * slice;
+    if (need > kSplitWorkspaceCap) need = kSplitWorkspaceCap;
+    *bytes = (need + 255) / 256 * 256;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream)
+{
+    if ((ws_dev == nullptr) != (bytes == 0)) return SCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(ws_dev) % 16) return SCONV_EINVAL;
+    std::lock_guard<std::mutex> lock(g_lock);
+    return split_workspace_set(ws_dev, bytes, (hipStream_t)hip_stream);
 }
 
 extern "C" int sconv_tune_reset(void)

@@ -277,7 +277,7 @@ Plan plan_geom(const Problem& p, int split)
     const bool small = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.G < 128;
     const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     auto split_fits = [&](int nss) {
-        return !POOL && nss <= nchunks && nss * part_bytes <= kSplitScratchBytes && (long long)p.G * nss <= 65535;
+        return !POOL && nss <= nchunks && nss * part_bytes <= split_scratch_bytes() && (long long)p.G * nss <= 65535;
     };
     // a pinned decomposition is priced as it is; the model ranks the unsplit decompositions and
     // splits the winner afterwards
@@ -367,7 +367,7 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         // raw partial sums of every chunk range into the scratch slices; the second kernel below
         // adds them and applies the epilogue
         if (POOL || pl.nss > gc.nchunks ||
-            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes())
             return SCONV_EUNSUPPORTED;
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;

@@ -78,16 +78,18 @@ const char* pinned_geom(const char* env_name);
 void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss = nullptr);
 
 // Channel split across workgroups: every workgroup stores the raw partial sums of its channel
-// range into slice ss of a scratch buffer laid out [nss][N][K][OH][OW]; launch_split_reduce adds
-// the slices in order and applies ReLU and, when pooled, the max over the pooling window.
-// split_scratch returns the stream's buffer of kSplitScratchBytes (allocated on first use, kept
-// until the process ends), or null when it cannot be had (the stream is recording a graph and has
-// no buffer yet, or the allocation failed): then the caller plans without a split.
-constexpr size_t kSplitScratchBytes = size_t(64) << 20;
-float* split_scratch(hipStream_t stream);
-// Whether split_scratch can succeed (the buffer exists, or the stream is not recording a graph):
-// asked while planning, so that the buffer is only allocated for a launch that is really split.
+// range into slice ss of a workspace laid out [nss][N][K][OH][OW]; launch_split_reduce adds the
+// slices in order and applies ReLU and, when pooled, the max over the pooling window.  The
+// workspace is lent by the caller per device and stream (split_workspace_set, behind
+// sconv_set_workspace).  The dispatcher selects the stream's workspace before every launch
+// (split_scratch_select, under its lock); the launchers then ask whether there is one, for its
+// address and for its size.  Without one they plan without a split.
+constexpr size_t kSplitWorkspaceCap = size_t(64) << 20;   // more than this is never asked for
+int split_workspace_set(void* ws, size_t bytes, hipStream_t stream);
+void split_scratch_select(hipStream_t stream);
 bool split_scratch_possible(hipStream_t stream);
+float* split_scratch(hipStream_t stream);
+size_t split_scratch_bytes();
 int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y,
                         hipStream_t stream);
 

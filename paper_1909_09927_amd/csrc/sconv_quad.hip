@@ -428,7 +428,7 @@ Plan plan_geom(const Problem& p)
     // sconv_tune or the environment: the static rules send small launches to the vector kernel.
     const int nss = pin_nss > 1 ? pin_nss : 1;
     if (nss > 1 && (G::POOL || nss > p.Cg / G::CCH || (long long)p.N * p.G * nss > 65535 ||
-                    (size_t)nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes))
+                    (size_t)nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes()))
         return best;
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
@@ -489,7 +489,7 @@ int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w
         // raw partial sums of every channel range into the scratch slices; the second kernel below
         // adds them and applies ReLU
         if (G::POOL || pl.nss > p.Cg / G::CCH ||
-            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes())
             return SCONV_EUNSUPPORTED;
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;

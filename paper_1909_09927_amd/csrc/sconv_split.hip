@@ -6,12 +6,12 @@
 // units.  Splitting the channel range over NSS workgroups per tile multiplies the workgroups (and
 // the filter fetches in flight) by NSS.  The sums of Section 5.4 are associative, so each
 // workgroup stores the raw partial sums of its channel range - the plain convolution layout,
-// no ReLU, no pooling - into slice number ss of a scratch buffer, and the small kernel below adds
+// no ReLU, no pooling - into slice number ss of a workspace, and the small kernel below adds
 // the slices in a fixed order (slice 0 first: results do not depend on scheduling) and applies the
 // epilogue of Sections 5.5 / 6: ReLU, and the max over the pooling window when fused.
 //
-// The scratch buffer belongs to the library: one per device and stream, allocated on the first
-// split launch enqueued on that stream and kept until the process ends.
+// The workspace is the caller's: lent per device and stream with sconv_set_workspace and looked up
+// for every launch.  Without one no launch is split; the library allocates nothing.
 #include <map>
 #include <utility>
 
@@ -55,47 +55,39 @@ __global__ __launch_bounds__(256) void split_pool_kernel(Problem p, const float*
     y[i] = m;
 }
 
-struct Scratch {
+struct Lent {
     float* ptr;
+    size_t bytes;
 };
-std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;   // under the dispatcher's lock
+std::map<std::pair<int, hipStream_t>, Lent> g_lent;   // under the dispatcher's lock
+Lent g_cur = {nullptr, 0};                              // the workspace of the launch being planned
 
 }  // namespace
 
-bool split_scratch_possible(hipStream_t stream)
+int split_workspace_set(void* ws, size_t bytes, hipStream_t stream)
 {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return false;
-    if (g_scratch.count(std::make_pair(dev, stream))) return true;
-    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &st) != hipSuccess || st != hipStreamCaptureStatusNone) {
-        (void)hipGetLastError();
-        return false;
-    }
-    return true;
+    if (hipGetDevice(&dev) != hipSuccess) return SCONV_ELAUNCH;
+    const auto key = std::make_pair(dev, stream);
+    if (!ws)
+        g_lent.erase(key);
+    else
+        g_lent[key] = Lent{static_cast<float*>(ws), bytes};
+    return SCONV_OK;
 }
 
-float* split_scratch(hipStream_t stream)
+void split_scratch_select(hipStream_t stream)
 {
+    g_cur = Lent{nullptr, 0};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    const auto key = std::make_pair(dev, stream);
-    auto it = g_scratch.find(key);
-    if (it != g_scratch.end()) return it->second.ptr;
-    // an allocation is not allowed while the stream records a graph: the caller plans without a split
-    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &st) != hipSuccess || st != hipStreamCaptureStatusNone) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    void* ptr = nullptr;
-    if (hipMalloc(&ptr, kSplitScratchBytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    g_scratch[key] = Scratch{static_cast<float*>(ptr)};
-    return static_cast<float*>(ptr);
+    if (hipGetDevice(&dev) != hipSuccess) return;
+    auto it = g_lent.find(std::make_pair(dev, stream));
+    if (it != g_lent.end()) g_cur = it->second;
 }
+
+bool split_scratch_possible(hipStream_t) { return g_cur.ptr != nullptr; }
+float* split_scratch(hipStream_t) { return g_cur.ptr; }
+size_t split_scratch_bytes() { return g_cur.bytes; }
 
 int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y, hipStream_t stream)
 {

@@ -400,7 +400,7 @@ Plan plan_geom(const Problem& p, int split)
     const bool large = tile_wgs >= 512;   // several rounds of workgroups
     const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     auto split_fits = [&](int nss) {
-        return !G::POOL && nss <= nchunks && nss * part_bytes <= kSplitScratchBytes &&
+        return !G::POOL && nss <= nchunks && nss * part_bytes <= split_scratch_bytes() &&
                (long long)p.N * p.G * nss <= 65535;
     };
     // a pinned decomposition is priced as it is; the model ranks the unsplit decompositions and
@@ -497,7 +497,7 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         // raw partial sums of every channel range into the scratch slices; the second kernel below
         // adds them and applies the epilogue
         if (G::POOL || pl.nss > p.Cg / G::CCH ||
-            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > kSplitScratchBytes)
+            (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes())
             return SCONV_EUNSUPPORTED;
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;

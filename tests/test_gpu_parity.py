@@ -402,9 +402,9 @@ def test_gen_chunk_split_across_workgroups(device, monkeypatch, shp, split):
         check_pool_forward(layer, x, w, integer_exact=True)
 
 
-def test_split_launches_on_two_streams_do_not_share_scratch(device):
-    """Every stream has its own scratch buffer for the partial sums: split launches of different
-    layers enqueued on two streams at the same time give what each gives alone."""
+def test_split_launches_on_two_streams_with_their_own_workspaces(device):
+    """Workspaces are lent per stream: split launches of different layers enqueued on two streams at
+    the same time, each stream with its own workspace, give what each gives alone."""
     shp_a = (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None)
     shp_b = (1, 256, 14, 14, 256, 3, 3, 1, 1, 1, None)
     la, xa, wa = _mk(185, shp_a)
@@ -414,6 +414,15 @@ def test_split_launches_on_two_streams_do_not_share_scratch(device):
     ref_b = sconv.sconv_forward(xbd, wbd, 1, 1, 1, relu=True)
     torch.cuda.synchronize()
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    da = sconv.desc_for(xad, wad, 1, 1, 1, None, True)
+    db = sconv.desc_for(xbd, wbd, 1, 1, 1, None, True)
+    ws1 = torch.empty(sconv.sconv_workspace_size(da), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(sconv.sconv_workspace_size(db), dtype=torch.uint8, device="cuda")
+    assert ws1.numel() > 0 and ws2.numel() > 0
+    with torch.cuda.stream(s1):
+        sconv.sconv_set_workspace(ws1)
+    with torch.cuda.stream(s2):
+        sconv.sconv_set_workspace(ws2)
     outs_a = [torch.empty_like(ref_a) for _ in range(20)]
     outs_b = [torch.empty_like(ref_b) for _ in range(20)]
     for oa, ob in zip(outs_a, outs_b):
@@ -422,14 +431,18 @@ def test_split_launches_on_two_streams_do_not_share_scratch(device):
         with torch.cuda.stream(s2):
             sconv.sconv_forward(xbd, wbd, 1, 1, 1, relu=True, out=ob)
     torch.cuda.synchronize()
+    with torch.cuda.stream(s1):
+        sconv.sconv_set_workspace(None)
+    with torch.cuda.stream(s2):
+        sconv.sconv_set_workspace(None)
     for oa, ob in zip(outs_a, outs_b):
         assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b)
     check_forward(la, xa, wa, relu=True)
 
 
-def test_split_plan_is_left_out_while_a_fresh_stream_records_a_graph(device):
-    """The scratch buffer of a split plan is allocated per stream on first use, which cannot happen
-    during graph capture: a capture on a stream that has none must still give the right result."""
+def test_a_workspace_that_is_too_small_or_absent_means_unsplit_plans(device):
+    """A split plan needs the workspace lent for its stream: with one that is too small, and on a
+    stream that has none (here one recording a graph), the launch runs unsplit and still matches."""
     shp = (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None)
     layer, x, w = _mk(182, shp)
     xd, wd = to_dev(x), to_dev(w)
@@ -437,6 +450,15 @@ def test_split_plan_is_left_out_while_a_fresh_stream_records_a_graph(device):
     ref, scale = oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
     eager = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)   # default stream
     torch.cuda.synchronize()
+    small = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    import conftest
+    try:
+        sconv.sconv_set_workspace(small)
+        tiny_ws = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
+        torch.cuda.synchronize()
+    finally:
+        sconv.sconv_set_workspace(conftest._WORKSPACE)
+    assert (np.abs(tiny_ws.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
     out = torch.empty_like(eager)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
@@ -620,11 +642,16 @@ def test_tuned_plan_is_replayed_from_a_graph_and_yields_to_a_pinned_variant(devi
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         out = torch.empty_like(y)
+        side_ws = torch.empty(sconv.sconv_workspace_size(d), dtype=torch.uint8, device="cuda")
         with torch.cuda.stream(side):
+            # the tuned plan may be a split one: the capture stream needs a workspace of its own
+            # (kept alive as long as the graph is replayed)
+            sconv.sconv_set_workspace(side_ws)
             sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, out=out)
             side.synchronize()
             with torch.cuda.graph(graph, stream=side):
                 sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, out=out)
+            sconv.sconv_set_workspace(None)
         torch.cuda.synchronize()
         for rep in range(3):
             _, xn, _ = _mk(176 + rep, shp)
@@ -720,11 +747,15 @@ def test_calls_can_be_captured_in_a_graph_and_replayed(device):
 
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
+    side_ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     with torch.cuda.stream(side):
+        # the same plans as on the default stream (bitwise equal results) need a workspace here too
+        sconv.sconv_set_workspace(side_ws)
         step()
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
             step()
+        sconv.sconv_set_workspace(None)
     torch.cuda.synchronize()
     for rep in range(4):
         for i, (layer, xd, wd, y, z) in enumerate(bufs):          # fresh inputs in the captured buffers

@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(sconv_[a-z_]+)\s*\(", text))
     assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
             "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool", "sconv_tune",
-            "sconv_tune_reset", "sconv_plan_name"} <= names
+            "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
@@ -177,6 +177,24 @@ def test_tuning_calls_validate_on_the_host():
     assert L.sconv_plan_name(ctypes.byref(d), 0, buf, 4) == 0 and buf.value == b"tap"
     assert L.sconv_plan_name(ctypes.byref(d), 0, None, 4) == sconv.SCONV_EINVAL
     assert L.sconv_plan_name(ctypes.byref(bad), 0, buf, 4) == sconv.SCONV_EINVAL
+
+
+def test_workspace_calls_validate_on_the_host():
+    L = sconv.lib()
+    n = ctypes.c_size_t(7)
+    deep = sconv.make_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)
+    assert L.sconv_workspace_size(ctypes.byref(deep), 0, ctypes.byref(n)) == 0
+    assert n.value == 16 * 512 * 49 * 4          # sixteen slices of the convolution tensor
+    big = sconv.make_desc(32, 256, 56, 56, 256, 3, 3, 1, 1)
+    assert L.sconv_workspace_size(ctypes.byref(big), 0, ctypes.byref(n)) == 0 and n.value == 64 << 20
+    odd = sconv.make_desc(1, 16, 40, 40, 8, 17, 17, 1, 2)     # only the window-row kernel covers it
+    assert L.sconv_workspace_size(ctypes.byref(odd), 0, ctypes.byref(n)) == 0 and n.value == 0
+    assert L.sconv_workspace_size(ctypes.byref(deep), 0, None) == sconv.SCONV_EINVAL
+    assert L.sconv_workspace_size(ctypes.byref(sconv.Desc()), 0, ctypes.byref(n)) == sconv.SCONV_EINVAL
+    assert L.sconv_workspace_size(ctypes.byref(deep), 1, ctypes.byref(n)) == sconv.SCONV_EINVAL   # no pooling fields
+    assert L.sconv_set_workspace(ctypes.c_void_p(256), 0, None) == sconv.SCONV_EINVAL
+    assert L.sconv_set_workspace(None, 4096, None) == sconv.SCONV_EINVAL
+    assert L.sconv_set_workspace(ctypes.c_void_p(260), 4096, None) == sconv.SCONV_EINVAL          # not 16-byte aligned
 
 
 def test_binding_refuses_host_tensors():
