@@ -439,7 +439,7 @@ int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, fl
     const char* pin = pinned_geom("SCONV_GEN_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
-    // a split of the chunks across workgroups needs the stream's scratch buffer
+    // a split of the chunks across workgroups needs a workspace lent for the stream
     const bool can_split = split_scratch_possible(stream);
     // A pooled layer: first the plain kernel with the split (the second kernel pools), which the
     // model offers for small launches only; the pooled kernel when that does not apply.

@@ -579,7 +579,7 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
     const char* pin = pinned_geom("SCONV_TAP_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
-    // a channel split across workgroups needs the stream's scratch buffer
+    // a channel split across workgroups needs a workspace lent for the stream
     const bool can_split = split_scratch_possible(stream);
     // A pooled layer: first the plain tiles with the split (the second kernel pools), which the
     // model offers for small launches only; the pooled tiles when none applies.
