@@ -154,8 +154,8 @@ int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
  * channels a multiple of 16; preferred for the deep layers - maps up to 14 wide with 256 or more
  * channels per group, maps up to 28 wide with 512 or more - and for launches too small to fill the
  * matrix kernels' tiles),
- * "gen" (every other shape with a kernel of at most 15x15 and, when pooling, a 2x2 / stride 2
- * window), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
+ * "gen" (every other shape with a kernel of at most 15x15; any pooling window of up to 64
+ * results), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes
  * before the static rules.
  * Returns NULL for an invalid descriptor.  Host only.

@@ -1,5 +1,6 @@
 // General matrix-core kernel: any kernel size up to 15x15, any stride, padding and grouping, any
-// channel count; optional 2x2 / stride 2 max-pooling epilogue.
+// channel count; optional max-pooling epilogue (2x2 / stride 2 in registers, any other window of up
+// to 64 results through a copy of the tile in LDS).
 //
 // Same arithmetic as the wide 3x3 kernel - 64 window rows per wavefront in format order (ECR
 // (n, oh, ow), or PECR (n, ph, pw, py, px) for the fused call, Section 6.2), one
@@ -42,7 +43,11 @@ struct GenCfg {
                                // raw partial sums, stored into slice blockIdx.z % nss of y
 };
 
-template <int KPL, bool POOL, int NWV, bool DENSE>
+// POOL: 0 plain; 1 fused 2x2 / stride 2 pooling (four window rows of a pooling window = the four
+// accumulator elements a lane holds for one filter); 2 any pooling window of up to 64 results:
+// a tile is 64 / (p_h*p_w) whole pooling windows in PECR order, the window rows of a pooling
+// window are consecutive lanes, and the maximum is taken over a copy of the tile in LDS.
+template <int KPL, int POOL, int NWV, bool DENSE>
 __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, GenCfg gc,
                                                        const float* __restrict__ x,
                                                        const float* __restrict__ w, float* __restrict__ y)
@@ -72,9 +77,23 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
 
     // this lane's window row
     const int P = tile * 64 + lane;
-    const bool pos_ok = tile_ok && P < cfg.npos;
+    bool pos_ok = tile_ok && P < cfg.npos;
     int n = 0, oh = 0, ow = 0;
-    if (pos_ok) {
+    const int WR = POOL == 2 ? p.ph * p.pw : 4;    // window rows per pooling window
+    const int wpt = 64 / WR;                       // pooling windows per tile
+    if (POOL == 2) {
+        const int wl = lane / WR, e = lane - wl * WR;
+        const int widx = tile * wpt + wl;          // pooling window number in the batch
+        pos_ok = tile_ok && wl < wpt && widx < cfg.npos;
+        if (pos_ok) {
+            n = widx / plane;
+            const int rem = widx - n * plane;
+            const int phi = rem / p.PW, pwi = rem - phi * p.PW;
+            const int py = e / p.pw, px = e - py * p.pw;
+            oh = phi * p.ps + py;
+            ow = pwi * p.ps + px;
+        }
+    } else if (pos_ok) {
         if (!POOL) {
             n = P / plane;
             const int rem = P - n * plane;
@@ -226,9 +245,44 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
         }
     }
 
-    // split: slice ss of the partial sums (plain layout; the host switched ReLU off)
-    finish_tile<KPL, POOL>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane,
-                           y + (size_t)ss * p.N * p.K * plane);
+    if constexpr (POOL == 2) {
+        // the tile, summed over the slices, goes to LDS as [filter register][window row][filter];
+        // then every wavefront of the tile takes pooling windows, a lane per filter
+        reduce_slices<KPL>(cfg, lds, acc, lane, ts, cs);
+        __syncthreads();                 // the reduction's buffers are read, the filter buffers free
+        float* tl = lds + (size_t)ts * (KPL * 64 * 64);
+        const int bps = 4 / cfg.NCS;
+        const int kf = lane & 15, rg = lane >> 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (cs != q / bps) continue;
+#pragma unroll
+            for (int i = 0; i < KPL; ++i)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        tl[(i * 64 + 16 * q + 4 * rg + e) * 64 + 16 * b + kf] = acc[i][q][4 * b + e];
+        }
+        __syncthreads();
+        if (!tile_ok) return;
+        for (int wl = cs; wl < wpt; wl += cfg.NCS) {
+            const int widx = tile * wpt + wl;      // uniform
+            if (widx >= cfg.npos) break;
+            const int nn = widx / plane, rem = widx - nn * plane;
+#pragma unroll
+            for (int i = 0; i < KPL; ++i) {
+                const int k = 64 * i + lane;
+                float m = 0.0f;                    // ReLU: the maximum is taken over max(value, 0)
+                for (int e = 0; e < WR; ++e) m = fmaxf(m, tl[(i * 64 + wl * WR + e) * 64 + lane]);
+                if (k < kvalid) y[((size_t)nn * p.K + (size_t)g * p.Kg + kb0 + k) * plane + rem] = m;
+            }
+        }
+    } else {
+        // split: slice ss of the partial sums (plain layout; the host switched ReLU off)
+        finish_tile<KPL, POOL == 1>(p, cfg, lds, acc, lane, ts, cs, tile, tile_ok, g, kb0, kvalid, plane,
+                                    y + (size_t)ss * p.N * p.K * plane);
+    }
 }
 
 struct Plan {
@@ -241,7 +295,7 @@ struct Plan {
     long long wgs1 = 0;   // workgroups of the launch before that split
 };
 
-template <int KPL, bool POOL, int NWV>
+template <int KPL, int POOL, int NWV>
 int occupancy(size_t lds_bytes)
 {
     int nb = 0;
@@ -258,14 +312,21 @@ int occupancy(size_t lds_bytes)
 // required - the plain kernel serving a pooled layer): the smallest power of two that gives every
 // compute unit a workgroup and leaves each workgroup two chunks; a second, small kernel adds the
 // partial sums.
-template <int KPL, bool POOL>
+template <int KPL, int POOL>
 Plan plan_geom(const Problem& p, int split)
 {
     constexpr int KB = 64 * KPL;
     Plan best;
     WideCfg cfg;
-    cfg.npos = POOL ? p.N * p.PH * p.PW * 4 : p.N * p.OH * p.OW;
-    cfg.ntiles = (cfg.npos + 63) / 64;
+    if (POOL == 2) {
+        // whole pooling windows per tile; npos counts pooling windows
+        const int wpt = 64 / (p.ph * p.pw);
+        cfg.npos = p.N * p.PH * p.PW;
+        cfg.ntiles = (cfg.npos + wpt - 1) / wpt;
+    } else {
+        cfg.npos = POOL ? p.N * p.PH * p.PW * 4 : p.N * p.OH * p.OW;
+        cfg.ntiles = (cfg.npos + 63) / 64;
+    }
     cfg.vec4 = 0;
     const int kblocks = (p.Kg + KB - 1) / KB;
     const int nchunks = (p.L + CW - 1) / CW;
@@ -294,6 +355,9 @@ Plan plan_geom(const Problem& p, int split)
             size_t lds_bytes = 2 * (size_t)CW * (KB + 1) * sizeof(float) + 3 * CW * sizeof(uint2);
             const size_t red_bytes = (size_t)nt * 4 * (ncs - 1) * KPL * 16 * 64 * sizeof(float);
             if (red_bytes > lds_bytes) lds_bytes = red_bytes;
+            // general pooling windows: a copy of every tile of the workgroup in LDS
+            if (POOL == 2 && (size_t)nt * KPL * 64 * 64 * sizeof(float) > lds_bytes)
+                lds_bytes = (size_t)nt * KPL * 64 * 64 * sizeof(float);
             if (lds_bytes > 160 * 1024) continue;
             const int occ = nwv == 4 ? occupancy<KPL, POOL, (KPL == 2 ? 8 : 4)>(lds_bytes)
                                      : occupancy<KPL, POOL, 8>(lds_bytes);
@@ -332,7 +396,7 @@ Plan plan_geom(const Problem& p, int split)
     return best;
 }
 
-template <int KPL, bool POOL, int NWV, bool DENSE>
+template <int KPL, int POOL, int NWV, bool DENSE>
 int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid, size_t lds_bytes,
                const float* x, const float* w, float* y, hipStream_t stream)
 {
@@ -348,7 +412,7 @@ int launch_nwv(const Problem& p, const WideCfg& cfg, const GenCfg& gc, dim3 grid
     return launch_status();
 }
 
-template <int KPL, bool POOL, bool DENSE>
+template <int KPL, int POOL, bool DENSE>
 int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
@@ -372,7 +436,7 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;
         q.relu = 0;
-    } else if (pooled != POOL) {
+    } else if (pooled != (POOL != 0)) {
         return SCONV_EUNSUPPORTED;
     }
     WideCfg cfg = pl.cfg;
@@ -390,10 +454,10 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
 bool shape_ok(const Problem& p, bool pooled)
 {
     if (p.R > 15 || p.S > 15) return false;            // one mask bit per kernel row and column
-    if (pooled && (p.ph != 2 || p.pw != 2 || p.ps != 2)) return false;
+    if (pooled && p.ph * p.pw > 64) return false;      // whole pooling windows in a 64-row tile
     // 32-bit byte offsets into the input with the top bit free, 32-bit window row numbers
     if ((long long)p.N * p.C * p.H * p.W >= (1LL << 29)) return false;
-    const long long npos = pooled ? (long long)p.N * p.PH * p.PW * 4 : (long long)p.N * p.OH * p.OW;
+    const long long npos = pooled ? (long long)p.N * p.PH * p.PW * 64 : (long long)p.N * p.OH * p.OW;
     if (npos >= (1LL << 31) - 64) return false;
     // the multiply-high quotients col / (R*S) and t / S are exact while dividend * divisor < 2^32
     const long long T = (long long)p.R * p.S;
@@ -408,6 +472,7 @@ struct Candidate {
     bool pooled;
     int kpl;
     bool by_model;
+    bool any_window = false;   // pooled: serves every pooling window (the others 2x2 / stride 2 only)
 };
 
 const Candidate kCandidates[] = {
@@ -420,13 +485,16 @@ const Candidate kCandidates[] = {
     {"gk2d", plan_geom<2, false>, launch_plan<2, false, true>, false, 2, false},
     {"gpk1d", plan_geom<1, true>, launch_plan<1, true, true>, true, 1, false},
     {"gpk2d", plan_geom<2, true>, launch_plan<2, true, true>, true, 2, false},
+    // any pooling window of up to 64 results
+    {"ggk1", plan_geom<1, 2>, launch_plan<1, 2, false>, true, 1, true, true},
+    {"ggk2", plan_geom<2, 2>, launch_plan<2, 2, false>, true, 2, true, true},
 };
 
 }  // namespace
 
 const char* const* gen_geoms()
 {
-    static const char* const names[] = {"gk1", "gk2", "gpk1", "gpk2", "gk1d", "gk2d", "gpk1d", "gpk2d", nullptr};
+    static const char* const names[] = {"gk1", "gk2", "gpk1", "gpk2", "gk1d", "gk2d", "gpk1d", "gpk2d", "ggk1", "ggk2", nullptr};
     return names;
 }
 
@@ -446,6 +514,7 @@ int launch_gen(const Problem& p, bool pooled, const float* x, const float* w, fl
     for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {
         for (const Candidate& c : kCandidates) {
             if (c.pooled != (pooled && pass == 1)) continue;
+            if (c.pooled && c.any_window == (p.ph == 2 && p.pw == 2 && p.ps == 2)) continue;
             if (p.Kg <= 64 * (c.kpl - 1)) continue;
             if (pin ? strcmp(pin, c.name) != 0 : !c.by_model) continue;
             const Plan pl = c.plan(p, c.pooled != pooled ? 2 : (can_split && !c.pooled ? 1 : 0));

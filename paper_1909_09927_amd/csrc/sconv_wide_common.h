@@ -53,15 +53,13 @@ __device__ __forceinline__ void tap_blocks(const float xv, const unsigned long l
 // Reduction of the channel slices and epilogue of one 64-row tile, shared by the kernels of this
 // file.  acc[i][q][v]: filter register i, 16-row block q, element v (filter 16*(v/4) + lane%16, row
 // 4*(lane/16) + v%4 of the block).
-template <int KPL, bool POOL>
-__device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg, float* lds,
-                                            v16f (&acc)[KPL][4], int lane, int ts, int cs, int tile,
-                                            bool tile_ok, int g, int kb0, int kvalid, int plane,
-                                            float* __restrict__ y)
+// Reduction of the channel slices (NCS is 1, 2 or 4).  The four 16-row blocks of the tile are dealt
+// out to the slices: a slice writes the partial sums of the blocks it does not own to LDS, then
+// adds what the others wrote for its own blocks (block q belongs to slice q / (4 / NCS)).
+template <int KPL>
+__device__ __forceinline__ void reduce_slices(const WideCfg& cfg, float* lds, v16f (&acc)[KPL][4], int lane,
+                                              int ts, int cs)
 {
-    // Reduce the channel slices (NCS is 1, 2 or 4).  The four 16-row blocks of the tile are dealt
-    // out to the slices: a slice writes the partial sums of the blocks it does not own to LDS,
-    // then adds what the others wrote for its own blocks and stores those.
     const int bps = 4 / cfg.NCS;                   // blocks per slice
     if (cfg.NCS > 1) {
         float* red = lds;  // [NT][4 blocks][NCS - 1 writers][KPL * 16][64]
@@ -90,6 +88,16 @@ __device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg
             }
         }
     }
+}
+
+template <int KPL, bool POOL>
+__device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg, float* lds,
+                                            v16f (&acc)[KPL][4], int lane, int ts, int cs, int tile,
+                                            bool tile_ok, int g, int kb0, int kvalid, int plane,
+                                            float* __restrict__ y)
+{
+    reduce_slices<KPL>(cfg, lds, acc, lane, ts, cs);
+    const int bps = 4 / cfg.NCS;                   // blocks per slice
     if (!tile_ok) return;
 
     // epilogue: element (q, 4*b + e) of the lane = filter 16*b + lane%16, window row

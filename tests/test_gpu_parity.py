@@ -376,6 +376,34 @@ def test_quad_channel_split_across_workgroups(device, monkeypatch, shp, geom, sp
     check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
+GEN_ANY_POOL = [
+    (2, 20, 13, 13, 70, 3, 3, 1, 1, 1, (3, 3, 2)),      # overlapping 3x3 / stride 2 windows (7 per tile)
+    (1, 48, 27, 27, 130, 5, 5, 1, 2, 2, (3, 3, 2)),     # grouped, two filters per lane possible
+    (3, 16, 12, 10, 40, 3, 3, 1, 1, 1, (2, 3, 1)),      # 6-result windows, stride 1
+    (1, 64, 16, 16, 64, 1, 1, 1, 0, 1, (4, 4, 4)),      # 1x1 convolution, 16-result windows
+    (1, 8, 20, 20, 24, 3, 3, 2, 1, 1, (7, 7, 1)),       # 49-result windows: one per tile
+    (2, 32, 9, 9, 64, 3, 3, 1, 1, 1, (2, 2, 1)),        # 2x2 windows of stride 1
+]
+
+
+@pytest.mark.parametrize("split", [None, "4,1", "8,2", "8,4"])
+@pytest.mark.parametrize("shp", GEN_ANY_POOL)
+def test_gen_fused_pooling_with_any_window(device, monkeypatch, shp, split):
+    """Pooling windows other than 2x2 / stride 2 fused into the general matrix-core kernel: whole
+    pooling windows per 64-row tile in PECR order, the maximum taken over a copy of the tile in LDS."""
+    monkeypatch.setenv("SCONV_VARIANT", "gen")
+    if split:
+        monkeypatch.setenv("SCONV_GEN_SPLIT", split)
+    layer, x, w = _mk(194, shp)
+    d = sconv.desc_for(to_dev(x), to_dev(w), layer.stride, layer.pad, layer.groups, layer.pool, True)
+    assert sconv.sconv_variant_name(d, True) == "gen"
+    check_pool_forward(layer, x, w)
+    layer, x, w = _mk(195, shp, integer=True)
+    check_pool_forward(layer, x, w, integer_exact=True)
+    layer, x, w = _mk(196, shp, z=1.0)
+    check_pool_forward(layer, x, w)
+
+
 GEN_SPLIT = [
     (1, 20, 11, 11, 50, 5, 5, 1, 0, 1, (2, 2, 2)),      # 500 columns: 8 chunks, the last one ragged
     (1, 480, 14, 14, 192, 1, 1, 1, 0, 1, (2, 2, 2)),    # 1x1 with a channel count off the 64 grid

@@ -142,7 +142,8 @@ def test_strerror_and_variant_name():
     assert sconv.sconv_variant_name(sconv.make_desc(1, 250, 56, 56, 64, 1, 1)) == "gen"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2)) == "gen"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 17, 17, 1, 2)) == "rows"
-    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2, 1, (3, 3, 2)), True) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2, 1, (3, 3, 2)), True) == "gen"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 16, 56, 56, 64, 5, 5, 1, 2, 1, (9, 9, 2)), True) == "rows"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 2, 1)) == "tap3x3"
@@ -156,7 +157,7 @@ def test_strerror_and_variant_name():
     assert sconv.sconv_variant_name(sconv.make_desc(32, 512, 14, 14, 512, 3, 3, 1, 1, pool=(2, 2, 2)), True) == "tap3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(32, 256, 28, 28, 256, 3, 3, 1, 1, pool=(2, 2, 2)), True) == "quad3x3"
     assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 5, 5, 1, 2)) == "gen"
-    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1, pool=(3, 3, 2)), True) == "rows"
+    assert sconv.sconv_variant_name(sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1, pool=(3, 3, 2)), True) == "gen"
     assert sconv.sconv_variant_name(sconv.Desc()) is None
 
 
