@@ -161,6 +161,11 @@ CONFIGS: List[Dict] = [
             Layer("googlenet-5x5-48to128x7", C=48, H=7, W=7, K=128, R=5, S=5, pad=2, zero_ratio=0.95),
             Layer("vgg-conv15-512x14", C=512, H=14, W=14, K=512, R=3, S=3, pad=1, zero_ratio=0.83),
             Layer("resnet-conv42-256x14", C=256, H=14, W=14, K=256, R=3, S=3, pad=1, zero_ratio=0.86),
+            # convolution + pooling pairs with the two other pooling windows of those networks
+            Layer("lenet-conv1-5x5-1to20x28-pool2", C=1, H=28, W=28, K=20, R=5, S=5, pool=(2, 2, 2),
+                  zero_ratio=0.8),
+            Layer("alexnet-conv5-384to256x13-g2-pool3", C=384, H=13, W=13, K=256, R=3, S=3, pad=1, groups=2,
+                  pool=(3, 3, 2), zero_ratio=0.9),
         ],
     },
 ]
