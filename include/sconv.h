@@ -109,6 +109,8 @@ int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_d
  * Sparse convolution fused with ReLU and max pooling (Section 6, Algorithm 4): the convolution
  * results of one pooling window are reduced on chip and only the pooled tensor is stored:
  *   y[n][k][ph][pw] = max over py < p_h, px < p_w of max(0, conv[n][k][ph*p_s+py][pw*p_s+px]).
+ * (A small launch that is split across workgroups - only with a workspace lent, see sconv_forward -
+ * passes its partial sums through that workspace; the second kernel then pools.)
  *   y_dev device, out: [N][K][PH][PW]
  * SCONV_EUNSUPPORTED if p_h*p_w > 64 or a tensor has 2^31 or more elements.
  */
