@@ -92,8 +92,8 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
  * With a workspace lent for the stream (sconv_set_workspace), a launch of fewer than 128
- * workgroups ("tap3x3" and "gen": deep layers at batch 1) is split along the channels over up to 16
- * workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
+ * workgroups ("tap3x3" and "gen": deep layers at batch 1), or of 100-400 tiles of "quad3x3" on a
+ * map 28 or more wide, is split along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
  * and a second kernel on the same stream adds them in a fixed order and applies ReLU (and the
  * pooling of sconv_pool_forward).  Results stay deterministic; the association of the fp32 sums
  * differs from the unsplit kernel's.
@@ -155,7 +155,8 @@ int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
  * more filters and fewer than 256 channels per group), "tap3x3" (3x3 / pad 1, stride 1 or 2,
  * channels a multiple of 16; preferred for the deep layers - maps up to 14 wide with 256 or more
  * channels per group, maps up to 28 wide with 512 or more - and for launches too small to fill the
- * matrix kernels' tiles),
+ * matrix kernels' tiles; when a workspace is lent on a stream of the current device, launches of
+ * 100-400 "quad3x3" tiles on maps 28 or more wide are "quad3x3", split, instead),
  * "gen" (every other shape with a kernel of at most 15x15; any pooling window of up to 64
  * results), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes

@@ -132,8 +132,41 @@ static const Tuned* tuned_for(const Problem& p, bool pooled)
     return it == g_tuned.end() ? nullptr : &it->second;
 }
 
-static Variant choose(const Problem& p, bool pooled)
+// Small launches of the matrix kernel that a workspace lets split: on maps 28 or more wide with 128 or
+// more channels per group, a launch of 200 to 400 two-row tiles (100 to 400 with 512 or more
+// channels) runs as one-filter-per-lane tiles, 8 wavefronts x 4 channel slices, with the channels of a
+// tile split over enough workgroups to make about 450 of them.  Against the vector kernel's plan
+// that measures 1.2-1.8x faster at 50 % zeros and 0.95-1.4x at 80 % (256 channels @56x56 at batch 1
+// 51 against 75 us at 60 %, 512 @28x28 48 against 69 at 75 %, 128->32 @28x28 at batch 16 30 against
+// 36 at 70 %); smaller launches, and maps whose width leaves the second 28-column tile mostly empty,
+// stay with the vector kernel.
+static bool small_quad_split(const Problem& p, bool pooled, PlanPin* pin)
 {
+    if (pooled || p.W < 28 || p.Cg < 128 || !quad_supported(p, pooled)) return false;
+    const int wtiles = (p.OW + 27) / 28;
+    if (wtiles * 28 * 3 > p.OW * 4) return false;  // more than a quarter of the tile columns empty
+    const long long tiles = (long long)((p.OH + 1) / 2) * wtiles * ((p.Kg + 63) / 64) * p.N * p.G;
+    if (tiles >= 400 || tiles < (p.Cg >= 512 ? 100 : 200)) return false;
+    const long long wgs1 = (tiles + 1) / 2;        // two tiles per workgroup
+    int nss = 2;
+    while (wgs1 * nss < 448 && nss < 16) nss *= 2;
+    if (wgs1 * nss < 448 || nss > p.Cg / 16) return false;
+    if (pin) {
+        memset(pin, 0, sizeof(*pin));
+        snprintf(pin->geom, sizeof(pin->geom), "q32k1");
+        pin->nwv = 8;
+        pin->ncs = 4;
+        pin->nss = nss;
+    }
+    return true;
+}
+
+// The static rules.  have_ws: a workspace is lent (the split plans of the matrix kernel need one;
+// the vector and general kernels decide on their own).  When the choice comes with a fixed
+// decomposition, *static_pin receives it (geom[0] != 0).
+static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr)
+{
+    if (static_pin) memset(static_pin, 0, sizeof(*static_pin));
     const char* pin = getenv("SCONV_VARIANT");
     if (pin && !strcmp(pin, "rows")) return V_ROWS;
     if (pin && !strcmp(pin, "tap")) return tap_supported(p, pooled) ? V_TAP : V_ROWS;
@@ -162,6 +195,7 @@ static Variant choose(const Problem& p, bool pooled)
         // measures 1.0-1.15x faster than the 6-element granule from 70 % zeros up (and 1.1x slower
         // at 60 %).
         if (p.W <= 14 && p.Cg >= 256 && tap_supported(p, pooled)) return V_TAP;
+        if (have_ws && small_quad_split(p, pooled, static_pin)) return V_QUAD;
         // The same one stage earlier, 512 channels on maps up to 28 wide: 1.14x faster at 75 % zeros.
         if (p.W <= 28 && p.Cg >= 512 && !pooled && tap_supported(p, pooled)) return V_TAP;
         // Maps up to 14 wide with 128 or more filters per group and shorter channel loops: the
@@ -215,8 +249,14 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
         const int rc = launch_variant(t->v, t->pinned ? &t->pin : nullptr, p, pooled, x, w, y, s);
         if (rc != SCONV_EUNSUPPORTED) return rc;
     }
-    Variant v = choose(p, pooled);
+    PlanPin sp;
+    Variant v = choose(p, pooled, split_workspace_lent(s, false), &sp);
     int rc = SCONV_EUNSUPPORTED;
+    if (sp.geom[0]) {
+        rc = launch_variant(v, &sp, p, pooled, x, w, y, s);
+        if (rc != SCONV_EUNSUPPORTED) return rc;
+        v = choose(p, pooled);      // e.g. the workspace is too small for this layer
+    }
     if (v == V_PW) rc = launch_variant(V_PW, nullptr, p, pooled, x, w, y, s);
     if (v == V_GEN) {
         rc = launch_variant(V_GEN, nullptr, p, pooled, x, w, y, s);
@@ -316,8 +356,13 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         return true;
     };
     // the static rules' own choice comes first: it stays unless something measures clearly faster
-    const Variant v_static = choose(p, pooled);
-    const bool have_static = try_one(v_static, nullptr);
+    PlanPin sp;
+    Variant v_static = choose(p, pooled, split_workspace_lent(s, false), &sp);
+    bool have_static = try_one(v_static, sp.geom[0] ? &sp : nullptr);
+    if (!have_static && sp.geom[0]) {
+        v_static = choose(p, pooled);
+        have_static = try_one(v_static, nullptr);
+    }
     for (const Family& f : fams) {
         if (!f.ok || err != SCONV_OK) continue;
         for (const char* const* g = f.geoms; *g && err == SCONV_OK; ++g) {
@@ -363,7 +408,9 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         best.ms = t;
         best.pin = c.pin;
         best.pinned = c.pinned;
-        if (c.pinned && c.pin.nss > 1)
+        if (have_static && i == 0)
+            snprintf(best.name, sizeof(best.name), "%s/model/kept", variant_name(c.v));
+        else if (c.pinned && c.pin.nss > 1)
             snprintf(best.name, sizeof(best.name), "%s/%s/%dx%dx%d", variant_name(c.v), c.pin.geom, c.pin.nwv,
                      c.pin.ncs, c.pin.nss);
         else if (c.pinned)
@@ -475,7 +522,7 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled != 0)) return variant_name(t->v);
-    return variant_name(choose(p, pooled != 0));
+    return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true)));
 }
 
 extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
@@ -533,7 +580,7 @@ extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, 
     if (const Tuned* t = tuned_for(p, pooled != 0))
         snprintf(out, (size_t)out_size, "%s", t->name);
     else
-        snprintf(out, (size_t)out_size, "%s/model", variant_name(choose(p, pooled != 0)));
+        snprintf(out, (size_t)out_size, "%s/model", variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true))));
     return SCONV_OK;
 }
 

@@ -86,6 +86,8 @@ void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss = nullptr);
 // address and for its size.  Without one they plan without a split.
 constexpr size_t kSplitWorkspaceCap = size_t(64) << 20;   // more than this is never asked for
 int split_workspace_set(void* ws, size_t bytes, hipStream_t stream);
+// whether a workspace is lent for this stream of the current device (any_stream: for any of its streams)
+bool split_workspace_lent(hipStream_t stream, bool any_stream);
 void split_scratch_select(hipStream_t stream);
 bool split_scratch_possible(hipStream_t stream);
 float* split_scratch(hipStream_t stream);

@@ -425,7 +425,8 @@ Plan plan_geom(const Problem& p)
     int pin_nwv = 0, pin_ncs = 0, pin_nss = 0;   // tuning aid: SCONV_QUAD_SPLIT="nwv,ncs[,nss]"
     pinned_split("SCONV_QUAD_SPLIT", &pin_nwv, &pin_ncs, &pin_nss);
     // The channel split across workgroups (see sconv_split.hip) is only ever pinned here - by
-    // sconv_tune or the environment: the static rules send small launches to the vector kernel.
+    // sconv_tune, by the dispatcher's static rule for small launches on wide maps, or by the
+    // environment; the cost model below ranks unsplit plans.
     const int nss = pin_nss > 1 ? pin_nss : 1;
     if (nss > 1 && (G::POOL || nss > p.Cg / G::CCH || (long long)p.N * p.G * nss > 65535 ||
                     (size_t)nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes()))

@@ -76,6 +76,16 @@ int split_workspace_set(void* ws, size_t bytes, hipStream_t stream)
     return SCONV_OK;
 }
 
+bool split_workspace_lent(hipStream_t stream, bool any_stream)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (!any_stream) return g_lent.count(std::make_pair(dev, stream)) != 0;
+    for (const auto& kv : g_lent)
+        if (kv.first.first == dev) return true;
+    return false;
+}
+
 void split_scratch_select(hipStream_t stream)
 {
     g_cur = Lent{nullptr, 0};

@@ -698,6 +698,66 @@ def test_tuned_plan_is_replayed_from_a_graph_and_yields_to_a_pinned_variant(devi
         sconv.sconv_tune_reset()
 
 
+def test_small_launches_on_wide_maps_take_the_split_matrix_plan_when_a_workspace_is_lent(device, monkeypatch):
+    """A 3x3 launch of 200-400 matrix-kernel tiles on a 28-wide map goes to quad3x3 with its channels
+    split across workgroups when the stream has a workspace, and to the vector kernel when it has
+    none; both meet the bars."""
+    import conftest
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    sconv.sconv_tune_reset()
+    shp = (4, 128, 28, 28, 256, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(188, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    d = sconv.desc_for(xd, wd, 1, 1, 1, None, True)
+    assert sconv.sconv_variant_name(d) == "quad3x3"
+    check_forward(layer, x, w, relu=True)
+    li, xi, wi = _mk(189, shp, integer=True)
+    check_forward(li, xi, wi, relu=False, integer_exact=True)
+    try:
+        sconv.sconv_set_workspace(None)
+        assert sconv.sconv_variant_name(d) == "tap3x3"
+        check_forward(layer, x, w, relu=True)
+    finally:
+        sconv.sconv_set_workspace(conftest._WORKSPACE)
+
+
+def test_a_tuned_split_plan_falls_back_when_its_workspace_is_taken_away(device, monkeypatch):
+    """A plan tuned with a workspace may split its launch across workgroups; once the workspace
+    is withdrawn the same descriptor must still run (unsplit) and meet the bar, and with the
+    workspace back the tuned plan runs again."""
+    import conftest
+    import oracle
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    sconv.sconv_tune_reset()
+    shp = (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(187, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    ref, scale = oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
+    try:
+        # pin a split decomposition the way the tuner would remember it
+        monkeypatch.setenv("SCONV_TAP_SPLIT", "16,16,8")
+        monkeypatch.setenv("SCONV_VARIANT", "tap")
+        with_ws = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+        torch.cuda.synchronize()
+        sconv.sconv_set_workspace(None)
+        without = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+        torch.cuda.synchronize()
+        monkeypatch.delenv("SCONV_TAP_SPLIT")
+        monkeypatch.delenv("SCONV_VARIANT")
+        sconv.sconv_set_workspace(conftest._WORKSPACE)
+        ms, plan = sconv.sconv_tune(xd, wd, 1, 1, 1, None, relu=True)
+        tuned = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+        torch.cuda.synchronize()
+        sconv.sconv_set_workspace(None)
+        tuned_without = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+        torch.cuda.synchronize()
+    finally:
+        sconv.sconv_set_workspace(conftest._WORKSPACE)
+        sconv.sconv_tune_reset()
+    for got in (with_ws, without, tuned, tuned_without):
+        assert (np.abs(got.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
 def test_chained_layers_each_match_the_oracle_on_the_input_they_got(device):
     """Layers chained on the device (each consumes the previous one's output, zeros as ReLU and
     pooling left them): every layer is checked against the oracle applied to the very input the
