@@ -158,7 +158,8 @@ int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
  * matrix kernels' tiles; when a workspace is lent on a stream of the current device, launches of
  * 100-400 "quad3x3" tiles on maps 28 or more wide are "quad3x3", split, instead),
  * "gen" (every other shape with a kernel of at most 15x15; any pooling window of up to 64
- * results), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
+ * results; also 1x1 layers of 512 or more channels per group and few tiles, which it splits
+ * across workgroups), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes
  * before the static rules.
  * Returns NULL for an invalid descriptor.  Host only.

@@ -174,11 +174,14 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
     if (pin && !strcmp(pin, "quad")) return quad_supported(p, pooled) ? V_QUAD : V_ROWS;
     if (pin && !strcmp(pin, "gen")) return gen_supported(p, pooled) ? V_GEN : V_ROWS;
     if (pw_supported(p, pooled)) {
-        // A 1x1 layer of a few dozen 32-position tiles walking 512 or more channels is one latency
-        // chain per workgroup: the general kernel, which splits such a launch's columns over
-        // workgroups, measures 1.2-1.6x faster there.
+        // A 1x1 layer of few 32-position tiles walking 512 or more channels is one latency chain per
+        // workgroup, the longer the more channels: the general kernel, which splits such a launch's
+        // columns over workgroups, measures 1.1-1.7x faster up to about 0.3 tiles per channel (512
+        // channels: 1.25x at 100 tiles, level at 200; 1024: 1.7x at 100, 1.4x at 200; 2048: 1.7x at 200).
         const long long pw_tiles = ((long long)p.N * p.H * p.W + 31) / 32 * ((p.Kg + 63) / 64) * p.G;
-        if (pw_tiles < 64 && p.Cg >= 512 && gen_supported(p, pooled)) return V_GEN;
+        // (the split needs a workspace; without one only launches of fewer than 64 tiles go there)
+        if (p.Cg >= 512 && (pw_tiles < 64 || (have_ws && pw_tiles * 16 < 5LL * p.Cg)) && gen_supported(p, pooled))
+            return V_GEN;
         return V_PW;
     }
     // The 16-row granule needs many tile-wavefronts (64 window rows x 64 filters each) to fill the
