@@ -475,10 +475,13 @@ Plan plan_geom(const Problem& p)
     return best;
 }
 
+// pooled: the caller asked for the fused call; a pooled geometry does the pooling itself, a plain one
+// (split plans only) leaves it to the kernel that adds the parts.
 template <class G>
-int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w, float* y,
+int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, const float* w, float* y,
                 hipStream_t stream)
 {
+    if (pooled && !G::POOL && pl.nss == 1) return SCONV_EUNSUPPORTED;
     const size_t lds_bytes = pl.lds_bytes;
     const long long gx = (pl.cfg.ntiles + pl.cfg.NT - 1) / pl.cfg.NT;
     const long long gz = (long long)p.N * p.G * pl.nss;
@@ -502,7 +505,7 @@ int launch_plan(const Plan& pl, const Problem& p, const float* x, const float* w
     else
         rc = launch_nwv<G, 8>(q, pl.cfg, grid, lds_bytes, x, w, out, stream);
     if (rc != SCONV_OK || pl.nss == 1) return rc;
-    return launch_split_reduce(p, false, out, pl.nss, y, stream);
+    return launch_split_reduce(p, pooled, out, pl.nss, y, stream);
 }
 
 // Geometries.  Maps wider than 14: rows of 32 lanes, 28 output columns (7 quads), 2 output rows.
@@ -529,7 +532,7 @@ bool shape_ok(const Problem& p, bool pooled)
 struct Candidate {
     const char* name;
     Plan (*plan)(const Problem&);
-    int (*launch)(const Plan&, const Problem&, const float*, const float*, float*, hipStream_t);
+    int (*launch)(const Plan&, const Problem&, bool, const float*, const float*, float*, hipStream_t);
     bool pooled;
     int kpl;              // filters per lane: needs more than 64*(kpl-1) filters in the group
     bool wide;            // for maps wider than 14
@@ -563,10 +566,15 @@ int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, f
 {
     if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
     const char* pin = pinned_geom("SCONV_QUAD_GEOM");   // tuning aid: candidate name, or !name to exclude one
+    int pin_nwv = 0, pin_ncs = 0, pin_nss = 0;
+    pinned_split("SCONV_QUAD_SPLIT", &pin_nwv, &pin_ncs, &pin_nss);
+    // a fused call whose plan is pinned to a channel split across workgroups runs on the plain
+    // tiles: the kernel that adds the parts takes the maximum over the pooling window
+    const bool plain_for_pooled = pooled && pin_nss > 1;
     const Candidate* best = nullptr;
     Plan best_plan;
     for (const Candidate& c : kCandidates) {
-        if (c.pooled != pooled) continue;
+        if (c.pooled != (pooled && !plain_for_pooled)) continue;
         if (p.Kg <= 64 * (c.kpl - 1)) continue;
         if (pin ? (pin[0] == '!' ? strcmp(pin + 1, c.name) == 0 || c.wide != (p.W > 14) : strcmp(pin, c.name) != 0)
                 : (c.wide != (p.W > 14)))
@@ -580,7 +588,7 @@ int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, f
         }
     }
     if (!best) return SCONV_EUNSUPPORTED;
-    return best->launch(best_plan, p, x, w, y, stream);
+    return best->launch(best_plan, p, pooled, x, w, y, stream);
 }
 
 }  // namespace sconv

@@ -362,6 +362,8 @@ def test_tap_channel_split_across_workgroups(device, monkeypatch, shp, split):
 @pytest.mark.parametrize("shp", [
     (1, 64, 28, 30, 130, 3, 3, 1, 1, 1, None),          # wide map, ragged filter block
     (2, 128, 14, 14, 140, 3, 3, 1, 1, 2, None),         # map up to 14 wide, grouped
+    (2, 64, 14, 13, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # fused pooling: plain tiles, pooled by the adding kernel
+    (1, 48, 30, 58, 64, 3, 3, 1, 1, 1, (2, 2, 2)),      # the same on a wide map
 ])
 def test_quad_channel_split_across_workgroups(device, monkeypatch, shp, geom, split):
     """The matrix-core 3x3 kernel with a tile's channels split over workgroups (a pinned plan: a
@@ -372,8 +374,12 @@ def test_quad_channel_split_across_workgroups(device, monkeypatch, shp, geom, sp
     layer, x, w = _mk(187, shp)
     check_forward(layer, x, w, relu=True)
     check_forward(layer, x, w, relu=False)
+    if layer.pool:
+        check_pool_forward(layer, x, w)
     layer, x, w = _mk(188, shp, integer=True)
     check_forward(layer, x, w, relu=False, integer_exact=True)
+    if layer.pool:
+        check_pool_forward(layer, x, w, integer_exact=True)
 
 
 GEN_ANY_POOL = [
