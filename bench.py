@@ -165,7 +165,7 @@ def ramp_up(fn, seconds: float = 0.03) -> None:
 
 def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
     """Average launch duration in ms, events on the launch stream (torch's current stream): the
-    median of three back-to-back rounds of `iters` launches, so that one stall of the machine (seen
+    median of five back-to-back rounds of `iters` launches, so that a stall of the machine (seen
     now and then on 20-us layers) does not pass for the kernel's time."""
     import torch
     ramp_up(dl.run)
@@ -173,7 +173,7 @@ def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
         dl.run()
     torch.cuda.synchronize()
     rounds = []
-    for _ in range(3):
+    for _ in range(5):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
@@ -193,7 +193,7 @@ def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
         e1.synchronize()
         singles.append(e0.elapsed_time(e1))
     dl.single_launch_ms = sorted(singles)[2]
-    return sorted(rounds)[1]
+    return sorted(rounds)[2]
 
 
 def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:

@@ -173,7 +173,7 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  * every variant and every decomposition that covers the descriptor on the caller's operands - each
  * one untimed launch and three timed ones between two events on hip_stream, the static choice and
  * the four fastest then again for about a millisecond each - and remembers the fastest (the static
- * choice unless another measures 3 % faster) for this exact descriptor (and pooled flag) in a
+ * choice unless another measures 3 % and 1.5 us faster) for this exact descriptor (and pooled flag) in a
  * host-side table; later sconv_forward / sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
  * models' choice.  The table is per process, guarded by the library's lock, and holds no device
  * memory.

@@ -392,7 +392,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     if (err == SCONV_OK && cands.empty()) try_one(V_ROWS, nullptr);   // only the general kernel covers it
     // The static choice and the four fastest again, long enough for the timing to be trusted (about
     // a millisecond each).  The static choice is timed first and a candidate replaces it only when
-    // it measures 3 % faster: launches of 10-20 us differ by that much from one timing to the next.
+    // it measures 3 % faster: launches of 10-20 us differ by that much from one timing to the next
     Tuned best;
     best.ms = -1.0f;
     std::sort(cands.begin() + (have_static ? 1 : 0), cands.end(),
@@ -406,7 +406,8 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         const float t = time_candidate(c.v, c.pinned ? &c.pin : nullptr, p, pooled, x, w, y, s, e0, e1, reps, flush,
                                        &err);
         if (t < 0.0f || (bar >= 0.0f && t >= bar)) continue;
-        bar = (have_static && i == 0) ? 0.97f * t : t;
+        // (and by at least 1.5 us: single launches of 10-15 us time that far apart)
+        bar = (have_static && i == 0) ? std::min(0.97f * t, t - 0.0015f) : t;
         best.v = c.v;
         best.ms = t;
         best.pin = c.pin;

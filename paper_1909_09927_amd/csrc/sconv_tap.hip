@@ -371,8 +371,9 @@ struct Plan {
 // filter chunk in flight, so a launch of fewer workgroups than compute units waits on the memory
 // latency chunk after chunk; the split divides that chain, for the price of the second, small
 // kernel that adds the partial sums.  The model splits launches of fewer than 128 tile-workgroups
-// (measured 1.4-3.5x faster there; around 200 workgroups the split measures between 1.2x faster
-// and 1.5x slower); sconv_tune tries splits of launches up to 512.
+// (measured 1.4-3.5x faster there) and, two to four ways, launches of up to 512 that walk 16 or more
+// chunks with one filter per lane (around 200 workgroups of shorter chains the split measures
+// between 1.2x faster and 1.5x slower); sconv_tune tries splits of launches up to 512.
 template <class G>
 Plan plan_geom(const Problem& p, int split)
 {
@@ -398,6 +399,9 @@ Plan plan_geom(const Problem& p, int split)
     const long long tile_wgs = (long long)cfg.ntiles * ((p.Kg + 63) / 64) * p.N * p.G;
     const bool small = tile_wgs < 128;
     const bool large = tile_wgs >= 512;   // several rounds of workgroups
+    // a few workgroups per compute unit, each walking 16 or more chunks: still a chain of chunk
+    // latencies with little to overlap it
+    const bool mid = !small && tile_wgs <= 512 && nchunks >= 16;
     const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     auto split_fits = [&](int nss) {
         return !G::POOL && nss <= nchunks && nss * part_bytes <= split_scratch_bytes() &&
@@ -409,10 +413,16 @@ Plan plan_geom(const Problem& p, int split)
     if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
     if (pin_nss == 1 && split == 2) return best;
     if (!pin_nss && split == 2 && !small) return best;
+    // measured on mid-sized launches: one filter per lane (twice the workgroups) with the channels
+    // split beats two filters per lane, which the pricing below would prefer
+    if (mid && split == 1 && G::KPL > 1 && !pin_nss && !pin_nwv && !pinned_geom("SCONV_TAP_GEOM")) return best;
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
+            // a whole-map tile has as many channel slices as wavefronts; split across workgroups,
+            // eight longer slices measure 10 % faster than sixteen (512 @7x7, batch 16 and 32)
+            if (!pin_nwv && !pin_nss && mid && split == 1 && cfg.ntiles == 1 && nwv != 8) continue;
             // the slice reduction reuses the filter buffers; a large tile's partial sums need more
             size_t lds_bytes = buf_bytes;
             if (ncs > 1 && nt * red_per_tile > lds_bytes) lds_bytes = nt * red_per_tile;
@@ -478,6 +488,22 @@ Plan plan_geom(const Problem& p, int split)
         if (want == 1 && split == 2) return Plan();
         best.nss = best.cfg.NSS = want;
         if (want > 1) best.cost = best.cost / want + 9000.0;
+    }
+    if (!pin_nss && split == 1 && mid && best.cost >= 0.0) {
+        // mid-sized launches: up to 768 workgroups (a round and a half of two per compute unit) of
+        // four chunks or more, four ways at most (512 channels @14x14: batch 4 57 -> 46 us, batch 8
+        // 87 -> 64; @7x7: batch 16 56 -> 43, batch 32 80 -> 72)
+        int want = 1;
+        // and every wavefront keeps 16 channels or more (fewer do not pay for the slice reduction
+        // and the tile epilogue, which every workgroup runs: 512 @7x7 at batch 32, 16 slices, four
+        // ways 102 against 80 us unsplit)
+        while (want < 4 && best.wgs1 * want * 2 <= 768 && want * 2 * 4 <= nchunks &&
+               p.Cg / (best.cfg.NCS * want * 2) >= 16)
+            want *= 2;
+        if (want > 1 && split_fits(want)) {
+            best.nss = best.cfg.NSS = want;
+            best.cost = best.cost / want + 9000.0;
+        }
     }
     return best;
 }
