@@ -182,7 +182,8 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  *   flush_dev device, scratch, optional (NULL with flush_bytes 0): when given, its flush_bytes
  *            bytes are overwritten before every timed launch, so that no launch finds its operands
  *            in the caches (give it at least twice the last-level cache, 512 MiB); without it the
- *            launches run back to back and plans are ranked cache-warm.  This buffer is
+ *            launches run back to back and plans are ranked cache-warm.  With it, the finalists
+ *            are timed both ways and a plan replaces the static choice only if it wins both.  This buffer is
  *            the caller's and only used during this call.  Split plans are tried only when a
  *            workspace is lent for hip_stream (sconv_set_workspace) - lend it first.
  *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.

@@ -387,7 +387,11 @@ Plan plan_geom(const Problem& p, int split)
     }
     if (!pin_nss && split && small && best.cost >= 0.0) {
         int want = split == 2 ? 2 : 1;
-        while (want < 16 && best.wgs1 * want < 256 && want * 4 <= nchunks) want *= 2;
+        // down to one chunk per workgroup (measured on 1x1 832->256 @7x7: 8 ways 14.4 us, 4 ways
+        // 17.0); two chunks when the adding kernel also pools (it reads every part of a window:
+        // 512->256 @28x28 + pool 15.6 against 19.7 us)
+        const int keep = split == 2 ? 4 : 2;
+        while (want < 16 && best.wgs1 * want < 256 && want * keep <= nchunks) want *= 2;
         if (want > 1 && !split_fits(want)) want = 1;
         if (want == 1 && split == 2) return Plan();
         best.nss = want;
