@@ -199,7 +199,8 @@ int sconv_tune_reset(void);
 
 /*
  * Writes the plan the forward calls would launch for this descriptor into out (NUL-terminated,
- * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices), or
+ * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices;
+ * geometry "-": the variant has one; "dense" and names ending in d: the form without zero tests), or
  * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor
  * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice);
  * "variant/model" for a descriptor that was not tuned.  Host only.

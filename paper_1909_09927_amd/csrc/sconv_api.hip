@@ -330,9 +330,8 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         int nwv_lo, nwv_hi;
         int nss_hi;        // largest channel split across workgroups to try (1: the variant has none)
     };
-    static const char* const no_geoms[] = {"", nullptr};
     const Family fams[] = {
-        {V_PW, pw_supported(p, pooled), no_geoms, 8, 16, 1},
+        {V_PW, pw_supported(p, pooled), pw_geoms(), 8, 16, 1},
         {V_TAP, tap_supported(p, pooled), tap_geoms(), 8, 16, 16},
         {V_QUAD, quad_supported(p, pooled), quad_geoms(), 8, 16, 16},
         {V_WIDE, wide_supported(p, pooled), wide_geoms(), 4, 8, 1},

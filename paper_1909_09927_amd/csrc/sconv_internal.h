@@ -96,6 +96,7 @@ int launch_split_reduce(const Problem& p, bool pooled, const float* part, int ns
                         hipStream_t stream);
 
 // Candidate geometry names of the variants (for sconv_tune); null-terminated arrays.
+const char* const* pw_geoms();
 const char* const* tap_geoms();
 const char* const* quad_geoms();
 const char* const* wide_geoms();

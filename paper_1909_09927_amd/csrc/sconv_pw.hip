@@ -58,7 +58,11 @@ __device__ __forceinline__ void channel_blocks(std::integer_sequence<int, Qs...>
 
 // Plain: a tile is 32 consecutive positions of the batch's flattened planes (8 quads).
 // Pooled: a tile is 2 rows x 14 columns of one image, row r in lanes 16r .. 16r+13 (quads 4r .. 4r+3).
-template <bool POOL, int NWV, int XB>
+// DENSE: no zero tests - for maps without dead channels or empty regions, where no channel of a
+// 32-position tile is ever all zero and the test (a compare, a mask, two scalar branches per channel
+// pair) only takes issue time from the matrix instructions.  Lanes without a position then feed
+// whatever they loaded into accumulators that are never stored.
+template <bool POOL, int NWV, int XB, bool DENSE>
 __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))) void pw_kernel(Problem p, PwCfg cfg, const float* __restrict__ x,
                                                       const float* __restrict__ w, float* __restrict__ y)
 {
@@ -164,13 +168,19 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
                     wn0 = wl[(2 * j + 2) * KBP];
                     wn1 = wl[(2 * j + 3) * KBP];
                 }
-                const float xv = xok ? xb[j] : 0.0f;
-                // one test per channel and tile: a channel without a nonzero in the tile is skipped
-                const unsigned long long m = __ballot(xv != 0.0f);
-                unsigned lo = (unsigned)m, hi = (unsigned)(m >> 32);
-                asm volatile("" : "+s"(lo), "+s"(hi));   // two 32-bit scalar tests
-                if (lo) channel_blocks<0>(std::make_integer_sequence<int, 8>{}, xv, wc0, acc);
-                if (hi) channel_blocks<8>(std::make_integer_sequence<int, 8>{}, xv, wc1, acc);
+                if (DENSE) {
+                    const float xv = xb[j];
+                    channel_blocks<0>(std::make_integer_sequence<int, 8>{}, xv, wc0, acc);
+                    channel_blocks<8>(std::make_integer_sequence<int, 8>{}, xv, wc1, acc);
+                } else {
+                    const float xv = xok ? xb[j] : 0.0f;
+                    // one test per channel and tile: a channel without a nonzero in the tile is skipped
+                    const unsigned long long m = __ballot(xv != 0.0f);
+                    unsigned lo = (unsigned)m, hi = (unsigned)(m >> 32);
+                    asm volatile("" : "+s"(lo), "+s"(hi));   // two 32-bit scalar tests
+                    if (lo) channel_blocks<0>(std::make_integer_sequence<int, 8>{}, xv, wc0, acc);
+                    if (hi) channel_blocks<8>(std::make_integer_sequence<int, 8>{}, xv, wc1, acc);
+                }
                 xb[j] = load_x(cnext + 2 * j);
                 wc0 = wn0;
                 wc1 = wn1;
@@ -278,7 +288,7 @@ int occupancy(size_t lds_bytes)
     for (int i = 0; i < nseen; ++i)
         if (seen_bytes[i] == lds_bytes) return seen_occ[i];
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, pw_kernel<POOL, NWV, XB>, NWV * 64, lds_bytes) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, pw_kernel<POOL, NWV, XB, false>, NWV * 64, lds_bytes) !=
             hipSuccess || nb < 1)
         nb = 1;
     if (nseen < 8) {
@@ -289,11 +299,11 @@ int occupancy(size_t lds_bytes)
     return nb;
 }
 
-template <bool POOL, int NWV, int XB>
-int launch_nwv(const Problem& p, const PwCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
-               const float* w, float* y, hipStream_t stream)
+template <bool POOL, int NWV, int XB, bool DENSE>
+int launch_inst(const Problem& p, const PwCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
+                const float* w, float* y, hipStream_t stream)
 {
-    auto kern = pw_kernel<POOL, NWV, XB>;
+    auto kern = pw_kernel<POOL, NWV, XB, DENSE>;
     static size_t opted = 48 * 1024;  // dynamic LDS above 48 KiB is opted into once per kernel
     if (lds_bytes > opted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -303,6 +313,19 @@ int launch_nwv(const Problem& p, const PwCfg& cfg, dim3 grid, size_t lds_bytes, 
     }
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds_bytes, stream, p, cfg, x, w, y);
     return launch_status();
+}
+
+const char* const kPwGeoms[] = {"", "dense", nullptr};
+
+// the zero-testing kernel unless the dense form is named (by sconv_tune's measurement or SCONV_PW_GEOM)
+template <bool POOL, int NWV, int XB>
+int launch_nwv(const Problem& p, const PwCfg& cfg, dim3 grid, size_t lds_bytes, const float* x,
+               const float* w, float* y, hipStream_t stream)
+{
+    const char* geom = pinned_geom("SCONV_PW_GEOM");
+    if (geom && !strcmp(geom, "dense"))
+        return launch_inst<POOL, NWV, XB, true>(p, cfg, grid, lds_bytes, x, w, y, stream);
+    return launch_inst<POOL, NWV, XB, false>(p, cfg, grid, lds_bytes, x, w, y, stream);
 }
 
 // Split of one launch over wavefronts, priced like the 3x3 kernels: rounds of workgroups over 256
@@ -388,6 +411,8 @@ bool pw_supported(const Problem& p, bool pooled)
     if ((long long)p.N * p.C * p.H * p.W >= (1LL << 30)) return false;   // 32-bit byte offsets into the input
     return true;
 }
+
+const char* const* pw_geoms() { return kPwGeoms; }
 
 int launch_pointwise(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                      hipStream_t stream)

@@ -382,6 +382,33 @@ def test_quad_channel_split_across_workgroups(device, monkeypatch, shp, geom, sp
         check_pool_forward(layer, x, w, integer_exact=True)
 
 
+PW_SHAPES = [
+    (2, 64, 9, 11, 70, 1, 1, 1, 0, 1, (2, 2, 2)),       # ragged filter block, odd plane size, ragged last tile
+    (1, 128, 28, 28, 128, 1, 1, 1, 0, 1, (2, 2, 2)),
+    (3, 256, 7, 7, 64, 1, 1, 1, 0, 2, (2, 2, 2)),       # grouped, plane smaller than a tile
+    (1, 192, 30, 58, 40, 1, 1, 1, 0, 1, (2, 2, 2)),     # pooled tiles with ragged columns
+    (2, 64, 5, 8, 64, 1, 1, 1, 0, 1, (2, 2, 2)),        # odd height: last row unpooled
+]
+
+
+@pytest.mark.parametrize("split", [None, "8,2", "16,4"])
+@pytest.mark.parametrize("shp", PW_SHAPES)
+def test_pointwise_dense_form(device, monkeypatch, shp, split):
+    """The 1x1 matrix-core kernel without its zero tests: the same sums, and lanes that have no
+    position must not leak into stored results (ragged tiles, pooled tiles with unused columns)."""
+    monkeypatch.setenv("SCONV_PW_GEOM", "dense")
+    if split:
+        monkeypatch.setenv("SCONV_PW_SPLIT", split)
+    layer, x, w = _mk(195, shp)
+    d = sconv.desc_for(to_dev(x), to_dev(w), layer.stride, layer.pad, layer.groups, None, True)
+    assert sconv.sconv_variant_name(d) == "quad1x1"
+    check_forward(layer, x, w, relu=True)
+    check_pool_forward(layer, x, w)
+    layer, x, w = _mk(196, shp, integer=True)
+    check_forward(layer, x, w, relu=False, integer_exact=True)
+    check_pool_forward(layer, x, w, integer_exact=True)
+
+
 GEN_ANY_POOL = [
     (2, 20, 13, 13, 70, 3, 3, 1, 1, 1, (3, 3, 2)),      # overlapping 3x3 / stride 2 windows (7 per tile)
     (1, 48, 27, 27, 130, 5, 5, 1, 2, 2, (3, 3, 2)),     # grouped, two filters per lane possible
