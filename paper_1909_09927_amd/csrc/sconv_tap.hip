@@ -412,17 +412,17 @@ Plan plan_geom(const Problem& p, int split)
     const int nss = pin_nss ? pin_nss : 1;
     if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
     if (pin_nss == 1 && split == 2) return best;
-    if (!pin_nss && split == 2 && !small) return best;
+    if (!pin_nss && split == 2 && !small && !mid) return best;
     // measured on mid-sized launches: one filter per lane (twice the workgroups) with the channels
     // split beats two filters per lane, which the pricing below would prefer
-    if (mid && split == 1 && G::KPL > 1 && !pin_nss && !pin_nwv && !pinned_geom("SCONV_TAP_GEOM")) return best;
+    if (mid && split >= 1 && G::KPL > 1 && !pin_nss && !pin_nwv && !pinned_geom("SCONV_TAP_GEOM")) return best;
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
             // a whole-map tile has as many channel slices as wavefronts; split across workgroups,
             // eight longer slices measure 10 % faster than sixteen (512 @7x7, batch 16 and 32)
-            if (!pin_nwv && !pin_nss && mid && split == 1 && cfg.ntiles == 1 && nwv != 8) continue;
+            if (!pin_nwv && !pin_nss && mid && split >= 1 && cfg.ntiles == 1 && nwv != 8) continue;
             // the slice reduction reuses the filter buffers; a large tile's partial sums need more
             size_t lds_bytes = buf_bytes;
             if (ncs > 1 && nt * red_per_tile > lds_bytes) lds_bytes = nt * red_per_tile;
@@ -489,10 +489,10 @@ Plan plan_geom(const Problem& p, int split)
         best.nss = best.cfg.NSS = want;
         if (want > 1) best.cost = best.cost / want + 9000.0;
     }
-    if (!pin_nss && split == 1 && mid && best.cost >= 0.0) {
+    if (!pin_nss && split >= 1 && mid && best.cost >= 0.0) {
         // mid-sized launches: up to 768 workgroups (a round and a half of two per compute unit) of
         // four chunks or more, four ways at most (512 channels @14x14: batch 4 57 -> 46 us, batch 8
-        // 87 -> 64; @7x7: batch 16 56 -> 43, batch 32 80 -> 72)
+        // 87 -> 64, with fused pooling 71 -> 65; @7x7: batch 16 56 -> 43, batch 32 80 -> 72)
         int want = 1;
         // and every wavefront keeps 16 channels or more (fewer do not pay for the slice reduction
         // and the tile epilogue, which every workgroup runs: 512 @7x7 at batch 32, 16 slices, four
@@ -503,6 +503,8 @@ Plan plan_geom(const Problem& p, int split)
         if (want > 1 && split_fits(want)) {
             best.nss = best.cfg.NSS = want;
             best.cost = best.cost / want + 9000.0;
+        } else if (split == 2) {
+            return Plan();    // a pooled layer stays on its pooled tiles
         }
     }
     return best;
