@@ -373,8 +373,10 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
             PlanPin pin;
             memset(&pin, 0, sizeof(pin));
             snprintf(pin.geom, sizeof(pin.geom), "%s", *g);
-            if (!try_one(f.v, &pin)) continue;
-            for (int nss = 1; nss <= f.nss_hi && err == SCONV_OK; nss *= 2) {
+            // (a plain geometry serves a fused call only with its channels split: start there)
+            const bool unsplit_ok = try_one(f.v, &pin);
+            if (!unsplit_ok && !(pooled && f.nss_hi > 1)) continue;
+            for (int nss = unsplit_ok ? 1 : 2; nss <= f.nss_hi && err == SCONV_OK; nss *= 2) {
                 bool any = false;   // a split the launch is too large for applies with no nwv, ncs
                 for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
                     for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
