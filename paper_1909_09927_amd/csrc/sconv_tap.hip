@@ -371,7 +371,7 @@ struct Plan {
 // filter chunk in flight, so a launch of fewer workgroups than compute units waits on the memory
 // latency chunk after chunk; the split divides that chain, for the price of the second, small
 // kernel that adds the partial sums.  The model splits launches of fewer than 128 tile-workgroups
-// (measured 1.4-3.5x faster there) and, two to four ways, launches of up to 512 that walk 16 or more
+// (measured 1.4-3.5x faster there) and, two to four ways, launches of up to 768 that walk 16 or more
 // chunks with one filter per lane (around 200 workgroups of shorter chains the split measures
 // between 1.2x faster and 1.5x slower); sconv_tune tries splits of launches up to 512.
 template <class G>
@@ -401,7 +401,7 @@ Plan plan_geom(const Problem& p, int split)
     const bool large = tile_wgs >= 512;   // several rounds of workgroups
     // a few workgroups per compute unit, each walking 16 or more chunks: still a chain of chunk
     // latencies with little to overlap it
-    const bool mid = !small && tile_wgs <= 512 && nchunks >= 16;
+    const bool mid = !small && tile_wgs <= 768 && nchunks >= 16;
     const size_t part_bytes = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     auto split_fits = [&](int nss) {
         return !G::POOL && nss <= nchunks && nss * part_bytes <= split_scratch_bytes() &&
@@ -416,13 +416,18 @@ Plan plan_geom(const Problem& p, int split)
     // measured on mid-sized launches: one filter per lane (twice the workgroups) with the channels
     // split beats two filters per lane, which the pricing below would prefer
     if (mid && split >= 1 && G::KPL > 1 && !pin_nss && !pin_nwv && !pinned_geom("SCONV_TAP_GEOM")) return best;
+    // Mid-sized launches, measured: whole-map tiles (as many channel slices as wavefronts) run 10 %
+    // faster split across workgroups with eight longer slices than with sixteen (512 @7x7, batch 16
+    // and 32); smaller tiles run fastest as 2 tiles x 8 slices on every shape tried (14x14 and 28x28
+    // maps, 256-512 channels, batch 4-32: sconv_tune's pick each time, 5-20 % ahead of 16 slices).
+    // The first scan keeps to those; the second takes anything if they do not fit.
+    const bool steer = mid && split >= 1 && !pin_nwv && !pin_nss;
+    for (int scan = steer ? 0 : 1; scan < 2 && best.cost < 0.0; ++scan)
     for (int nwv = 8; nwv <= G::MAXW; nwv *= 2) {
         for (int ncs = 1; ncs <= nwv && ncs <= G::CCH; ncs *= 2) {
             const int nt = nwv / ncs;
             if (pin_nwv && (pin_nwv != nwv || pin_ncs != ncs)) continue;
-            // a whole-map tile has as many channel slices as wavefronts; split across workgroups,
-            // eight longer slices measure 10 % faster than sixteen (512 @7x7, batch 16 and 32)
-            if (!pin_nwv && !pin_nss && mid && split >= 1 && cfg.ntiles == 1 && nwv != 8) continue;
+            if (scan == 0 && (cfg.ntiles == 1 ? nwv != 8 : (nwv != 16 || ncs != 8))) continue;
             // the slice reduction reuses the filter buffers; a large tile's partial sums need more
             size_t lds_bytes = buf_bytes;
             if (ncs > 1 && nt * red_per_tile > lds_bytes) lds_bytes = nt * red_per_tile;
@@ -490,8 +495,8 @@ Plan plan_geom(const Problem& p, int split)
         if (want > 1) best.cost = best.cost / want + 9000.0;
     }
     if (!pin_nss && split >= 1 && mid && best.cost >= 0.0) {
-        // mid-sized launches: up to 768 workgroups (a round and a half of two per compute unit) of
-        // four chunks or more, four ways at most (512 channels @14x14: batch 4 57 -> 46 us, batch 8
+        // mid-sized launches (up to 768 tile-workgroups): up to 768 workgroups (a round and a half of two
+        // per compute unit) of four chunks or more, four ways at most (512 channels @14x14: batch 4 57 -> 46 us, batch 8
         // 87 -> 64, with fused pooling 71 -> 65; @7x7: batch 16 56 -> 43, batch 32 80 -> 72)
         int want = 1;
         // and every wavefront keeps 16 channels or more (fewer do not pay for the slice reduction
