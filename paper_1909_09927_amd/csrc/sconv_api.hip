@@ -386,7 +386,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
                         any |= try_one(f.v, &pin);
                     }
                 }
-                if (!any) break;
+                if (!any && !(pooled && nss == 1)) break;   // (a plain geometry serves a fused call only when split)
             }
         }
     }
