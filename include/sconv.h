@@ -92,8 +92,9 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
  * With a workspace lent for the stream (sconv_set_workspace), a launch of fewer than 128
- * workgroups ("tap3x3" and "gen": deep layers at batch 1), or of 100-400 tiles of "quad3x3" on a
- * map 28 or more wide, is split along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
+ * workgroups ("tap3x3" and "gen": deep layers at batch 1), a "tap3x3" launch of up to 768
+ * workgroups that walks 256 or more channels, or one of 100-400 tiles of "quad3x3" on a map 28 or
+ * more wide, is split along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
  * and a second kernel on the same stream adds them in a fixed order and applies ReLU (and the
  * pooling of sconv_pool_forward).  Results stay deterministic; the association of the fp32 sums
  * differs from the unsplit kernel's.
