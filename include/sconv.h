@@ -8,8 +8,11 @@
  * Outputs are overwritten, never accumulated into.  Calls may come from several host threads
  * (planning and enqueueing are serialised inside the library); the only state kept between calls
  * is cached launch information (occupancy answers) for the device the first calls ran on - so one
- * process should drive one device -, the plans sconv_tune found and the workspaces lent with
- * sconv_set_workspace.
+ * process should drive one device -, the plans sconv_tune found, the workspaces lent with
+ * sconv_set_workspace and the SCONV_* environment as first read.  Calls that change process state:
+ * sconv_tune / sconv_tune_reset (plan table), sconv_set_workspace / sconv_clear_workspaces (lent
+ * workspaces), sconv_env_refresh; every other call only reads it.  A caller that wants none of it
+ * uses the ..._ws forms and never tunes.
  *
  * Notation follows Table 1 of the paper: feature map i_h x i_w (H x W here), kernel k_h x k_w
  * (R x S), pooling window p_h x p_w, convolution stride c_s, pooling stride p_s.  Several input
@@ -142,10 +145,32 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  *            layers).  The caller keeps the memory alive while such launches - or graphs captured
  *            from them - can still run, and runs the launches that share a workspace in stream
  *            order: concurrent launches on one workspace race.  Contents need no initialisation.
- *            Host only; nothing is enqueued.
+ *            Nothing is enqueued, but the current device is asked of the HIP runtime (which
+ *            initialises it).  The entry is keyed by (device, stream handle) and outlives the
+ *            stream: withdraw a workspace (NULL, 0) before destroying its stream - a later stream
+ *            that reuses the handle would otherwise inherit the stale pointer - or call
+ *            sconv_clear_workspaces.  The ..._ws calls below need none of this.
+ *   sconv_clear_workspaces: withdraws every lent workspace of every device and stream.
  */
 int sconv_workspace_size(const sconv_desc_t* desc, int pooled, size_t* bytes);
 int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
+int sconv_clear_workspaces(void);
+
+/*
+ * sconv_forward / sconv_pool_forward (Sections 5 and 6) with the workspace as an argument of the
+ * call instead of a buffer lent to the stream beforehand: nothing about the workspace is remembered
+ * after the call returns, and a buffer lent with sconv_set_workspace is ignored for this call.
+ *   ws_dev device, scratch: ws_bytes bytes, 16-byte aligned, contents irrelevant before and undefined
+ *          after; NULL with ws_bytes 0: the call plans without a split.  sconv_workspace_size tells
+ *          how much a descriptor can use; with less, smaller splits or none are planned.
+ * The launches read and write ws_dev in stream order; the caller keeps it alive until they have
+ * run and does not share it with launches that may run at the same time.
+ * Errors as the plain calls, plus SCONV_EINVAL for a misaligned or half-given workspace.
+ */
+int sconv_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
+                     void* ws_dev, size_t ws_bytes, void* hip_stream);
+int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
+                          void* ws_dev, size_t ws_bytes, void* hip_stream);
 
 /*
  * Name of the kernel variant the two forward calls would pick for this descriptor (a static
@@ -163,7 +188,8 @@ int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream);
  * across workgroups), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes
  * before the static rules.
- * Returns NULL for an invalid descriptor.  Host only.
+ * Returns NULL for an invalid descriptor.  Nothing is enqueued, but the call asks the HIP runtime for
+ * the current device (to see whether a workspace is lent there), which initialises the runtime.
  */
 const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
 
@@ -204,9 +230,19 @@ int sconv_tune_reset(void);
  * geometry "-": the variant has one; "dense" and names ending in d: the form without zero tests), or
  * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor
  * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice);
- * "variant/model" for a descriptor that was not tuned.  Host only.
+ * "variant/model" for a descriptor that was not tuned.  Nothing is enqueued; asks the HIP runtime
+ * for the current device, as sconv_variant_name does.
  */
 int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size);
+
+/*
+ * The SCONV_* environment variables (tuning aids for profiles and tests: SCONV_VARIANT,
+ * SCONV_{TAP,QUAD,WIDE,GEN,PW}_GEOM, SCONV_{TAP,QUAD,WIDE,GEN,PW}_SPLIT, SCONV_ENCODE,
+ * SCONV_TRACE_PLAN) are read once, by the first call that needs one, and kept; no launch calls
+ * getenv.  sconv_env_refresh reads them again (a test that changes the environment calls it).  It must
+ * not run while another thread is inside a launching call.  Host only.
+ */
+int sconv_env_refresh(void);
 
 /* Static description of an error code. */
 const char* sconv_strerror(int code);

@@ -64,9 +64,14 @@ def lib() -> ctypes.CDLL:
         L.sconv_strerror.restype = ctypes.c_char_p
         L.sconv_workspace_size.argtypes = [P(Desc), ctypes.c_int, P(ctypes.c_size_t)]
         L.sconv_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
+        L.sconv_clear_workspaces.argtypes = []
+        L.sconv_env_refresh.argtypes = []
+        L.sconv_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sconv_pool_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
-                  "sconv_workspace_size", "sconv_set_workspace"):
+                  "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
+                  "sconv_forward_ws", "sconv_pool_forward_ws"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -145,6 +150,25 @@ def sconv_set_workspace(ws) -> None:
         raise RuntimeError(f"sconv_set_workspace: {strerror(rc)}")
 
 
+def sconv_clear_workspaces() -> None:
+    lib().sconv_clear_workspaces()
+
+
+def sconv_env_refresh() -> None:
+    """Makes the library read its SCONV_* tuning-aid environment variables again (it reads them once)."""
+    lib().sconv_env_refresh()
+
+
+def _ws_args(ws):
+    """(pointer, bytes) of an explicit workspace: None -> (None, 0)."""
+    import torch
+    if ws is None:
+        return None, 0
+    if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.is_contiguous()):
+        raise TypeError("ws must be a contiguous tensor in device memory")
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
 def _check_dev(t, dtype, what):
     import torch
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
@@ -183,8 +207,12 @@ def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None, out
     return values, index, count
 
 
-def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
-    """Sparse convolution; returns y[N,K,OH,OW] (device, fp32)."""
+_NO_WS = object()   # "no ws argument": the plain entry point (a lent workspace applies)
+
+
+def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS):
+    """Sparse convolution; returns y[N,K,OH,OW] (device, fp32).  ws: a device tensor (or None) passed as
+    this call's workspace through sconv_forward_ws; left out, sconv_forward runs."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -196,7 +224,12 @@ def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, OH, OW):
             raise ValueError("out has the wrong shape")
-    rc = lib().sconv_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    if ws is _NO_WS:
+        rc = lib().sconv_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    else:
+        wp, wb = _ws_args(ws)
+        rc = lib().sconv_forward_ws(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), wp, wb,
+                                    _stream())
     if rc:
         raise SconvError(rc, "sconv_forward")
     return out
@@ -224,8 +257,9 @@ def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=N
     return out
 
 
-def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None):
-    """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32)."""
+def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS):
+    """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32).
+    ws: as in sconv_forward (sconv_pool_forward_ws)."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -237,7 +271,12 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None):
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, PH, PW):
             raise ValueError("out has the wrong shape")
-    rc = lib().sconv_pool_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    if ws is _NO_WS:
+        rc = lib().sconv_pool_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    else:
+        wp, wb = _ws_args(ws)
+        rc = lib().sconv_pool_forward_ws(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), wp, wb,
+                                         _stream())
     if rc:
         raise SconvError(rc, "sconv_pool_forward")
     return out

@@ -5,6 +5,8 @@
 
 #include <algorithm>
 #include <array>
+#include <atomic>
+#include <string>
 #include <map>
 #include <vector>
 #include <mutex>
@@ -13,15 +15,48 @@
 
 namespace sconv {
 
-// The pin of the launch in progress.  Written and read under the dispatcher's lock only.
-static const PlanPin* g_pin = nullptr;
+// The pin of the launch in progress, per calling thread.
+static thread_local const PlanPin* g_pin = nullptr;
 
 const PlanPin* current_pin() { return g_pin; }
+
+// The tuning-aid environment (SCONV_*), read once - at the first call that looks - and again only when
+// sconv_env_refresh is called: no launch pays for getenv.
+static const char* const kEnvNames[] = {
+    "SCONV_VARIANT", "SCONV_TAP_GEOM", "SCONV_QUAD_GEOM", "SCONV_WIDE_GEOM", "SCONV_GEN_GEOM", "SCONV_PW_GEOM",
+    "SCONV_TAP_SPLIT", "SCONV_QUAD_SPLIT", "SCONV_WIDE_SPLIT", "SCONV_GEN_SPLIT", "SCONV_PW_SPLIT",
+    "SCONV_ENCODE", "SCONV_TRACE_PLAN", "SCONV_POOL_SPLIT", "SCONV_HANDOFF"};
+constexpr int kEnvCount = (int)(sizeof(kEnvNames) / sizeof(kEnvNames[0]));
+static std::mutex g_env_lock;
+static std::atomic<bool> g_env_read{false};
+static std::string g_env_val[kEnvCount];
+static bool g_env_set[kEnvCount];
+
+static void env_load_locked()
+{
+    for (int i = 0; i < kEnvCount; ++i) {
+        const char* v = getenv(kEnvNames[i]);
+        g_env_set[i] = v != nullptr;
+        g_env_val[i] = v ? v : "";
+    }
+    g_env_read.store(true, std::memory_order_release);
+}
+
+const char* env_value(const char* name)
+{
+    if (!g_env_read.load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_env_lock);
+        if (!g_env_read.load(std::memory_order_relaxed)) env_load_locked();
+    }
+    for (int i = 0; i < kEnvCount; ++i)
+        if (!strcmp(name, kEnvNames[i])) return g_env_set[i] ? g_env_val[i].c_str() : nullptr;
+    return nullptr;
+}
 
 const char* pinned_geom(const char* env_name)
 {
     if (g_pin) return g_pin->geom[0] ? g_pin->geom : nullptr;
-    return getenv(env_name);
+    return env_value(env_name);
 }
 
 void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss)
@@ -35,7 +70,7 @@ void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss)
         *nss = g_pin->nwv ? (g_pin->nss > 1 ? g_pin->nss : 1) : 0;
         return;
     }
-    if (const char* pin = getenv(env_name)) {
+    if (const char* pin = env_value(env_name)) {
         const int got = sscanf(pin, "%d,%d,%d", nwv, ncs, nss);
         if (got == 2) *nss = 1;
         else if (got != 3) *nwv = *ncs = *nss = 0;
@@ -70,8 +105,12 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     p.stride = d->stride; p.pad = d->pad; p.G = d->groups;
     p.Cg = d->C / d->groups;
     p.Kg = d->K / d->groups;
-    p.OH = (d->H + 2 * d->pad - d->R) / d->stride + 1;
-    p.OW = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    // (in 64 bits: H + 2*pad can pass 2^31 with a large pad under a larger kernel)
+    const int64_t oh64 = (d->H + 2 * (int64_t)d->pad - d->R) / d->stride + 1;
+    const int64_t ow64 = (d->W + 2 * (int64_t)d->pad - d->S) / d->stride + 1;
+    if (oh64 >= (int64_t(1) << 31) || ow64 >= (int64_t(1) << 31)) return SCONV_EUNSUPPORTED;
+    p.OH = (int)oh64;
+    p.OW = (int)ow64;
     p.relu = (d->flags & SCONV_RELU) ? 1 : 0;
     if (pooled) {
         if (d->pool_h <= 0 || d->pool_w <= 0 || d->pool_stride <= 0) return SCONV_EINVAL;
@@ -127,7 +166,7 @@ static TuneKey tune_key(const Problem& p, bool pooled)
 // The tuned entry for this problem, unless SCONV_VARIANT pins the variant.  Caller holds g_lock.
 static const Tuned* tuned_for(const Problem& p, bool pooled)
 {
-    if (getenv("SCONV_VARIANT")) return nullptr;
+    if (env_value("SCONV_VARIANT")) return nullptr;
     auto it = g_tuned.find(tune_key(p, pooled));
     return it == g_tuned.end() ? nullptr : &it->second;
 }
@@ -167,7 +206,7 @@ static bool small_quad_split(const Problem& p, bool pooled, PlanPin* pin)
 static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr)
 {
     if (static_pin) memset(static_pin, 0, sizeof(*static_pin));
-    const char* pin = getenv("SCONV_VARIANT");
+    const char* pin = env_value("SCONV_VARIANT");
     if (pin && !strcmp(pin, "rows")) return V_ROWS;
     if (pin && !strcmp(pin, "tap")) return tap_supported(p, pooled) ? V_TAP : V_ROWS;
     if (pin && !strcmp(pin, "wide")) return wide_supported(p, pooled) ? V_WIDE : V_ROWS;
@@ -243,6 +282,16 @@ static int launch_variant(Variant v, const PlanPin* pin, const Problem& p, bool 
     return rc;
 }
 
+// Whether a launch on stream s would find a workspace: the one that came with the call, else a lent one.
+static bool have_workspace(hipStream_t s)
+{
+    if (split_scratch_is_given()) {
+        split_scratch_select(s);
+        return split_scratch_possible(s);
+    }
+    return split_workspace_lent(s, false);
+}
+
 static int run(const Problem& p, bool pooled, const float* x, const float* w, float* y, hipStream_t s)
 {
     // the launchers cache occupancy answers and attribute opt-ins in static variables: planning and
@@ -253,7 +302,7 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
         if (rc != SCONV_EUNSUPPORTED) return rc;
     }
     PlanPin sp;
-    Variant v = choose(p, pooled, split_workspace_lent(s, false), &sp);
+    Variant v = choose(p, pooled, have_workspace(s), &sp);
     int rc = SCONV_EUNSUPPORTED;
     if (sp.geom[0]) {
         rc = launch_variant(v, &sp, p, pooled, x, w, y, s);
@@ -359,7 +408,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     };
     // the static rules' own choice comes first: it stays unless something measures clearly faster
     PlanPin sp;
-    Variant v_static = choose(p, pooled, split_workspace_lent(s, false), &sp);
+    Variant v_static = choose(p, pooled, have_workspace(s), &sp);
     bool have_static = try_one(v_static, sp.geom[0] ? &sp : nullptr);
     if (!have_static && sp.geom[0]) {
         v_static = choose(p, pooled);
@@ -522,6 +571,47 @@ extern "C" int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, 
     return run(p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
+// Runs one forward call with the workspace the caller passed (null: none) in place of a lent one.
+static int run_with(const Problem& p, bool pooled, const float* x, const float* w, float* y, void* ws,
+                    size_t ws_bytes, hipStream_t s)
+{
+    split_scratch_given(ws, ws_bytes, true);
+    const int rc = run(p, pooled, x, w, y, s);
+    split_scratch_given(nullptr, 0, false);
+    return rc;
+}
+
+extern "C" int sconv_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
+                                void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    if ((ws_dev == nullptr) != (ws_bytes == 0) || reinterpret_cast<uintptr_t>(ws_dev) % 16) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    return run_with(p, false, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                     float* y_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    if ((ws_dev == nullptr) != (ws_bytes == 0) || reinterpret_cast<uintptr_t>(ws_dev) % 16) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, true, &p);
+    if (rc) return rc;
+    if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    return run_with(p, true, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_env_refresh(void)
+{
+    std::lock_guard<std::mutex> lock(g_lock);
+    std::lock_guard<std::mutex> elock(g_env_lock);
+    env_load_locked();
+    return SCONV_OK;
+}
+
 extern "C" int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
                              void* hip_stream)
 {
@@ -577,6 +667,13 @@ extern "C" int sconv_set_workspace(void* ws_dev, size_t bytes, void* hip_stream)
     if (reinterpret_cast<uintptr_t>(ws_dev) % 16) return SCONV_EINVAL;
     std::lock_guard<std::mutex> lock(g_lock);
     return split_workspace_set(ws_dev, bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_clear_workspaces(void)
+{
+    std::lock_guard<std::mutex> lock(g_lock);
+    split_workspace_clear();
+    return SCONV_OK;
 }
 
 extern "C" int sconv_tune_reset(void)

@@ -314,7 +314,7 @@ int launch_encode(const Problem& p, int fmt, const float* x, float* values, int3
     const bool large_map = (long long)p.H * p.W >= 2048;
     const bool long_1x1 = p.R == 1 && p.S == 1 && (long long)p.H * p.W >= 196 && p.Cg >= 384;
     bool tiled = large_map || long_1x1;
-    if (const char* pin = getenv("SCONV_ENCODE"))   // tuning aid and tests: "tile" or "rows"
+    if (const char* pin = env_value("SCONV_ENCODE"))   // tuning aid and tests: "tile" or "rows"
         tiled = !strcmp(pin, "tile");
     if (tiled && bh_max * bw_max <= STAGE && tiles < (1ll << 31) && rows_per_ng < (1ll << 31)) {
         hipLaunchKernelGGL(encode_tile_kernel, dim3((unsigned)tiles), dim3(kTileBlock), 0, stream, p, pecr ? 1 : 0,

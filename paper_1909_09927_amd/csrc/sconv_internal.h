@@ -72,6 +72,10 @@ struct PlanPin {
 };
 const PlanPin* current_pin();
 
+// Value of one of the library's tuning-aid environment variables as it was when the library first
+// looked (or when sconv_env_refresh last ran); null when unset.
+const char* env_value(const char* name);
+
 // Geometry pin for a launcher: the dispatcher's, else the named environment variable's.
 const char* pinned_geom(const char* env_name);
 // Split pin "nwv,ncs" or "nwv,ncs,nss" likewise; all 0 when there is none.
@@ -86,9 +90,15 @@ void pinned_split(const char* env_name, int* nwv, int* ncs, int* nss = nullptr);
 // address and for its size.  Without one they plan without a split.
 constexpr size_t kSplitWorkspaceCap = size_t(64) << 20;   // more than this is never asked for
 int split_workspace_set(void* ws, size_t bytes, hipStream_t stream);
+void split_workspace_clear();
 // whether a workspace is lent for this stream of the current device (any_stream: for any of its streams)
 bool split_workspace_lent(hipStream_t stream, bool any_stream);
 void split_scratch_select(hipStream_t stream);
+// A workspace that comes with one call (the ..._ws entry points) instead of the stream's lent one:
+// set before the call's launches are planned and cleared (on = false) after them; per calling thread.
+// ws may be null: that call then plans without a split.
+void split_scratch_given(void* ws, size_t bytes, bool on);
+bool split_scratch_is_given();
 bool split_scratch_possible(hipStream_t stream);
 float* split_scratch(hipStream_t stream);
 size_t split_scratch_bytes();

@@ -60,7 +60,9 @@ struct Lent {
     size_t bytes;
 };
 std::map<std::pair<int, hipStream_t>, Lent> g_lent;   // under the dispatcher's lock
-Lent g_cur = {nullptr, 0};                              // the workspace of the launch being planned
+thread_local Lent g_cur = {nullptr, 0};                 // the workspace of the launch being planned
+thread_local Lent g_given = {nullptr, 0};               // the workspace passed with the call in progress
+thread_local bool g_given_on = false;
 
 }  // namespace
 
@@ -76,6 +78,8 @@ int split_workspace_set(void* ws, size_t bytes, hipStream_t stream)
     return SCONV_OK;
 }
 
+void split_workspace_clear() { g_lent.clear(); }
+
 bool split_workspace_lent(hipStream_t stream, bool any_stream)
 {
     int dev = 0;
@@ -86,8 +90,20 @@ bool split_workspace_lent(hipStream_t stream, bool any_stream)
     return false;
 }
 
+void split_scratch_given(void* ws, size_t bytes, bool on)
+{
+    g_given = Lent{static_cast<float*>(ws), bytes};
+    g_given_on = on;
+}
+
+bool split_scratch_is_given() { return g_given_on; }
+
 void split_scratch_select(hipStream_t stream)
 {
+    if (g_given_on) {   // a call that brought its own workspace (or none) does not look at the lent ones
+        g_cur = g_given;
+        return;
+    }
     g_cur = Lent{nullptr, 0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return;

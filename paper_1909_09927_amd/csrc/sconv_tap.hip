@@ -633,7 +633,7 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
         }
     }
     if (!best) return SCONV_EUNSUPPORTED;
-    if (getenv("SCONV_TRACE_PLAN"))
+    if (env_value("SCONV_TRACE_PLAN"))
         fprintf(stderr, "sconv: tap3x3 %s nwv=%d ncs=%d nt=%d nss=%d cost=%.0f\n", best->name, best_plan.nwv,
                 best_plan.cfg.NCS, best_plan.cfg.NT, best_plan.nss, best_plan.cost);
     return best->launch(best_plan, p, pooled, x, w, y, stream);

@@ -531,6 +531,32 @@ def test_a_workspace_that_is_too_small_or_absent_means_unsplit_plans(device):
         assert (np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
 
 
+def test_a_workspace_passed_with_the_call_splits_like_a_lent_one_and_none_means_unsplit(device):
+    """sconv_forward_ws / sconv_pool_forward_ws: the workspace is an argument, nothing sticky.  With the
+    same bytes as the lent one the launch plans the same split (bit-identical results); with none it
+    runs unsplit; both meet the oracle's bar.  A lent workspace is ignored by these calls."""
+    import oracle
+    for shp, pool in (((1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None), None),
+                      ((2, 256, 14, 14, 128, 3, 3, 1, 1, 1, (2, 2, 2)), (2, 2, 2))):
+        layer, x, w = _mk(187, shp)
+        xd, wd = to_dev(x), to_dev(w)
+        own = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        if pool:
+            ref, scale = oracle.conv_pool(x, w, pool, 1, 1, 1)
+            lent = sconv.sconv_pool_forward(xd, wd, pool, 1, 1, 1)
+            given = sconv.sconv_pool_forward(xd, wd, pool, 1, 1, 1, ws=own)
+            none = sconv.sconv_pool_forward(xd, wd, pool, 1, 1, 1, ws=None)
+        else:
+            ref, scale = oracle.conv(x, w, 1, 1, 1, relu=True)
+            lent = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True)
+            given = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, ws=own)
+            none = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, ws=None)
+        torch.cuda.synchronize()
+        assert torch.equal(lent, given)
+        for got in (given, none):
+            assert (np.abs(got.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
 @pytest.mark.parametrize("geom", ["gk1d", "gk2d", "gpk1d", "gpk2d"])
 @pytest.mark.parametrize("shp", [
     (2, 20, 11, 11, 70, 5, 5, 1, 0, 1, (2, 2, 2)),

@@ -18,7 +18,8 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(sconv_[a-z_]+)\s*\(", text))
     assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
             "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool", "sconv_tune",
-            "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace"} <= names
+            "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace",
+            "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_env_refresh", "sconv_clear_workspaces"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
@@ -196,6 +197,48 @@ def test_workspace_calls_validate_on_the_host():
     assert L.sconv_set_workspace(ctypes.c_void_p(256), 0, None) == sconv.SCONV_EINVAL
     assert L.sconv_set_workspace(None, 4096, None) == sconv.SCONV_EINVAL
     assert L.sconv_set_workspace(ctypes.c_void_p(260), 4096, None) == sconv.SCONV_EINVAL          # not 16-byte aligned
+
+
+def test_explicit_workspace_calls_validate_on_the_host():
+    L = sconv.lib()
+    d = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1, 1, (2, 2, 2))
+    p = ctypes.c_void_p(4096)
+    for fn in (L.sconv_forward_ws, L.sconv_pool_forward_ws):
+        assert fn(ctypes.byref(d), None, p, p, None, 0, None) == sconv.SCONV_EINVAL          # null input
+        assert fn(ctypes.byref(d), p, p, p, ctypes.c_void_p(4096), 0, None) == sconv.SCONV_EINVAL   # pointer, no bytes
+        assert fn(ctypes.byref(d), p, p, p, None, 64, None) == sconv.SCONV_EINVAL            # bytes, no pointer
+        assert fn(ctypes.byref(d), p, p, p, ctypes.c_void_p(4100), 64, None) == sconv.SCONV_EINVAL  # misaligned
+    bad = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 0, 1, 1)
+    assert L.sconv_forward_ws(ctypes.byref(bad), p, p, p, None, 0, None) == sconv.SCONV_EINVAL
+    assert L.sconv_clear_workspaces() == sconv.SCONV_OK
+
+
+def test_output_size_is_computed_in_64_bits():
+    """H + 2*pad passes 2^31 with a large pad under a larger kernel: an error code, not an overflow."""
+    L = sconv.lib()
+    big = 2**31 - 1
+    d = sconv.make_desc(1, 1, big, 4, 1, big, 3, 1, 2**30 + 5, 1)
+    d.pad = 2**30 + 5
+    oh, ow = ctypes.c_int32(), ctypes.c_int32()
+    rc = L.sconv_output_dims(ctypes.byref(d), ctypes.byref(oh), ctypes.byref(ow), None, None)
+    assert rc in (sconv.SCONV_EINVAL, sconv.SCONV_EUNSUPPORTED)
+
+
+def test_environment_is_read_once_and_on_request(monkeypatch):
+    """SCONV_VARIANT is a tuning aid the library reads once; sconv_env_refresh makes it look again."""
+    d = sconv.make_desc(2, 64, 14, 14, 64, 3, 3, 1, 1, 1)
+    os.environ.pop("SCONV_VARIANT", None)
+    sconv.sconv_env_refresh()
+    before = sconv.sconv_variant_name(d)
+    os.environ["SCONV_VARIANT"] = "rows"
+    try:
+        assert sconv.sconv_variant_name(d) == before          # not looked at again
+        sconv.sconv_env_refresh()
+        assert sconv.sconv_variant_name(d) == "rows"
+    finally:
+        del os.environ["SCONV_VARIANT"]
+        sconv.sconv_env_refresh()
+    assert sconv.sconv_variant_name(d) == before
 
 
 def test_binding_refuses_host_tensors():
