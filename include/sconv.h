@@ -49,7 +49,8 @@ enum {
                                 pad >= R or pad >= S, empty output, pooling window larger than
                                 the convolution output, unknown format or flag                 */
     SCONV_EUNSUPPORTED = -2, /* valid problem that exceeds a kernel limit (see each call)      */
-    SCONV_ELAUNCH = -3       /* the HIP runtime reported an error for the launch               */
+    SCONV_ELAUNCH = -3,      /* the HIP runtime reported an error for the launch               */
+    SCONV_ETOOLARGE = -4     /* sconv_forward_static: the problem exceeds the static scratch   */
 };
 
 /*
@@ -171,6 +172,26 @@ int sconv_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* 
                      void* ws_dev, size_t ws_bytes, void* hip_stream);
 int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
                           void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/*
+ * sconv_forward for callers that cannot allocate or lend device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same result and plans as sconv_forward_ws,
+ * but the workspace is the library's own: a fixed array of SCONV_STATIC_SCRATCH_BYTES (16 MiB) in
+ * device memory that belongs to the loaded library (every GPU the library runs on holds its copy
+ * until the process ends).  The call allocates and frees nothing and uses no allocating library
+ * routine; the first call on a device looks the array's address up once (make that call outside a
+ * graph capture).
+ *   Limit: 2 * N*K*OH*OW * 4 bytes (two slices of partial sums, the smallest split) must fit the
+ *   array; a larger problem is refused with SCONV_ETOOLARGE before anything is enqueued - use
+ *   sconv_forward or sconv_forward_ws for it.
+ *   The array keeps the previous call's contents; nothing in it needs clearing, because a split
+ *   launch writes every partial sum it later reads.  All calls on one GPU share the array: run them
+ *   in stream order on one stream.  Calls that overlap on one GPU (two streams, two threads) race.
+ * Other errors as sconv_forward.
+ */
+enum { SCONV_STATIC_SCRATCH_BYTES = 16 << 20 };
+int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
+                         void* hip_stream);
 
 /*
  * Name of the kernel variant the two forward calls would pick for this descriptor (a static

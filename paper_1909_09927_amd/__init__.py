@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libsconv.so")
 SCONV_RELU = 1
 FMT_ECR = 0
 FMT_PECR = 1
-SCONV_OK, SCONV_EINVAL, SCONV_EUNSUPPORTED, SCONV_ELAUNCH = 0, -1, -2, -3
+SCONV_OK, SCONV_EINVAL, SCONV_EUNSUPPORTED, SCONV_ELAUNCH, SCONV_ETOOLARGE = 0, -1, -2, -3, -4
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class SconvError(RuntimeError):
@@ -68,10 +69,11 @@ def lib() -> ctypes.CDLL:
         L.sconv_env_refresh.argtypes = []
         L.sconv_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sconv_pool_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sconv_forward_static.argtypes = [P(Desc), vp, vp, vp, vp]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
-                  "sconv_forward_ws", "sconv_pool_forward_ws"):
+                  "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -232,6 +234,26 @@ def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_
                                     _stream())
     if rc:
         raise SconvError(rc, "sconv_forward")
+    return out
+
+
+def sconv_forward_static(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
+    """sconv_forward with the library's static scratch as workspace (allocates nothing itself: pass
+    `out` to keep the whole call allocation-free); raises SconvError(SCONV_ETOOLARGE) beyond its limit."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    _check_dev(w, torch.float32, "w")
+    desc = desc_for(x, w, stride, pad, groups, None, relu)
+    OH, OW, _, _ = sconv_output_dims(desc)
+    if out is None:
+        out = torch.empty((desc.N, desc.K, OH, OW), dtype=torch.float32, device=x.device)
+    else:
+        _check_dev(out, torch.float32, "out")
+        if tuple(out.shape) != (desc.N, desc.K, OH, OW):
+            raise ValueError("out has the wrong shape")
+    rc = lib().sconv_forward_static(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_forward_static")
     return out
 
 

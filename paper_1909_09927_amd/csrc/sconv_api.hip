@@ -604,6 +604,25 @@ extern "C" int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_de
     return run_with(p, true, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                    float* y_dev, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    // the smallest split keeps two slices of partial sums
+    if (2 * (size_t)p.N * p.K * p.OH * p.OW * sizeof(float) > kStaticScratchBytes) return SCONV_ETOOLARGE;
+    float* ws = nullptr;
+    size_t ws_bytes = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_lock);
+        rc = split_static_scratch(&ws, &ws_bytes);
+    }
+    if (rc) return rc;
+    return run_with(p, false, x_dev, w_dev, y_dev, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
 extern "C" int sconv_env_refresh(void)
 {
     std::lock_guard<std::mutex> lock(g_lock);
@@ -704,6 +723,7 @@ extern "C" const char* sconv_strerror(int code)
     case SCONV_EINVAL: return "invalid argument";
     case SCONV_EUNSUPPORTED: return "shape exceeds a kernel limit";
     case SCONV_ELAUNCH: return "HIP launch failed";
+    case SCONV_ETOOLARGE: return "output tensor too large for the library's static scratch (sconv_forward_static)";
     default: return "unknown sconv error code";
     }
 }

@@ -104,6 +104,10 @@ float* split_scratch(hipStream_t stream);
 size_t split_scratch_bytes();
 int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y,
                         hipStream_t stream);
+// The library's own scratch for callers that may not allocate: a fixed array in device memory, one
+// copy per device.  Looks its address up on the current device at the first call there.
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+int split_static_scratch(float** ptr, size_t* bytes);
 
 // Candidate geometry names of the variants (for sconv_tune); null-terminated arrays.
 const char* const* pw_geoms();

@@ -115,6 +115,31 @@ bool split_scratch_possible(hipStream_t) { return g_cur.ptr != nullptr; }
 float* split_scratch(hipStream_t) { return g_cur.ptr; }
 size_t split_scratch_bytes() { return g_cur.bytes; }
 
+// Scratch of the entry point that may not allocate (sconv_forward_static): partial sums of a split
+// launch, in device memory that is part of the loaded code object.  Every device the library runs on
+// holds its own copy, at its own address, until the process ends.  In host code the array's name is
+// only a handle for the symbol lookup below; kernels get the looked-up address as an argument.
+__device__ __align__(256) static float scratch[kStaticScratchBytes / sizeof(float)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_static_ptr[kMaxDevices];   // per device, under the dispatcher's lock
+}
+
+int split_static_scratch(float** ptr, size_t* bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCONV_ELAUNCH;
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SCONV_ELAUNCH;
+        g_static_ptr[dev] = static_cast<float*>(p);
+    }
+    *ptr = g_static_ptr[dev];
+    *bytes = kStaticScratchBytes;
+    return SCONV_OK;
+}
+
 int launch_split_reduce(const Problem& p, bool pooled, const float* part, int nss, float* y, hipStream_t stream)
 {
     const long long slice = (long long)p.N * p.K * p.OH * p.OW;
