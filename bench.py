@@ -42,11 +42,14 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TF = 157.3  # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
 FP32_MFMA_PEAK_TF = 157.3    # dense fp32 matrix instructions, published
 MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3", "gen")
-# HBM/fabric bytes per launch from the rocprofv3 counter runs (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB,
-# scaled by the copy calibration); keyed by (variant, layer, batch); the summaries are in profiles/.
+# HBM/fabric bytes per launch from rocprofv3 counter runs (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, scaled
+# by the copy calibration), keyed by (plan name, layer, batch): a figure from profiles/, not something this
+# run measures - the line names its source, and prints null when the plan that ran is not in the table.
 MEASURED_TRAFFIC = {
-    ("quad3x3", "vgg-256x56", 8): 54.8e6 + 25.7e6,       # profiles/quad3x3_vgg-256x56_n8.txt (7-row tiles)
+    ("quad3x3/q32t7d/8x4", "vgg-256x56", 8): (54.8e6 + 25.7e6, "profiles/quad3x3_vgg-256x56_n8.txt"),
 }
+# elements per zero test of the kernels that skip whole groups (1: every zero element is skipped)
+SKIP_GRANULE = {"rows": 1, "tap3x3": 1, "quad3x3": 6, "quad1x1": 32, "wide3x3": 16, "gen": 16}
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
 TUNE = True                   # --no-tune: the static dispatch rules and cost models only
 CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
@@ -80,6 +83,42 @@ def layer_work(layer: workloads.Layer, N: int, x: np.ndarray) -> dict:
     alg_bytes = 4.0 * (x.size + layer.K * layer.Cg * layer.R * layer.S + out_elems)
     return {"dense_flops": dense_flops, "nz_flops": nz_flops, "alg_bytes": alg_bytes,
             "zero_ratio": float((x == 0).mean())}
+
+
+def sampled_check(layer, x, w, got, seed: int, npts: int = 4000) -> dict:
+    """Compares outputs of one layer (a host copy `got` of what the GPU wrote) with the CPU oracle at
+    sampled points: `npts` random ones plus a grid of tile and filter-block boundaries (first and last
+    image; filters 0, 63, 64, last; rows and columns around multiples of the kernels' tile sizes and the
+    map's edges).  Pooled layers compare with the window maximum of the oracle's ReLU'd convolution.
+    Bar: |got - ref| <= 1e-4 * sum|x*w| per element.  Returns counts and the worst ratio."""
+    import oracle
+    rng = np.random.default_rng(seed)
+    N, K, OHp, OWp = got.shape
+    pts = [np.stack([rng.integers(0, d, size=npts) for d in got.shape], axis=1)]
+    edge = lambda n: sorted({v for v in (0, 1, 3, 4, 5, 6, 7, 13, 14, 15, 27, 28, 29, n - 2, n - 1) if 0 <= v < n})
+    ns = sorted({0, N - 1})
+    ks = sorted({v for v in (0, 63, 64, 127, 128, K - 1) if v < K})
+    grid = np.array([(n, k, a, b) for n in ns for k in ks for a in edge(OHp) for b in edge(OWp)], dtype=np.int64)
+    pts.append(grid)
+    pts = np.concatenate(pts, axis=0)
+    if layer.pool:
+        ph, pw, ps = layer.pool
+        ref = np.zeros(len(pts))
+        scale = np.zeros(len(pts))
+        for py in range(ph):
+            for px in range(pw):
+                q = pts.copy()
+                q[:, 2] = pts[:, 2] * ps + py
+                q[:, 3] = pts[:, 3] * ps + px
+                v, a = oracle.conv_at(x, w, q, layer.stride, layer.pad, layer.groups, relu=True)
+                ref = np.maximum(ref, v)
+                scale = np.maximum(scale, a)
+    else:
+        ref, scale = oracle.conv_at(x, w, pts, layer.stride, layer.pad, layer.groups, relu=True)
+    err = np.abs(got[tuple(pts.T)].astype(np.float64) - ref)
+    ratio = err / np.maximum(scale, 1e-300)
+    ratio[(err == 0)] = 0.0
+    return {"checked": int(len(pts)), "failed": int((err > 1e-4 * scale).sum()), "worst_ratio": float(ratio.max())}
 
 
 _flush = None
@@ -130,15 +169,29 @@ class DeviceLayer:
                 y = sconv.sconv_forward(xs, ws, layer.stride, layer.pad, layer.groups, relu=True)
             self.sets.append((xs, ws, y))
         d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+        self.host = (x, w)
+        self.tune_wall_s = 0.0
         if TUNE:
             # set-up, outside every timed region: the library times its variants and decompositions on
             # this layer's operands and remembers the fastest for this descriptor
             xs, ws, y = self.sets[0]
+            t0 = time.perf_counter()
             sconv.sconv_tune(xs, ws, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, out=y,
                              flush=flush_buffer())
+            self.tune_wall_s = time.perf_counter() - t0
         self.variant = sconv.sconv_variant_name(d, bool(layer.pool))
         self.plan = sconv.sconv_plan_name(d, bool(layer.pool))
         self.i = 0
+
+    def parity(self, seed: int) -> dict:
+        """The plan that will be timed, on the buffers that will be timed (set 0), against the oracle."""
+        import torch
+        self.i = 0
+        self.run()
+        torch.cuda.synchronize()
+        self.i = 0
+        x, w = self.host
+        return sampled_check(self.layer, x, w, self.sets[0][2].cpu().numpy(), seed)
 
     def run(self):
         xs, ws, y = self.sets[self.i]
@@ -207,6 +260,7 @@ def time_layer(dl: DeviceLayer, iters: int, warmup: int) -> float:
         warm.append(e0.elapsed_time(e1) / iters)
     dl.sets, dl.i = saved, 0
     dl.warm_ms = sorted(warm)[1]
+    dl.round_ms = (min(rounds), max(rounds))
     return sorted(rounds)[2]
 
 
@@ -214,8 +268,24 @@ def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
     t = ms * 1e-3
     t_hbm = work["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_valu = work["nz_flops"] / (FP32_VECTOR_PEAK_TF * 1e12)
+    # what the plan really issues: a kernel that tests groups of g elements multiplies every element of a
+    # group that holds a nonzero (independent zeros: a share z^g of the groups is skipped); the forms without
+    # any test (geometry names ending in d, "dense") issue everything - the dense fallback on the matrix pipe
+    g = SKIP_GRANULE.get(dl.variant, 1)
+    geom = dl.plan.split("/")[1] if "/" in dl.plan else ""
+    dense_form = dl.variant in MFMA_VARIANTS and (geom == "dense" or (geom.endswith("d") and geom != "kept"))
+    z = work["zero_ratio"]
+    skipped = 0.0 if dense_form else (z if g == 1 else z ** g)
+    issued = work["dense_flops"] * (1.0 - skipped) if g > 1 or dense_form else work["nz_flops"]
+    rounds = getattr(dl, "round_ms", (float("nan"), float("nan")))
     return {
         "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "plan": dl.plan, "ms": round(ms, 5),
+        "ms_min_max_of_5_rounds": [round(rounds[0], 5), round(rounds[1], 5)],
+        "pipe": "mfma" if dl.variant in MFMA_VARIANTS else "valu",
+        "dense_fallback": dense_form, "skip_granule_elements": g,
+        "granules_skipped_est": round(skipped, 4),
+        "issued_gflops_est": round(issued / t / 1e9, 1),
+        "tune_wall_s": round(getattr(dl, "tune_wall_s", 0.0), 3),
         "single_launch_ms": round(getattr(dl, "single_launch_ms", float("nan")), 5),
         "warm_ms": round(getattr(dl, "warm_ms", float("nan")), 5),
         "zero_ratio": round(work["zero_ratio"], 4),
@@ -224,7 +294,8 @@ def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
         "alg_GBps": round(work["alg_bytes"] / t / 1e9, 1),
         "hbm_frac": round(work["alg_bytes"] / t / 1e9 / HBM_PEAK_GBS, 4),
         "valu_frac": round(work["nz_flops"] / t / 1e12 / FP32_VECTOR_PEAK_TF, 4),
-        "bound": "hbm" if t_hbm >= t_valu else "alu",
+        "frac_of_unpacked_fp32_peak": round(work["nz_flops"] / t / 1e12 / FP32_UNPACKED_PEAK_TF, 4),
+        "bound": "hbm" if t_hbm >= t_valu else ("mfma" if dl.variant in MFMA_VARIANTS else "alu"),
         "bound_frac": round(max(t_hbm, t_valu) / t, 4),
     }
 
@@ -234,8 +305,26 @@ def copies_for(work_list) -> int:
     return int(max(2, min(16, -(-CACHE_BYTES // int(per_set)))))
 
 
+def cpu_baseline_one_thread(config_index: int) -> dict:
+    """The dense oracle held to one thread, on the config's last layer at batch 1."""
+    import oracle
+    cfg = workloads.CONFIGS[config_index]
+    li = len(cfg["layers"]) - 1
+    layer, x, w = workloads.make_layer_inputs(config_index, li, 1)
+    with oracle.one_thread():
+        t0 = time.perf_counter()
+        if layer.pool:
+            oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+        else:
+            oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
+        secs = time.perf_counter() - t0
+    flops = 2.0 * layer.K * layer.OH * layer.OW * layer.Cg * layer.R * layer.S
+    return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)", "cores": 1,
+            "kind": "oracle", "sample": f"{layer.name} at batch 1, {secs:.2f} s"}
+
+
 def cpu_baseline(config_index: int, batch: int = 2) -> dict:
-    """The oracle as it stands, on the host cores, on the same layer set at a small batch."""
+    """The oracle as it stands, on the host cores, on the same layer set at the benchmark's batch."""
     import oracle
     cfg = workloads.CONFIGS[config_index]
     flops, secs = 0.0, 0.0
@@ -289,6 +378,19 @@ def run_headline(args) -> None:
     copies = copies_for(works)
     dls = [DeviceLayer(layer, N, x, w, copies) for layer, x, w in host]
     torch.cuda.synchronize()
+    # parity first, on the buffers and with the plans that are timed below
+    parity = {"checked": 0, "failed": 0, "worst_ratio": 0.0, "tolerance": "1e-4 * sum|x*w| per element",
+              "against": "CPU oracle (fp64) at sampled outputs: random points + tile and filter-block boundaries"}
+    if not args.no_parity:
+        for li, dl in enumerate(dls):
+            r = dl.parity(4242 + li)
+            parity["checked"] += r["checked"]
+            parity["failed"] += r["failed"]
+            parity["worst_ratio"] = max(parity["worst_ratio"], r["worst_ratio"])
+        if parity["failed"]:
+            print(json.dumps({"error": "parity check failed before timing", "parity": parity,
+                              "plans": [dl.plan for dl in dls]}), flush=True)
+            sys.exit(3)
 
     def step():
         for dl in dls:
@@ -307,7 +409,7 @@ def run_headline(args) -> None:
     # per-kernel durations, events on the launch stream
     recs = []
     for dl, wk in zip(dls, works):
-        ms = time_layer(dl, max(20, args.steps), 5)
+        ms = time_layer(dl, max(200, args.steps), 20)
         recs.append(layer_record(dl, wk, ms))
     dom = max(range(len(recs)), key=lambda i: recs[i]["ms"])
     r, wk = recs[dom], works[dom]
@@ -326,8 +428,11 @@ def run_headline(args) -> None:
             roof = {"bound": "alu", "achieved": round(ach, 2), "peak": FP32_VECTOR_PEAK_TF, "unit": "TFLOP/s",
                     "frac": round(ach / FP32_VECTOR_PEAK_TF, 4), "traffic": None,
                     "frac_of_unpacked_fp32_peak": round(ach / FP32_UNPACKED_PEAK_TF, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC.get((r["variant"], r["layer"], N))
-    roof["kernel"] = f"{r['variant']} on {r['layer']} N={N}"
+    traffic = MEASURED_TRAFFIC.get((r["plan"], r["layer"], N))
+    roof["traffic"] = traffic[0] if traffic else None
+    roof["traffic_source"] = traffic[1] if traffic else "no counter run of this plan in profiles/"
+    roof["kernel"] = f"{r['plan']} on {r['layer']} N={N}"
+    roof["dense_fallback"] = r["dense_fallback"]
     roof["kernel_ms"] = r["ms"]
     roof["alg_bytes_per_launch"] = wk["alg_bytes"]
     roof["nonzero_flops_per_launch"] = wk["nz_flops"]
@@ -341,14 +446,19 @@ def run_headline(args) -> None:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}-shaped layer set ({', '.join(l.name for l in cfg['layers'])}), "
-                               f"batch {N}, conv+ReLU / fused conv+ReLU+2x2 max-pool",
-                   "batch": N, "buffer_copies_rotated": copies},
+                               f"batch {N}; per layer: " + "; ".join(
+                                   f"{r['layer']}: {'conv+ReLU+max-pool' if l.pool else 'conv+ReLU'} as {r['plan']}"
+                                   for r, (l, _, _) in zip(recs, host)),
+                   "batch": N, "buffer_copies_rotated": copies,
+                   "tune_wall_s": round(sum(dl.tune_wall_s for dl in dls), 2)},
         "layers": recs,
+        "parity": parity,
         "roofline": roof,
         "paper_context": paper_context(),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(ci)
+        out["cpu_baseline"] = cpu_baseline(ci, N)
+        out["cpu_baseline_one_thread"] = cpu_baseline_one_thread(ci)
         out["cpu_sparse_oracle"] = cpu_sparse_baseline(ci)
     print(json.dumps(out), flush=True)
 
@@ -615,6 +725,52 @@ def run_chain(args) -> None:
                       "output_zero_ratio": round(float((cur == 0).float().mean()), 4)}), flush=True)
 
 
+MICRO_MODES = [
+    (0, "fma", "8 independent v_fmac_f32 with a scalar operand", 8),
+    (1, "salu_dep", "8 dependent s_add_u32", 8),
+    (2, "test_not_taken", "s_bitcmp1 + s_cbranch_scc1, not taken", 1),
+    (3, "test_taken", "s_bitcmp1 + s_cbranch_scc1, taken to the next instruction", 1),
+    (4, "skip5_not_taken", "test + branch not taken + the 5 v_fmac it guards", 1),
+    (5, "skip5_taken", "test + branch taken over 5 v_fmac", 1),
+    (6, "setpc", "s_getpc + s_add + s_addc + s_setpc to the next instruction", 1),
+    (7, "readlane_fma5", "v_readlane + s_nop 1 + 5 v_fmac on the broadcast value", 1),
+    (8, "far_taken", "branch ~1.5 KB out of line, 5 v_fmac there, branch back", 1),
+    (9, "ff1_setpc", "s_ff1 + s_bitset0 + s_lshl + s_getpc + s_add + s_addc + s_setpc", 1),
+]
+
+
+def run_micro(args) -> None:
+    """Issue-rate microbenchmarks (libsconv_micro.so): clocks per pattern for one wavefront and per
+    SIMD at 1, 2, 4 and 8 resident wavefronts per SIMD.  Clocks are event time x 2.4 GHz (the nominal
+    clock; the fma row shows what the chip really holds: 4 clocks per v_fmac is the hardware's rate)."""
+    import ctypes
+    import torch
+    from paper_1909_09927_amd import build as hip_build
+    if not os.path.exists(hip_build.MICRO_LIB):
+        sys.exit("libsconv_micro.so is not built; run python -m paper_1909_09927_amd.build")
+    lib = ctypes.CDLL(hip_build.MICRO_LIB)
+    lib.sconv_micro_launch.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.sconv_micro_launch.restype = ctypes.c_int
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.empty(cus * 8 * 256, dtype=torch.float32, device="cuda")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    iters = 2000
+    for mode, name, what, per_repeat in MICRO_MODES:
+        rec = {"micro": name, "pattern": what, "instructions_counted_per_repeat": per_repeat}
+        for w in (1, 2, 4, 8):
+            blocks = cus * w
+
+            def go():
+                rc = lib.sconv_micro_launch(mode, iters, blocks, out.data_ptr(), stream)
+                if rc:
+                    sys.exit(f"sconv_micro_launch({name}) failed: {rc}")
+            ms = _time(go, 5, 2)
+            clocks = ms * 1e-3 * 2.4e9 / (iters * 64 * per_repeat)
+            rec[f"clocks_per_wavefront_at_{w}_per_simd"] = round(clocks, 2)
+            rec[f"clocks_per_simd_at_{w}_per_simd"] = round(clocks / w, 2)
+        print(json.dumps(rec), flush=True)
+
+
 def run_copy_calibration(args) -> None:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -630,8 +786,8 @@ def run_copy_calibration(args) -> None:
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="vgg19", choices=[c["name"] for c in workloads.CONFIGS])
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--table", action="store_true")
@@ -646,8 +802,12 @@ def main() -> None:
     ap.add_argument("--graph", action="store_true",
                     help="one step of --config at --batch (default: its smallest) eagerly and as a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true",
+                    help="skip the sampled comparison with the CPU oracle that precedes the timed region")
     ap.add_argument("--no-tune", action="store_true",
                     help="skip sconv_tune at set-up: static dispatch rules and cost models only")
+    ap.add_argument("--micro", action="store_true",
+                    help="issue-rate microbenchmarks: vector FMAs, scalar tests, branches, computed jumps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a 1 GiB device copy (scales the HBM traffic counters)")
     ap.add_argument("--layer", default="", help="CONFIG:INDEX, time that layer alone")
@@ -670,6 +830,8 @@ def main() -> None:
         sys.exit("libsconv.so is not built; run python -m paper_1909_09927_amd.build")
     if args.copy_calibration:
         run_copy_calibration(args)
+    elif args.micro:
+        run_micro(args)
     elif args.shape:
         run_shape(args)
     elif args.layer:

@@ -65,6 +65,8 @@ def _load():
         lib.oracle_maxpool.restype = None
         lib.oracle_conv_pool.argtypes = [P(Shape), P(f32), P(f32), P(f64), P(f64), P(f64), P(f64)]
         lib.oracle_conv_pool.restype = None
+        lib.oracle_set_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -209,6 +211,18 @@ def sparse_op_counts(count: np.ndarray) -> Tuple[int, int]:
     """Section 5.4: one multiplication per stored nonzero, one addition fewer per non-empty window."""
     c = np.maximum(np.asarray(count, np.int64), 0)
     return int(c.sum()), int(np.maximum(c - 1, 0).sum())
+
+
+class one_thread:
+    """Context manager: the OpenMP loop of oracle_conv runs on one thread inside (timing aid)."""
+
+    def __enter__(self):
+        self.before = _load().oracle_set_threads(1)
+        return self
+
+    def __exit__(self, *exc):
+        _load().oracle_set_threads(self.before)
+        return False
 
 
 def threads():

@@ -29,6 +29,7 @@
  *   - zero padding contributes zeros, which are never emitted;
  *   - sizes that do not divide are floored.
  */
+#include <omp.h>
 #include <math.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -47,6 +48,15 @@ typedef struct {
 static int conv_out(int i, int k, int pad, int cs) { return (i + 2 * pad - k) / cs + 1; }
 /* Pooled size: windows that do not fit are dropped. */
 static int pool_out(int o, int p, int ps) { return o < p ? 0 : (o - p) / ps + 1; }
+
+/* Number of threads the OpenMP loop of oracle_conv may use from now on (timing aid: the benchmark
+ * times the oracle on all host cores and on one); returns the previous limit.  No arithmetic here. */
+int oracle_set_threads(int n)
+{
+    const int before = omp_get_max_threads();
+    if (n > 0) omp_set_num_threads(n);
+    return before;
+}
 
 void oracle_output_dims(const oracle_shape_t* s, int32_t* OH, int32_t* OW, int32_t* PH, int32_t* PW)
 {

@@ -9,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsconv.so")
+MICRO_SRC = os.path.join(CSRC, "micro", "sconv_micro.hip")
+MICRO_LIB = os.path.join(HERE, "libsconv_micro.so")   # issue-rate microbenchmarks (bench.py --micro)
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
@@ -25,7 +27,9 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
+    if not os.path.exists(MICRO_LIB):
+        return True
+    deps = sources() + [MICRO_SRC] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -46,7 +50,18 @@ def build(force: bool = True, jobs: int = 8) -> str:
             _drain(procs)
     _drain(procs)
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    build_micro()
     return LIB
+
+
+def build_micro() -> str:
+    """The microbenchmark library: one source file, its own shared object."""
+    pr = subprocess.run([HIPCC, *FLAGS, "-shared", MICRO_SRC, "-o", MICRO_LIB],
+                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    msgs = [l for l in pr.stdout.splitlines() if "packed-fp32-ops" not in l and l.strip()]
+    if pr.returncode != 0:
+        raise RuntimeError("hipcc failed for the microbenchmarks:\n" + "\n".join(msgs))
+    return MICRO_LIB
 
 
 def _drain(procs):

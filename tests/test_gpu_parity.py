@@ -167,50 +167,148 @@ def _full_size_cases():
     return out
 
 
+def _run_layer(layer, xd, wd, **kw):
+    if layer.pool:
+        return sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups, **kw)
+    return sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True, **kw)
+
+
 @pytest.mark.parametrize("ci,li,N", _full_size_cases())
 def test_benchmark_layers_full_batch_sampled(device, ci, li, N):
-    """Every benchmark layer at its largest batch, in the launch configuration bench.py times:
-    sampled outputs against the oracle evaluated point by point, plus properties that hold for the
-    whole tensor (ReLU range, all-zero images give zero, same result when called twice)."""
-    import oracle
-    from parity import TOL
+    """Every benchmark layer at its largest batch with the plan the static rules give it (what
+    `bench.py --no-tune` times): sampled outputs - random points plus tile and filter-block boundaries -
+    against the oracle evaluated point by point, plus properties that hold for the whole tensor (ReLU
+    range, all-zero images give zero, same result when called twice)."""
+    import bench
     layer, x, w = workloads.make_layer_inputs(ci, li, N)
     x[N - 1] = 0                                   # one all-zero image: its outputs must be exactly 0
     xd, wd = to_dev(x), to_dev(w)
-    rng = np.random.default_rng(1000 * ci + li)
-    if layer.pool:
-        y = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups)
-        y2 = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups)
-    else:
-        y = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
-        y2 = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True)
+    y = _run_layer(layer, xd, wd)
+    y2 = _run_layer(layer, xd, wd)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
     got = y.cpu().numpy()
     assert (got >= 0).all() and np.isfinite(got).all()
     assert not got[N - 1].any()
-    npts = 4000
-    pts = np.stack([rng.integers(0, d, size=npts) for d in got.shape], axis=1)
-    # corners and edges of the map and the last filter are always among the samples
-    pts[:8, 2] = [0, 0, got.shape[2] - 1, got.shape[2] - 1, 0, got.shape[2] - 1, 1, 0]
-    pts[:8, 3] = [0, got.shape[3] - 1, 0, got.shape[3] - 1, 1, 1, 0, 0]
-    pts[:8, 1] = got.shape[1] - 1
-    if layer.pool:
-        ph, pw, ps = layer.pool
-        ref = np.zeros(npts)
-        scale = np.zeros(npts)
-        for py in range(ph):
-            for px in range(pw):
-                q = pts.copy()
-                q[:, 2] = pts[:, 2] * ps + py
-                q[:, 3] = pts[:, 3] * ps + px
-                v, a = oracle.conv_at(x, w, q, layer.stride, layer.pad, layer.groups, relu=True)
-                ref = np.maximum(ref, v)
-                scale = np.maximum(scale, a)
-    else:
-        ref, scale = oracle.conv_at(x, w, pts, layer.stride, layer.pad, layer.groups, relu=True)
-    err = np.abs(got[tuple(pts.T)].astype(np.float64) - ref)
-    assert (err <= TOL * scale).all(), f"worst ratio {np.max(err / np.maximum(scale, 1e-300)):.3e}"
+    r = bench.sampled_check(layer, x, w, got, 1000 * ci + li)
+    assert r["checked"] >= 4000 and r["failed"] == 0, r
+
+
+_FLUSH = None
+
+
+@pytest.mark.parametrize("ci,li,N", _full_size_cases())
+def test_benchmark_layers_full_batch_tuned_plan_sampled(device, ci, li, N):
+    """The launch configuration the default `bench.py` run times: workspace lent, caches evicted through a
+    flush buffer while sconv_tune ranks every variant and decomposition, then the remembered plan - whatever
+    it is - on the same sampled comparison with the oracle (and the whole-tensor properties)."""
+    import bench
+    global _FLUSH
+    if _FLUSH is None:
+        _FLUSH = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    layer, x, w = workloads.make_layer_inputs(ci, li, N)
+    xd, wd = to_dev(x), to_dev(w)
+    try:
+        ms, plan = sconv.sconv_tune(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=_FLUSH)
+        assert ms > 0 and plan
+        y = _run_layer(layer, xd, wd)
+        y2 = _run_layer(layer, xd, wd)
+        torch.cuda.synchronize()
+    finally:
+        sconv.sconv_tune_reset()
+    assert torch.equal(y, y2), plan
+    got = y.cpu().numpy()
+    assert (got >= 0).all() and np.isfinite(got).all()
+    r = bench.sampled_check(layer, x, w, got, 2000 * ci + li)
+    assert r["failed"] == 0, (plan, r)
+
+
+# Pooled 3x3 layers with several staged chunks per channel loop and several channel slices: the one-kernel
+# fused tiles (no workspace: nothing can be split), the same with a workspace, and every pooled geometry
+# of both element-stationary kernels pinned.
+POOLED_DEEP = [
+    (2, 256, 14, 14, 128, 3, 3, 1, 1, 1, (2, 2, 2)),     # 16 chunks of 16 channels, two filter blocks
+    (1, 96, 12, 20, 64, 3, 3, 1, 1, 1, (2, 2, 2)),       # 4x6 tiles with halo, ragged tile columns
+    (3, 64, 14, 14, 200, 3, 3, 1, 1, 2, (2, 2, 2)),      # grouped, ragged filter block
+]
+
+
+@pytest.mark.parametrize("ws", ["lent", "none", "own"])
+@pytest.mark.parametrize("shp", POOLED_DEEP)
+def test_fused_pooling_with_and_without_a_workspace(device, shp, ws):
+    import oracle
+    layer, x, w = _mk(310, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    kw = {}
+    if ws == "none":
+        kw["ws"] = None
+    elif ws == "own":
+        kw["ws"] = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    y = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups, **kw)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+    assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
+@pytest.mark.parametrize("geom,split", [("p4x14k1", "16,16"), ("p4x14k1", "8,2"), ("p4x14k2", "8,4"), ("p4x6k1", "16,8"),
+                                        ("p4x6k2", "8,8"), ("p4x14k1t", "16,16"), ("p4x14k1t", "8,1"),
+                                        ("p4x6k1t", "16,4"), ("p4x6k2t", "8,8"), ("p2x14k2t", "16,16"),
+                                        ("p2x14k2t", "8,2")])
+@pytest.mark.parametrize("shp", POOLED_DEEP)
+def test_pooled_tile_geometries_of_the_element_stationary_kernels(device, monkeypatch, shp, geom, split):
+    """One kernel computes convolution, ReLU and pooling (no split: the pinned decomposition has one
+    workgroup per tile), with channel loops of several chunks and up to 16 channel slices."""
+    import oracle
+    if "x14" in geom and shp[3] != 14:
+        pytest.skip("tile spans a 14-wide map")
+    if "k2" in geom and shp[4] // shp[9] <= 64:
+        pytest.skip("two filters per lane need more than 64 filters per group")
+    monkeypatch.setenv("SCONV_VARIANT", "tap")
+    monkeypatch.setenv("SCONV_TAP_GEOM", geom)
+    monkeypatch.setenv("SCONV_TAP_SPLIT", split)
+    layer, x, w = _mk(311, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    y = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+    assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
+TAPT = [
+    (2, 64, 14, 14, 96, 3, 3, 1, 1, 1, None),          # ragged filter block
+    (1, 128, 28, 28, 128, 3, 3, 1, 1, 1, None),        # 5x7 tiles, ragged last tile row
+    (3, 32, 7, 7, 64, 3, 3, 1, 1, 2, None),            # whole-map tile, grouped
+    (2, 48, 19, 23, 70, 3, 3, 2, 1, 1, None),          # stride 2, odd sizes
+    (1, 256, 7, 7, 256, 3, 3, 1, 1, 1, None),          # deep and small: split over workgroups
+]
+
+
+@pytest.mark.parametrize("split", ["8,1", "8,8", "16,4", "16,16", "8,2,2", "16,4,4"])
+@pytest.mark.parametrize("shp", TAPT)
+def test_transposed_filter_kernel(device, monkeypatch, shp, split):
+    """The element-stationary kernel that reads a transposed copy of the filters (no LDS staging, no
+    barrier in the channel loop): every plain geometry that fits the shape, pinned decompositions with
+    and without a split across workgroups, ReLU on and off, integer inputs bit for bit."""
+    stride = shp[7]
+    geoms = ["s2-3x4k1t", "s2-3x4k2t"] if stride == 2 else ["5x7k1t", "5x7k2t"] + (["7x7k1t", "7x7k2t"] if shp[2] == 7 else [])
+    monkeypatch.setenv("SCONV_VARIANT", "tap")
+    monkeypatch.setenv("SCONV_TAP_SPLIT", split)
+    ran = 0
+    for geom in geoms:
+        if "k2" in geom and shp[4] // shp[9] <= 64:
+            continue
+        parts = [int(t) for t in split.split(",")]
+        if (shp[1] // shp[9]) % (parts[1] * (parts[2] if len(parts) > 2 else 1)):
+            continue
+        monkeypatch.setenv("SCONV_TAP_GEOM", geom)
+        layer, x, w = _mk(320, shp)
+        check_forward(layer, x, w, relu=True)
+        check_forward(layer, x, w, relu=False)
+        layer, x, w = _mk(321, shp, integer=True)
+        check_forward(layer, x, w, relu=True, integer_exact=True)
+        ran += 1
+    if not ran:
+        pytest.skip("no geometry of this kernel fits the shape with this decomposition")
 
 
 @pytest.mark.parametrize("variant", ["rows", "tap", "quad", "wide", "gen", None])
