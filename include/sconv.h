@@ -251,7 +251,8 @@ int sconv_tune_reset(void);
  * geometry "-": the variant has one; "dense" and names ending in d: the form without zero tests), or
  * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor
  * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice);
- * "variant/model" for a descriptor that was not tuned.  Nothing is enqueued; asks the HIP runtime
+ * "variant/model" for a descriptor that was not tuned ("tap3x3/model:geometry/WxS[xP]": the vector
+ * kernel's cost model is asked what it would launch on the default stream, so a split shows).  Nothing is enqueued; asks the HIP runtime
  * for the current device, as sconv_variant_name does.
  */
 int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size);

@@ -709,10 +709,17 @@ extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, 
     int rc = fill_problem(desc, pooled != 0, &p);
     if (rc) return rc;
     std::lock_guard<std::mutex> lock(g_lock);
-    if (const Tuned* t = tuned_for(p, pooled != 0))
+    if (const Tuned* t = tuned_for(p, pooled != 0)) {
         snprintf(out, (size_t)out_size, "%s", t->name);
+        return SCONV_OK;
+    }
+    const Variant v = choose(p, pooled != 0, split_workspace_lent(nullptr, true));
+    char detail[40];
+    split_scratch_select(nullptr);   // the default stream's workspace, as for a launch there
+    if (v == V_TAP && describe_tap(p, pooled != 0, nullptr, detail, sizeof(detail)))
+        snprintf(out, (size_t)out_size, "%s/model:%s", variant_name(v), detail);
     else
-        snprintf(out, (size_t)out_size, "%s/model", variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true))));
+        snprintf(out, (size_t)out_size, "%s/model", variant_name(v));
     return SCONV_OK;
 }
 

@@ -40,6 +40,9 @@ bool tap_supported(const Problem& p, bool pooled);
 int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
                hipStream_t stream);
 
+// "geometry/WxS[xP]" of the plan launch_tap would take on this stream (after split_scratch_select).
+bool describe_tap(const Problem& p, bool pooled, hipStream_t stream, char* out, size_t out_size);
+
 // Matrix-core variant of the same kernel (3x3 / stride 1 / pad 1): four inputs per instruction.
 bool quad_supported(const Problem& p, bool pooled);
 int launch_quad(const Problem& p, bool pooled, const float* x, const float* w, float* y,

@@ -251,7 +251,9 @@ Plan plan_geom(const Problem& p, int split)
     const int nss = pin_nss ? pin_nss : 1;
     if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
     if (pin_nss == 1 && split == 2) return best;
-    if (!pin_nss && split == 2 && !small && !mid) return best;
+    // (a fused call takes plain tiles plus the pooling second kernel only when the launch is too small to
+    // fill the chip otherwise: the convolution tensor of a larger one stays on chip, Section 6.4)
+    if (!pin_nss && split == 2 && !small) return best;
     // measured on mid-sized launches: one filter per lane (twice the workgroups) with the channels
     // split beats two filters per lane, which the pricing below would prefer
     if (mid && split >= 1 && G::KPL > 1 && !pin_nss && !pin_nwv && !pinned_geom("SCONV_TAP_GEOM")) return best;
@@ -333,7 +335,7 @@ Plan plan_geom(const Problem& p, int split)
         best.nss = best.cfg.NSS = want;
         if (want > 1) best.cost = best.cost / want + 9000.0;
     }
-    if (!pin_nss && split >= 1 && mid && best.cost >= 0.0) {
+    if (!pin_nss && split == 1 && mid && best.cost >= 0.0) {
         // mid-sized launches (up to 768 tile-workgroups): up to 768 workgroups (a round and a half of two
         // per compute unit) of four chunks or more, four ways at most (512 channels @14x14: batch 4 57 -> 46 us, batch 8
         // 87 -> 64, with fused pooling 71 -> 65; @7x7: batch 16 56 -> 43, batch 32 80 -> 72)
@@ -347,8 +349,6 @@ Plan plan_geom(const Problem& p, int split)
         if (want > 1 && split_fits(want)) {
             best.nss = best.cfg.NSS = want;
             best.cost = best.cost / want + 9000.0;
-        } else if (split == 2) {
-            return Plan();    // a pooled layer stays on its pooled tiles
         }
     }
     return best;
@@ -482,15 +482,39 @@ const char* const* tap_geoms()
 
 bool tap_supported(const Problem& p, bool pooled) { return shape_ok(p, pooled); }
 
-int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
-               hipStream_t stream)
+namespace {
+// The candidate and decomposition a launch on `stream` would get (the dispatcher has selected the
+// stream's workspace); null when no tile plan applies.
+const Candidate* select_tap(const Problem& p, bool pooled, hipStream_t stream, Plan* plan_out)
 {
-    if (!shape_ok(p, pooled)) return SCONV_EUNSUPPORTED;
+    if (!shape_ok(p, pooled)) return nullptr;
     const char* pin = pinned_geom("SCONV_TAP_GEOM");   // tuning aid: candidate name
     const Candidate* best = nullptr;
     Plan best_plan;
     // a channel split across workgroups needs a workspace lent for the stream
     const bool can_split = split_scratch_possible(stream);
+    // Large launches with a workspace that holds a transposed copy of the filters: the kernel without
+    // LDS staging (sconv_tapt.hip) measures 5-13 % faster on every launch of 512 or more tile-workgroups
+    // with 128 or more channels per group tried (512 @28x28 batch 8: 231 -> 210 us; 512 @14x14 batch 32:
+    // 190 -> 168; 256 @14x14 batch 32: 63 -> 55; 896 in 7 groups @14x14 batch 32: 130 -> 126), and its
+    // pooled tiles beat both the staged pooled tiles and the split plain tiles (512 @14x14 + pooling at
+    // batch 8: 61 against 71 and 65 us).
+    int dn = 0, dc = 0, ds = 0;
+    pinned_split("SCONV_TAP_SPLIT", &dn, &dc, &ds);
+    if (!pin && !dn && can_split && p.stride == 1 && p.Cg >= 128 && (p.H > 7 || p.W > 7)) {
+        const long long tile_wgs = (long long)((p.OH + 4) / 5) * ((p.OW + 6) / 7) * ((p.Kg + 63) / 64) * p.N * p.G;
+        const char* want = nullptr;
+        if (tile_wgs >= 512)
+            want = !pooled ? "5x7k1t" : (p.W == 14 ? (p.Kg >= 128 ? "p2x14k2t" : "p4x14k1t") : "p4x6k1t");
+        for (const Candidate& c : kCandidates) {
+            if (!want || strcmp(want, c.name) != 0) continue;
+            const Plan pl = c.plan(p, 0);
+            if (pl.cost >= 0.0) {
+                best = &c;
+                best_plan = pl;
+            }
+        }
+    }
     // A pooled layer: first the plain tiles with the split (the second kernel pools), which the
     // model offers for small launches only; the pooled tiles when none applies.
     for (int pass = pooled && can_split ? 0 : 1; pass < 2 && !best; ++pass) {
@@ -509,11 +533,33 @@ int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, fl
             }
         }
     }
+    if (best) *plan_out = best_plan;
+    return best;
+}
+}  // namespace
+
+int launch_tap(const Problem& p, bool pooled, const float* x, const float* w, float* y,
+               hipStream_t stream)
+{
+    Plan best_plan;
+    const Candidate* best = select_tap(p, pooled, stream, &best_plan);
     if (!best) return SCONV_EUNSUPPORTED;
     if (env_value("SCONV_TRACE_PLAN"))
         fprintf(stderr, "sconv: tap3x3 %s nwv=%d ncs=%d nt=%d nss=%d cost=%.0f\n", best->name, best_plan.nwv,
                 best_plan.cfg.NCS, best_plan.cfg.NT, best_plan.nss, best_plan.cost);
     return best->launch(best_plan, p, pooled, x, w, y, stream);
+}
+
+bool describe_tap(const Problem& p, bool pooled, hipStream_t stream, char* out, size_t out_size)
+{
+    Plan pl;
+    const Candidate* c = select_tap(p, pooled, stream, &pl);
+    if (!c) return false;
+    if (pl.nss > 1)
+        snprintf(out, out_size, "%s/%dx%dx%d", c->name, pl.nwv, pl.cfg.NCS, pl.nss);
+    else
+        snprintf(out, out_size, "%s/%dx%d", c->name, pl.nwv, pl.cfg.NCS);
+    return true;
 }
 
 }  // namespace sconv

@@ -180,8 +180,8 @@ size_t wt_bytes(const Problem& p, int KB)
 // Decomposition of one launch of the transposed-filter kernel: wavefronts per workgroup nwv = NT tiles
 // x NCS channel slices (slices only add up through LDS at the end), NSS workgroups per tile along the
 // channels.  split: 0 = not allowed, 1 = allowed, 2 = required (a plain tile serving a pooled call).
-// Pinned decompositions are taken as they are; otherwise enough channel slices for about six
-// wavefronts per SIMD, at least 16 channels each.
+// Pinned decompositions are taken as they are; otherwise enough channel slices to fill all eight
+// wavefront slots of every SIMD, at least 16 channels each.
 template <class G>
 Plan plan_tapt(const Problem& p, int split)
 {
@@ -201,7 +201,7 @@ Plan plan_tapt(const Problem& p, int split)
     if (!pin_nwv) {
         nwv = G::MAXW == 16 ? 16 : 8;
         ncs = 1;
-        while (ncs < nwv && tile_waves * ncs < 6 * 1024 && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
+        while (ncs < nwv && tile_waves * ncs < 8 * 1024 && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
         if (split == 2) nss = 2;
         // (small launches: the channels of a tile over several workgroups as well)
         while (split >= 1 && nss < 16 && tile_waves * ncs * nss < 2 * 1024 && p.Cg / (ncs * nss * 2) >= 16) nss *= 2;

@@ -173,7 +173,7 @@ def test_tuning_calls_validate_on_the_host():
     assert L.sconv_tune(ctypes.byref(bad), 0, p, p, p, None, 0, None, None) == sconv.SCONV_EINVAL
     assert L.sconv_tune(ctypes.byref(d), 1, p, p, p, None, 0, None, None) == sconv.SCONV_EINVAL   # no pooling fields
     assert L.sconv_tune_reset() == 0
-    assert sconv.sconv_plan_name(d) == "tap3x3/model"
+    assert sconv.sconv_plan_name(d).startswith("tap3x3/model")
     assert sconv.sconv_plan_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)) == "quad3x3/model"
     buf = ctypes.create_string_buffer(4)
     assert L.sconv_plan_name(ctypes.byref(d), 0, buf, 4) == 0 and buf.value == b"tap"
