@@ -52,6 +52,7 @@ MEASURED_TRAFFIC = {
 SKIP_GRANULE = {"rows": 1, "tap3x3": 1, "quad3x3": 6, "quad1x1": 32, "wide3x3": 16, "gen": 16}
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
 TUNE = True                   # --no-tune: the static dispatch rules and cost models only
+HINT = False                  # --hint: no tuning; the density probe's zero ratio is given to the static rules
 CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
 
 
@@ -171,6 +172,12 @@ class DeviceLayer:
         d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
         self.host = (x, w)
         self.tune_wall_s = 0.0
+        if HINT:
+            # set-up: one probe of the input (two small kernels, up to 4 Mi elements) and the hint
+            t0 = time.perf_counter()
+            z = sconv.zero_ratio_of(sconv.sconv_density(xd))
+            sconv.sconv_set_density_hint(d, bool(layer.pool), z)
+            self.tune_wall_s = time.perf_counter() - t0
         if TUNE:
             # set-up, outside every timed region: the library times its variants and decompositions on
             # this layer's operands and remembers the fastest for this descriptor
@@ -483,21 +490,25 @@ def run_table(args) -> None:
 
 
 def run_sweep(args) -> None:
-    """Zero-ratio sweep on the RegNetX 896-channel grouped layer (batch from --batch, default 32)."""
+    """Zero-ratio sweep 0.00-0.95: on the RegNetX 896-channel grouped layer at batch 32 by default, or on
+    --layer CONFIG:INDEX at --batch (default: the config's largest)."""
     import torch
-    ci = 4
-    base = workloads.CONFIGS[ci]["layers"][0]
-    N = args.batch or 32
+    ci, li = 4, 0
+    if args.layer:
+        name, li = args.layer.split(":")
+        ci, li = [c["name"] for c in workloads.CONFIGS].index(name), int(li)
+    base = workloads.CONFIGS[ci]["layers"][li]
+    N = args.batch or max(workloads.CONFIGS[ci]["batches"])
     for z in workloads.SWEEP_ZERO_RATIOS:
         layer = base.with_zero_ratio(z)
         if args.structure != "iid":
             layer = layer.with_structure(args.structure)
-        layer, x, w = workloads.make_layer_inputs(ci, 0, N, layer)
+        layer, x, w = workloads.make_layer_inputs(ci, li, N, layer)
         wk = layer_work(layer, N, x)
         dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
         ms = time_layer(dl, args.steps, args.warmup)
         rec = layer_record(dl, wk, ms)
-        rec["config"] = "regnetx16gf-sweep" + ("" if args.structure == "iid" else "-" + args.structure)
+        rec["config"] = workloads.CONFIGS[ci]["name"] + "-sweep" + ("" if args.structure == "iid" else "-" + args.structure)
         print(json.dumps(rec), flush=True)
         del dl
         torch.cuda.empty_cache()
@@ -806,6 +817,9 @@ def main() -> None:
                     help="skip the sampled comparison with the CPU oracle that precedes the timed region")
     ap.add_argument("--no-tune", action="store_true",
                     help="skip sconv_tune at set-up: static dispatch rules and cost models only")
+    ap.add_argument("--hint", action="store_true",
+                    help="no tuning: probe every layer's input once (sconv_density) and give the static rules "
+                         "its zero ratio (sconv_set_density_hint)")
     ap.add_argument("--micro", action="store_true",
                     help="issue-rate microbenchmarks: vector FMAs, scalar tests, branches, computed jumps")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -817,8 +831,9 @@ def main() -> None:
                     help="zero pattern of the input for --sweep / --layer: independent zeros, or dead "
                          "planes plus spatial patches at the same overall ratio")
     args = ap.parse_args()
-    global TUNE
-    TUNE = not args.no_tune and not os.environ.get("SCONV_VARIANT")
+    global TUNE, HINT
+    HINT = args.hint
+    TUNE = not args.no_tune and not args.hint and not os.environ.get("SCONV_VARIANT")
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part (images or filters would "
                  "simply be split across devices with no exchange); run with --gpus 1")
@@ -834,12 +849,12 @@ def main() -> None:
         run_micro(args)
     elif args.shape:
         run_shape(args)
+    elif args.sweep:
+        run_sweep(args)
     elif args.layer:
         run_layer(args)
     elif args.table:
         run_table(args)
-    elif args.sweep:
-        run_sweep(args)
     elif args.split:
         run_split(args)
     elif args.chain:

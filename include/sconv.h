@@ -242,7 +242,29 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
 int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
                float* y_dev, void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms);
 
-/* Forgets every tuned plan.  Host only. */
+/*
+ * Density probe and hint (the cheap alternative to sconv_tune).  The zero ratio of a feature map decides
+ * which kernel is fastest (Section 8.3 plots the method's time against it; the first layers of a network
+ * are far less sparse than the deep ones, Section 8.2), and the host cannot see it.
+ *   sconv_density: enqueues two small kernels on hip_stream that count, with the test of Algorithm 1's
+ *            scan (x != 0), the elements of x examined and those that are nonzero:
+ *            counts_dev[0] = examined, counts_dev[1] = nonzero (device, 2 x 64-bit, 8-byte aligned,
+ *            overwritten).  Every element is examined when the map has at most 4 Mi of them, else 4 Mi
+ *            in runs of 256 spread evenly over the tensor.  Does not synchronise; the caller reads the
+ *            counts after the stream has run (zero ratio = 1 - nonzero / examined).  A producer that knows
+ *            its output's zero ratio some other way needs no probe.
+ *   sconv_set_density_hint: remembers zero_ratio (0..1) for this descriptor and pooled flag in a
+ *            host-side table; later forward calls with an identical descriptor that sconv_tune has not
+ *            tuned choose their kernel variant with it: 3x3 / stride 1 / pad 1 launches that fill the
+ *            matrix kernels' tiles take the matrix kernels below 68 % zeros, the vector kernel
+ *            ("tap3x3") from 68 %, and "quad3x3" again from 92 % (crossovers of the zero-ratio sweeps on
+ *            independent zeros).  A negative ratio forgets the hint; sconv_tune_reset forgets all.
+ *            Host only; changes process state.
+ */
+int sconv_density(const sconv_desc_t* desc, const float* x_dev, unsigned long long* counts_dev, void* hip_stream);
+int sconv_set_density_hint(const sconv_desc_t* desc, int pooled, float zero_ratio);
+
+/* Forgets every tuned plan and every density hint.  Host only. */
 int sconv_tune_reset(void);
 
 /*

@@ -70,10 +70,13 @@ def lib() -> ctypes.CDLL:
         L.sconv_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sconv_pool_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sconv_forward_static.argtypes = [P(Desc), vp, vp, vp, vp]
+        L.sconv_density.argtypes = [P(Desc), vp, vp, vp]
+        L.sconv_set_density_hint.argtypes = [P(Desc), ctypes.c_int, ctypes.c_float]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
-                  "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static"):
+                  "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_density",
+                  "sconv_set_density_hint"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -159,6 +162,33 @@ def sconv_clear_workspaces() -> None:
 def sconv_env_refresh() -> None:
     """Makes the library read its SCONV_* tuning-aid environment variables again (it reads them once)."""
     lib().sconv_env_refresh()
+
+
+def sconv_density(x, counts=None):
+    """Enqueues the density probe on x (device, fp32, NCHW); returns the device tensor of two int64
+    counts (examined, nonzero).  Reading it (e.g. zero_ratio_of) synchronises; the call itself does not."""
+    import torch
+    _check_dev(x, torch.float32, "x")
+    N, C, H, W = x.shape
+    desc = make_desc(N, C, H, W, C, 1, 1)
+    if counts is None:
+        counts = torch.empty(2, dtype=torch.int64, device=x.device)
+    rc = lib().sconv_density(ctypes.byref(desc), x.data_ptr(), counts.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_density")
+    return counts
+
+
+def zero_ratio_of(counts) -> float:
+    """Zero ratio from the probe's counts (copies them to the host: waits for the probe)."""
+    seen, nonzero = (int(v) for v in counts.cpu())
+    return 1.0 - nonzero / max(seen, 1)
+
+
+def sconv_set_density_hint(desc: Desc, pooled: bool, zero_ratio: float) -> None:
+    rc = lib().sconv_set_density_hint(ctypes.byref(desc), 1 if pooled else 0, float(zero_ratio))
+    if rc:
+        raise SconvError(rc, "sconv_set_density_hint")
 
 
 def _ws_args(ws):

@@ -157,6 +157,8 @@ typedef std::array<int32_t, 15> TuneKey;   // the descriptor's fields and the po
 static std::mutex g_lock;                  // planning, enqueueing and the tuning cache
 static std::map<TuneKey, Tuned> g_tuned;
 
+static std::map<TuneKey, float> g_density;   // zero ratio the caller reported for a descriptor
+
 static TuneKey tune_key(const Problem& p, bool pooled)
 {
     return TuneKey{p.N, p.C, p.H, p.W, p.K, p.R, p.S, p.stride, p.pad, p.G,
@@ -164,6 +166,14 @@ static TuneKey tune_key(const Problem& p, bool pooled)
 }
 
 // The tuned entry for this problem, unless SCONV_VARIANT pins the variant.  Caller holds g_lock.
+// The zero ratio reported for this problem with sconv_set_density_hint; negative when none was.
+static float density_hint(const Problem& p, bool pooled)
+{
+    if (g_density.empty()) return -1.0f;
+    auto it = g_density.find(tune_key(p, pooled));
+    return it == g_density.end() ? -1.0f : it->second;
+}
+
 static const Tuned* tuned_for(const Problem& p, bool pooled)
 {
     if (env_value("SCONV_VARIANT")) return nullptr;
@@ -203,7 +213,15 @@ static bool small_quad_split(const Problem& p, bool pooled, PlanPin* pin)
 // The static rules.  have_ws: a workspace is lent (the split plans of the matrix kernel need one;
 // the vector and general kernels decide on their own).  When the choice comes with a fixed
 // decomposition, *static_pin receives it (geom[0] != 0).
-static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr)
+//
+// z: the map's zero ratio when the caller reported one (sconv_set_density_hint), negative when unknown.
+// Known, it moves 3x3 / stride 1 / pad 1 launches that fill the matrix kernels' tiles along the
+// crossovers measured on the zero-ratio sweeps (independent zeros; 896 channels in 7 groups @14x14 at
+// batch 32 and 256 channels @56x56 at batch 8): below 68 % zeros whole groups are almost never empty and
+// the matrix kernels run at their dense rate, which the vector kernel only matches from about 68 %;
+// from 92 % the 6-element granule of quad3x3 is empty often enough to lead again.
+static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr,
+                      float z = -1.0f)
 {
     if (static_pin) memset(static_pin, 0, sizeof(*static_pin));
     const char* pin = env_value("SCONV_VARIANT");
@@ -232,6 +250,20 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // Maps of 7x7 and below are one whole-map tile of the vector kernel (no halo, no ragged
         // tiles); it measures 1.4-1.8x faster there than either matrix kernel.
         if (p.H <= 7 && p.W <= 7 && tap_supported(p, pooled)) return V_TAP;
+        const long long quad_tiles_z = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
+                                       p.N * p.G;
+        if (z >= 0.0f && quad_tiles_z >= 400 && tap_supported(p, pooled)) {
+            if (z >= 0.92f && !(pooled && p.W <= 14)) return V_QUAD;
+            if (z >= 0.68f) return V_TAP;
+            // a denser map: the matrix kernels (the 16-row granule on maps up to 14 wide, else quad3x3 in
+            // its form without zero tests where that form applies: below 68 % independent zeros fewer than
+            // one group of six in ten is empty and the tests cost more than they save)
+            if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
+            if (!(pooled && p.W <= 14)) {
+                if (static_pin && p.W > 14) snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
+                return V_QUAD;
+            }
+        }
         // Maps up to 14 wide with 256 or more channels per group are the deep layers, whose zero
         // ratio the paper puts above 0.7 (Fig. 2): there per-element skipping on the vector pipe
         // measures 1.0-1.15x faster than the 6-element granule from 70 % zeros up (and 1.1x slower
@@ -302,12 +334,13 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
         if (rc != SCONV_EUNSUPPORTED) return rc;
     }
     PlanPin sp;
-    Variant v = choose(p, pooled, have_workspace(s), &sp);
+    const float z = density_hint(p, pooled);
+    Variant v = choose(p, pooled, have_workspace(s), &sp, z);
     int rc = SCONV_EUNSUPPORTED;
     if (sp.geom[0]) {
         rc = launch_variant(v, &sp, p, pooled, x, w, y, s);
         if (rc != SCONV_EUNSUPPORTED) return rc;
-        v = choose(p, pooled);      // e.g. the workspace is too small for this layer
+        v = choose(p, pooled, false, nullptr, z);      // e.g. the workspace is too small for this layer
     }
     if (v == V_PW) rc = launch_variant(V_PW, nullptr, p, pooled, x, w, y, s);
     if (v == V_GEN) {
@@ -408,7 +441,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     };
     // the static rules' own choice comes first: it stays unless something measures clearly faster
     PlanPin sp;
-    Variant v_static = choose(p, pooled, have_workspace(s), &sp);
+    Variant v_static = choose(p, pooled, have_workspace(s), &sp, density_hint(p, pooled));
     bool have_static = try_one(v_static, sp.geom[0] ? &sp : nullptr);
     if (!have_static && sp.geom[0]) {
         v_static = choose(p, pooled);
@@ -623,6 +656,31 @@ extern "C" int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev
     return run_with(p, false, x_dev, w_dev, y_dev, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_density(const sconv_desc_t* desc, const float* x_dev, unsigned long long* counts_dev,
+                             void* hip_stream)
+{
+    if (!x_dev || !counts_dev) return SCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(counts_dev) % 8) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    return launch_density_probe(p, x_dev, counts_dev, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_set_density_hint(const sconv_desc_t* desc, int pooled, float zero_ratio)
+{
+    Problem p;
+    int rc = fill_problem(desc, pooled != 0, &p);
+    if (rc) return rc;
+    if (zero_ratio != zero_ratio || zero_ratio > 1.0f) return SCONV_EINVAL;
+    std::lock_guard<std::mutex> lock(g_lock);
+    if (zero_ratio < 0.0f)
+        g_density.erase(tune_key(p, pooled != 0));
+    else
+        g_density[tune_key(p, pooled != 0)] = zero_ratio;
+    return SCONV_OK;
+}
+
 extern "C" int sconv_env_refresh(void)
 {
     std::lock_guard<std::mutex> lock(g_lock);
@@ -647,7 +705,7 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled != 0)) return variant_name(t->v);
-    return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true)));
+    return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, density_hint(p, pooled != 0)));
 }
 
 extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
@@ -699,6 +757,7 @@ extern "C" int sconv_tune_reset(void)
 {
     std::lock_guard<std::mutex> lock(g_lock);
     g_tuned.clear();
+    g_density.clear();
     return SCONV_OK;
 }
 
@@ -713,7 +772,7 @@ extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, 
         snprintf(out, (size_t)out_size, "%s", t->name);
         return SCONV_OK;
     }
-    const Variant v = choose(p, pooled != 0, split_workspace_lent(nullptr, true));
+    const Variant v = choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, density_hint(p, pooled != 0));
     char detail[40];
     split_scratch_select(nullptr);   // the default stream's workspace, as for a launch there
     if (v == V_TAP && describe_tap(p, pooled != 0, nullptr, detail, sizeof(detail)))

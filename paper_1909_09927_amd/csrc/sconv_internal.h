@@ -28,6 +28,9 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out);
 int launch_encode(const Problem& p, int fmt, const float* x, float* values, int32_t* index,
                   int32_t* count, hipStream_t stream);
 
+// Counts examined and nonzero elements of x into counts[0], counts[1] (device); at most 4 Mi elements.
+int launch_density_probe(const Problem& p, const float* x, unsigned long long* counts, hipStream_t stream);
+
 // ReLU + max pooling of a stored convolution tensor [N][K][OH][OW] -> [N][K][PH][PW].
 int launch_maxpool(const Problem& p, const float* conv, float* y, hipStream_t stream);
 

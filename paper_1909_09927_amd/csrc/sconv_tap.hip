@@ -504,7 +504,7 @@ const Candidate* select_tap(const Problem& p, bool pooled, hipStream_t stream, P
     if (!pin && !dn && can_split && p.stride == 1 && p.Cg >= 128 && (p.H > 7 || p.W > 7)) {
         const long long tile_wgs = (long long)((p.OH + 4) / 5) * ((p.OW + 6) / 7) * ((p.Kg + 63) / 64) * p.N * p.G;
         const char* want = nullptr;
-        if (tile_wgs >= 512)
+        if (tile_wgs >= (pooled ? 256 : 512))   // (pooled: measured from 384 up)
             want = !pooled ? "5x7k1t" : (p.W == 14 ? (p.Kg >= 128 ? "p2x14k2t" : "p4x14k1t") : "p4x6k1t");
         for (const Candidate& c : kCandidates) {
             if (!want || strcmp(want, c.name) != 0) continue;

@@ -180,8 +180,7 @@ size_t wt_bytes(const Problem& p, int KB)
 // Decomposition of one launch of the transposed-filter kernel: wavefronts per workgroup nwv = NT tiles
 // x NCS channel slices (slices only add up through LDS at the end), NSS workgroups per tile along the
 // channels.  split: 0 = not allowed, 1 = allowed, 2 = required (a plain tile serving a pooled call).
-// Pinned decompositions are taken as they are; otherwise enough channel slices to fill all eight
-// wavefront slots of every SIMD, at least 16 channels each.
+// Pinned decompositions are taken as they are; otherwise the rule inside.
 template <class G>
 Plan plan_tapt(const Problem& p, int split)
 {
@@ -199,9 +198,14 @@ Plan plan_tapt(const Problem& p, int split)
     const long long tile_waves = (long long)cfg.ntiles * kblocks * p.N * p.G;
     int nwv = pin_nwv, ncs = pin_ncs, nss = pin_nss ? pin_nss : 1;
     if (!pin_nwv) {
-        nwv = G::MAXW == 16 ? 16 : 8;
+        // Measured (sconv_tune's picks on 128- to 512-channel layers): eight channel slices whenever a slice
+        // keeps 16 channels - many short wavefronts even out the last round -, one tile per workgroup,
+        // two from 512 channels up; pooled tiles of 14-wide maps, few per image, sixteen slices.
         ncs = 1;
-        while (ncs < nwv && tile_waves * ncs < 8 * 1024 && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
+        const int want = (G::POOL && G::HW == 0) ? 16 : 8;
+        while (ncs < want && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
+        nwv = (p.Cg >= 512 || ncs == 16) && G::MAXW == 16 ? 16 : 8;
+        if (ncs > nwv) ncs = nwv;
         if (split == 2) nss = 2;
         // (small launches: the channels of a tile over several workgroups as well)
         while (split >= 1 && nss < 16 && tile_waves * ncs * nss < 2 * 1024 && p.Cg / (ncs * nss * 2) >= 16) nss *= 2;

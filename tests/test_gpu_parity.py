@@ -281,6 +281,45 @@ def test_pooled_tile_geometries_of_the_element_stationary_kernels(device, monkey
     assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
 
 
+def test_density_probe_counts_like_the_scan(device):
+    """sconv_density counts x != 0 exactly on maps it reads whole (negative zero is a zero, a denormal is
+    not), and within sampling error on larger ones."""
+    rng = np.random.default_rng(5)
+    x = np.where(rng.random((3, 17, 29, 31)) < 0.37, rng.standard_normal((3, 17, 29, 31)), 0.0).astype(np.float32)
+    x[0, 0, 0, :4] = [-0.0, 1e-42, 0.0, -3.0]
+    counts = sconv.sconv_density(to_dev(x)).cpu().numpy()
+    assert counts[0] == x.size and counts[1] == int((x != 0).sum())
+    big = np.where(rng.random((8, 256, 56, 56)) < 0.4, 1.0, 0.0).astype(np.float32)    # 6.4 Mi elements: sampled
+    c = sconv.sconv_density(to_dev(big)).cpu().numpy()
+    assert 3 << 20 <= c[0] <= 4 << 20
+    assert abs(c[1] / c[0] - (big != 0).mean()) < 2e-3
+
+
+@pytest.mark.parametrize("z_hint", [0.0, 0.5, 0.75, 0.95])
+@pytest.mark.parametrize("shp", [(16, 64, 28, 28, 128, 3, 3, 1, 1, 1, None), (32, 128, 14, 14, 128, 3, 3, 1, 1, 1, None),
+                                 (16, 64, 28, 28, 128, 3, 3, 1, 1, 1, (2, 2, 2))])
+def test_density_hint_moves_the_static_choice_and_keeps_parity(device, shp, z_hint):
+    """A reported zero ratio selects the matrix kernels (dense maps), the vector kernel (68-88 % zeros) or
+    quad3x3 (sparser still) for launches that fill the matrix tiles; whatever runs meets the oracle's bar."""
+    layer, x, w = _mk(330, shp, z=z_hint if z_hint < 1 else 0.95)
+    xd, wd = to_dev(x), to_dev(w)
+    d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+    pooled = layer.pool is not None
+    try:
+        sconv.sconv_set_density_hint(d, pooled, z_hint)
+        name = sconv.sconv_variant_name(d, pooled)
+        if 0.68 <= z_hint < 0.88:
+            assert name == "tap3x3"
+        elif not pooled:
+            assert name in ("quad3x3", "wide3x3")
+        if pooled:
+            check_pool_forward(layer, x, w)
+        else:
+            check_forward(layer, x, w, relu=True)
+    finally:
+        sconv.sconv_tune_reset()
+
+
 TAPT = [
     (2, 64, 14, 14, 96, 3, 3, 1, 1, 1, None),          # ragged filter block
     (1, 128, 28, 28, 128, 3, 3, 1, 1, 1, None),        # 5x7 tiles, ragged last tile row

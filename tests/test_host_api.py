@@ -241,6 +241,24 @@ def test_environment_is_read_once_and_on_request(monkeypatch):
     assert sconv.sconv_variant_name(d) == before
 
 
+def test_density_calls_validate_on_the_host():
+    L = sconv.lib()
+    d = sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1)
+    p = ctypes.c_void_p(4096)
+    assert L.sconv_density(ctypes.byref(d), None, p, None) == sconv.SCONV_EINVAL
+    assert L.sconv_density(ctypes.byref(d), p, None, None) == sconv.SCONV_EINVAL
+    assert L.sconv_density(ctypes.byref(d), p, ctypes.c_void_p(4100), None) == sconv.SCONV_EINVAL   # misaligned counts
+    assert L.sconv_set_density_hint(ctypes.byref(d), 0, 1.5) == sconv.SCONV_EINVAL
+    assert L.sconv_set_density_hint(ctypes.byref(d), 0, float("nan")) == sconv.SCONV_EINVAL
+    assert L.sconv_set_density_hint(ctypes.byref(d), 1, 0.5) == sconv.SCONV_EINVAL                  # no pooling fields
+    big = sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert sconv.sconv_variant_name(big) == "quad3x3"
+    assert L.sconv_set_density_hint(ctypes.byref(big), 0, 0.8) == sconv.SCONV_OK
+    assert sconv.sconv_variant_name(big) == "tap3x3"                     # the hint moved the static choice
+    assert L.sconv_set_density_hint(ctypes.byref(big), 0, -1.0) == sconv.SCONV_OK
+    assert sconv.sconv_variant_name(big) == "quad3x3"
+
+
 def test_binding_refuses_host_tensors():
     import torch
     x = torch.zeros(1, 2, 4, 4)
