@@ -65,6 +65,8 @@ def _load():
         lib.oracle_maxpool.restype = None
         lib.oracle_conv_pool.argtypes = [P(Shape), P(f32), P(f32), P(f64), P(f64), P(f64), P(f64)]
         lib.oracle_conv_pool.restype = None
+        lib.oracle_add_bias.argtypes = [i32, i32, i64, P(f32), ctypes.c_int, P(f64), P(f64)]
+        lib.oracle_add_bias.restype = None
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         lib.oracle_set_threads.restype = ctypes.c_int
         _lib = lib
@@ -151,6 +153,26 @@ def conv(x, w, stride=1, pad=0, groups=1, relu=False, want_absdot=True):
     lib.oracle_conv(ctypes.byref(shape), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
                     1 if relu else 0, _ptr(y, ctypes.c_double), _ptr(a, ctypes.c_double))
     return y, a
+
+
+def conv_bias(x, w, bias, stride=1, pad=0, groups=1, relu=False):
+    """Convolution layer with bias: the plain fp64 sums, + bias[k], then the optional ReLU:
+    (y[N,K,OH,OW], absdot including |bias|)."""
+    lib = _load()
+    y, a = conv(x, w, stride, pad, groups, relu=False)
+    b = _f32(bias)
+    N, K, OH, OW = y.shape
+    if b.shape != (K,):
+        raise ValueError("bias must have one value per filter")
+    lib.oracle_add_bias(N, K, OH * OW, _ptr(b, ctypes.c_float), 1 if relu else 0,
+                        _ptr(y, ctypes.c_double), _ptr(a, ctypes.c_double))
+    return y, a
+
+
+def conv_pool_bias(x, w, bias, pool, stride=1, pad=0, groups=1):
+    """Fused definition with bias: conv, + bias[k], ReLU, max pooling: (z[N,K,PH,PW], scale)."""
+    y, a = conv_bias(x, w, bias, stride, pad, groups, relu=True)
+    return maxpool(y, pool, a)
 
 
 def conv_at(x, w, points, stride=1, pad=0, groups=1, relu=False):

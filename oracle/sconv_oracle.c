@@ -15,6 +15,10 @@
  *     in the paper's scan order, because an encoding is a representation with exactly one
  *     correct value.
  *   - oracle_spmv: Algorithm 2 / the product part of Algorithm 4 evaluated on an encoding.
+ *   - oracle_add_bias: the layer's bias, added to the plain sums before the ReLU.  The paper's
+ *     kernels have no bias term; this is the ordinary definition of a convolution layer, pinned against
+ *     a brute-force loop, the library's fp64 convolution with bias, and the zero-input / zero-bias
+ *     special cases.
  *
  * Readings of the paper taken here (it is silent or inconsistent on these):
  *   - filter position of tap (i,j) is i*k_w + j, row-major (Algorithm 3 prints i*k_h+j and
@@ -240,6 +244,26 @@ void oracle_conv_at(const oracle_shape_t* s, const float* x, const float* w, int
         y[i] = acc;
         if (absdot) absdot[i] = mag;
     }
+}
+
+/*
+ * Bias of a convolution layer (not part of the paper's kernels, which stop at the products; the
+ * affine term every layer they are taken from carries): y[n][k][.][.] += bias[k], applied to the plain
+ * sums before the ReLU of Section 5.5.  y is a convolution computed WITHOUT ReLU; relu != 0 applies
+ * max(y, 0) afterwards.  absdot (optional) grows by |bias[k]|: the bias is one more term of the sum
+ * the rounding-error bound is scaled by.  count = OH*OW (or however many results each (n, k) has).
+ */
+void oracle_add_bias(int32_t N, int32_t K, int64_t count, const float* bias, int relu, double* y, double* absdot)
+{
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int64_t i = 0; i < count; ++i) {
+                size_t o = ((size_t)n * K + k) * (size_t)count + (size_t)i;
+                double v = y[o] + (double)bias[k];
+                if (relu && v < 0.0) v = 0.0;
+                y[o] = v;
+                if (absdot) absdot[o] += fabs((double)bias[k]);
+            }
 }
 
 /*

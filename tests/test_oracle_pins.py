@@ -465,3 +465,57 @@ def test_expected_count_on_bernoulli_input():
     interior = count.reshape(28, 28)[1:-1, 1:-1]
     assert abs(interior.mean() / (16 * 9) - 0.3) < 0.01
     assert abs((x == 0).mean() - 0.7) < 0.01
+
+
+# ---------------------------------------------------------------- bias (the layer's affine term)
+
+@pytest.mark.parametrize("shp", SHAPES[:5])
+def test_conv_bias_matches_brute_force_and_library(shp):
+    """Bias is added to the plain sums before the ReLU: the 7-loop brute force plus b[k], the library's
+    fp64 conv2d with its bias argument, and the error scale grown by |b[k]|."""
+    layer, x, w = _case(41, shp)
+    rng = np.random.default_rng(41)
+    b = rng.standard_normal(shp[4]).astype(np.float32)
+    y, a = oracle.conv_bias(x, w, b, shp[7], shp[8], shp[9], relu=False)
+    ref = _brute_conv(x, w, shp[7], shp[8], shp[9]) + b.astype(np.float64)[None, :, None, None]
+    np.testing.assert_allclose(y, ref, rtol=0, atol=1e-12)
+    lib = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(),
+                   shp[7], shp[8], 1, shp[9]).numpy()
+    np.testing.assert_allclose(y, lib, rtol=0, atol=1e-11)
+    _, a0 = oracle.conv(x, w, shp[7], shp[8], shp[9])
+    np.testing.assert_allclose(a, a0 + np.abs(b.astype(np.float64))[None, :, None, None], rtol=0, atol=1e-12)
+    yr, _ = oracle.conv_bias(x, w, b, shp[7], shp[8], shp[9], relu=True)
+    np.testing.assert_array_equal(yr, np.maximum(y, 0.0))       # ReLU comes after the bias
+    assert (yr != np.maximum(ref - b.astype(np.float64)[None, :, None, None], 0) + b[None, :, None, None]).any()
+
+
+def test_bias_special_cases():
+    """All-zero input: every output is its filter's bias (ReLU'd); zero bias: the plain convolution, bit
+    for bit; a bias on one filter moves that filter's plane only."""
+    shp = SHAPES[1]
+    layer, x, w = _case(42, shp)
+    b = np.array([0.5, -0.25, 2.0, -3.0], np.float32)
+    y, a = oracle.conv_bias(np.zeros_like(x), w, b, shp[7], shp[8], shp[9], relu=True)
+    np.testing.assert_array_equal(y, np.broadcast_to(np.maximum(b, 0).astype(np.float64)[None, :, None, None], y.shape))
+    np.testing.assert_array_equal(a, np.broadcast_to(np.abs(b).astype(np.float64)[None, :, None, None], a.shape))
+    y0, a0 = oracle.conv(x, w, shp[7], shp[8], shp[9])
+    yz, az = oracle.conv_bias(x, w, np.zeros(4, np.float32), shp[7], shp[8], shp[9])
+    np.testing.assert_array_equal(yz, y0)
+    np.testing.assert_array_equal(az, a0)
+    one = np.array([0, 0, 1.5, 0], np.float32)
+    y1, _ = oracle.conv_bias(x, w, one, shp[7], shp[8], shp[9])
+    np.testing.assert_array_equal(y1[:, [0, 1, 3]], y0[:, [0, 1, 3]])
+    np.testing.assert_allclose(y1[:, 2], y0[:, 2] + 1.5, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("pool", [(2, 2, 2), (3, 3, 2)])
+def test_conv_pool_bias_matches_library(pool):
+    shp = (2, 3, 9, 10, 4, 3, 3, 1, 1, 1)
+    layer, x, w = _case(43, shp)
+    b = np.array([0.3, -0.7, 1.1, -0.1], np.float32)
+    z, sc = oracle.conv_pool_bias(x, w, b, pool, shp[7], shp[8], shp[9])
+    conv = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(),
+                    shp[7], shp[8], 1, shp[9])
+    ref = F.max_pool2d(torch.relu(conv), (pool[0], pool[1]), pool[2]).numpy()
+    np.testing.assert_allclose(z, ref, rtol=0, atol=1e-11)
+    assert (sc >= np.abs(b).min()).all()
