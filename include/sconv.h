@@ -123,6 +123,19 @@ int sconv_pool_forward(const sconv_desc_t* desc, const float* x_dev, const float
                        float* y_dev, void* hip_stream);
 
 /*
+ * The two forward calls with the layer's bias: bias_dev[k] (device, [K] fp32) is added to every result of
+ * filter k before the ReLU - y = max(0, bias[k] + sum) - inside the same kernels' epilogues (for a split
+ * launch, in the kernel that adds the partial sums).  The paper's kernels stop at the products and the
+ * ReLU (Sections 5.5 and 6.4); the bias is the affine term the layers they are taken from carry, so
+ * that one layer's output can feed the next layer directly.  Plans, workspaces and errors as the plain
+ * calls; bias_dev NULL is SCONV_EINVAL (use the plain calls).
+ */
+int sconv_forward_bias(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, const float* bias_dev,
+                       float* y_dev, void* hip_stream);
+int sconv_pool_forward_bias(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                            const float* bias_dev, float* y_dev, void* hip_stream);
+
+/*
  * The unfused second step, for comparison with sconv_pool_forward: ReLU and max pooling of a
  * convolution tensor that sconv_forward stored (Section 5.5 followed by a pooling layer; Section 6
  * fuses the two to save this tensor's trip through memory):

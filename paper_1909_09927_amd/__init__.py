@@ -70,12 +70,15 @@ def lib() -> ctypes.CDLL:
         L.sconv_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sconv_pool_forward_ws.argtypes = [P(Desc), vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sconv_forward_static.argtypes = [P(Desc), vp, vp, vp, vp]
+        L.sconv_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
+        L.sconv_pool_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
         L.sconv_density.argtypes = [P(Desc), vp, vp, vp]
         L.sconv_set_density_hint.argtypes = [P(Desc), ctypes.c_int, ctypes.c_float]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
-                  "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_density",
+                  "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_forward_bias",
+                  "sconv_pool_forward_bias", "sconv_density",
                   "sconv_set_density_hint"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
@@ -242,9 +245,10 @@ def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None, out
 _NO_WS = object()   # "no ws argument": the plain entry point (a lent workspace applies)
 
 
-def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS):
+def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS, bias=None):
     """Sparse convolution; returns y[N,K,OH,OW] (device, fp32).  ws: a device tensor (or None) passed as
-    this call's workspace through sconv_forward_ws; left out, sconv_forward runs."""
+    this call's workspace through sconv_forward_ws; left out, sconv_forward runs.  bias: a device tensor
+    [K] added before the ReLU (sconv_forward_bias; not together with ws)."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -256,7 +260,13 @@ def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, OH, OW):
             raise ValueError("out has the wrong shape")
-    if ws is _NO_WS:
+    if bias is not None:
+        _check_dev(bias, torch.float32, "bias")
+        if ws is not _NO_WS or tuple(bias.shape) != (desc.K,):
+            raise ValueError("bias must be [K] and cannot be combined with an explicit workspace")
+        rc = lib().sconv_forward_bias(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), bias.data_ptr(),
+                                      out.data_ptr(), _stream())
+    elif ws is _NO_WS:
         rc = lib().sconv_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
     else:
         wp, wb = _ws_args(ws)
@@ -309,7 +319,7 @@ def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=N
     return out
 
 
-def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS):
+def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS, bias=None):
     """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32).
     ws: as in sconv_forward (sconv_pool_forward_ws)."""
     import torch
@@ -323,7 +333,13 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_W
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, PH, PW):
             raise ValueError("out has the wrong shape")
-    if ws is _NO_WS:
+    if bias is not None:
+        _check_dev(bias, torch.float32, "bias")
+        if ws is not _NO_WS or tuple(bias.shape) != (desc.K,):
+            raise ValueError("bias must be [K] and cannot be combined with an explicit workspace")
+        rc = lib().sconv_pool_forward_bias(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), bias.data_ptr(),
+                                           out.data_ptr(), _stream())
+    elif ws is _NO_WS:
         rc = lib().sconv_pool_forward(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream())
     else:
         wp, wb = _ws_args(ws)

@@ -637,6 +637,29 @@ extern "C" int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_de
     return run_with(p, true, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_forward_bias(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                  const float* bias_dev, float* y_dev, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !bias_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    p.bias = bias_dev;
+    return run(p, false, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_pool_forward_bias(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                       const float* bias_dev, float* y_dev, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !bias_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, true, &p);
+    if (rc) return rc;
+    if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    p.bias = bias_dev;
+    return run(p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
+}
+
 extern "C" int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
                                     float* y_dev, void* hip_stream)
 {

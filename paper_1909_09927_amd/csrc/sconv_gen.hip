@@ -273,9 +273,12 @@ __global__ __launch_bounds__(NWV * 64) void gen_kernel(Problem p, WideCfg cfg, G
 #pragma unroll
             for (int i = 0; i < KPL; ++i) {
                 const int k = 64 * i + lane;
-                float m = 0.0f;                    // ReLU: the maximum is taken over max(value, 0)
-                for (int e = 0; e < WR; ++e) m = fmaxf(m, tl[(i * 64 + wl * WR + e) * 64 + lane]);
-                if (k < kvalid) y[((size_t)nn * p.K + (size_t)g * p.Kg + kb0 + k) * plane + rem] = m;
+                float m = tl[(i * 64 + wl * WR) * 64 + lane];
+                for (int e = 1; e < WR; ++e) m = fmaxf(m, tl[(i * 64 + wl * WR + e) * 64 + lane]);
+                if (k < kvalid) {                  // bias, then ReLU (both commute with the maximum)
+                    const size_t kglob = (size_t)g * p.Kg + kb0 + k;
+                    y[((size_t)nn * p.K + kglob) * plane + rem] = fmaxf(m + bias_of(p, kglob), 0.0f);
+                }
             }
         }
     } else {
@@ -451,6 +454,7 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;
         q.relu = 0;
+        q.bias = nullptr;
     } else if (pooled != (POOL != 0)) {
         return SCONV_EUNSUPPORTED;
     }

@@ -17,7 +17,11 @@ struct Problem {
     int PH, PW;          // pooled output (0 when not pooling)
     int L;               // slots per window row = Cg*R*S
     int relu;            // apply max(.,0) before the store
+    const float* bias;   // device, [K]: added to every result of filter k before the ReLU; null = none
 };
+
+// The bias of filter kglob (0 when the call carries none).
+__device__ __forceinline__ float bias_of(const Problem& p, size_t kglob) { return p.bias ? p.bias[kglob] : 0.0f; }
 
 // Validates a descriptor (pure host code) and fills a Problem.  pooled: the pooling fields
 // are required and checked.  Returns SCONV_OK / SCONV_EINVAL / SCONV_EUNSUPPORTED.

@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(Problem p, RowsCfg cfg,
         for (int idx = tid; idx < KT * WA; idx += kBlock) {
             const int k = idx / WA, i = idx - k * WA;
             if (k < kvalid && i < nw) {
-                float v = out[k * WTP + i];
+                float v = out[k * WTP + i] + bias_of(p, (size_t)g * p.Kg + k0 + k);
                 if (p.relu) v = fmaxf(v, 0.0f);
                 yg[(size_t)k * plane + i] = v;
             }
@@ -292,9 +292,9 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(Problem p, RowsCfg cfg,
         for (int idx = tid; idx < KT * TP; idx += kBlock) {
             const int k = idx / TP, i = idx - k * TP;
             if (k < kvalid && i < np) {
-                float m = 0.0f;  // ReLU folded into the start value
-                for (int t = 0; t < cfg.PP; ++t) m = fmaxf(m, out[k * WTP + i * cfg.PP + t]);
-                yg[(size_t)k * plane + i] = m;
+                float m = out[k * WTP + i * cfg.PP];
+                for (int t = 1; t < cfg.PP; ++t) m = fmaxf(m, out[k * WTP + i * cfg.PP + t]);
+                yg[(size_t)k * plane + i] = fmaxf(m + bias_of(p, (size_t)g * p.Kg + k0 + k), 0.0f);   // bias, ReLU
             }
         }
     }

@@ -22,12 +22,14 @@ namespace sconv {
 namespace {
 
 __global__ __launch_bounds__(256) void split_sum_kernel(const float* __restrict__ part, float* __restrict__ y,
-                                                        int nss, long long slice, long long total, int relu)
+                                                        int nss, long long slice, long long total, int relu,
+                                                        const float* __restrict__ bias, int K, int plane)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     float v = part[i];
     for (int s = 1; s < nss; ++s) v += part[s * slice + i];
+    if (bias) v += bias[(i / plane) % K];
     if (relu) v = fmaxf(v, 0.0f);
     y[i] = v;
 }
@@ -44,7 +46,7 @@ __global__ __launch_bounds__(256) void split_pool_kernel(Problem p, const float*
     const int phi = (int)(q % p.PH);
     const long long nk = q / p.PH;
     const float* src = part + (nk * p.OH + (long long)phi * p.ps) * p.OW + (long long)pwi * p.ps;
-    float m = 0.0f;   // ReLU: the maximum is taken over max(value, 0)
+    float m = -INFINITY;
     for (int py = 0; py < p.ph; ++py)
         for (int px = 0; px < p.pw; ++px) {
             const float* e = src + py * p.OW + px;
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(256) void split_pool_kernel(Problem p, const float*
             for (int s = 1; s < nss; ++s) v += e[s * slice];
             m = fmaxf(m, v);
         }
-    y[i] = m;
+    y[i] = fmaxf(m + bias_of(p, (size_t)(nk % p.K)), 0.0f);   // bias, ReLU: both commute with the maximum
 }
 
 struct Lent {
@@ -145,7 +147,7 @@ int launch_split_reduce(const Problem& p, bool pooled, const float* part, int ns
     const long long slice = (long long)p.N * p.K * p.OH * p.OW;
     if (!pooled) {
         hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((slice + 255) / 256)), dim3(256), 0, stream, part, y,
-                           nss, slice, slice, p.relu);
+                           nss, slice, slice, p.relu, p.bias, p.K, p.OH * p.OW);
     } else {
         const long long total = (long long)p.N * p.K * p.PH * p.PW;
         hipLaunchKernelGGL(split_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p, part,

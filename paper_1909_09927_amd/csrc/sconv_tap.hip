@@ -374,6 +374,7 @@ int launch_plan(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         out = split_scratch(stream);
         if (!out) return SCONV_EUNSUPPORTED;
         q.relu = 0;
+        q.bias = nullptr;
     } else if (pooled != G::POOL) {
         return SCONV_EUNSUPPORTED;
     }

@@ -108,11 +108,12 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < G::ACC; ++a) {
                 const int oh = oh0 + a / G::TW, ow = ow0 + a % G::TW;
                 if (oh < p.OH && ow < p.OW) {
-                    float v = acc[i][a];
+                    float v = acc[i][a] + bk;
                     if (p.relu) v = fmaxf(v, 0.0f);
                     yk[oh * p.OW + ow] = v;
                 }
@@ -126,6 +127,7 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
+            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < (G::TH / 2) * (G::TW / 2); ++a) {
                 const int pr = a / (G::TW / 2), pc = a % (G::TW / 2);
@@ -134,7 +136,7 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
                     const int b = (2 * pr) * G::TW + 2 * pc;
                     float m = fmaxf(fmaxf(acc[i][b], acc[i][b + 1]),
                                     fmaxf(acc[i][b + G::TW], acc[i][b + G::TW + 1]));
-                    yk[phh * p.PW + pww] = fmaxf(m, 0.0f);
+                    yk[phh * p.PW + pww] = fmaxf(m + bk, 0.0f);
                 }
             }
         }

@@ -260,6 +260,7 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
             return SCONV_EUNSUPPORTED;
         out = part;
         q.relu = 0;
+        q.bias = nullptr;
     } else if (pooled != G::POOL) {
         return SCONV_EUNSUPPORTED;
     }

@@ -110,12 +110,13 @@ __device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg
             const int k = 64 * i + 16 * b + kf;
             if (k >= kvalid) continue;
             const size_t kglob = (size_t)g * p.Kg + kb0 + k;
+            const float bk = bias_of(p, kglob);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int P0 = tile * 64 + 16 * q + 4 * rg;
                 if (cs != q / bps || P0 >= cfg.npos) continue;
-                float v0 = acc[i][q][4 * b], v1 = acc[i][q][4 * b + 1], v2 = acc[i][q][4 * b + 2],
-                      v3 = acc[i][q][4 * b + 3];
+                float v0 = acc[i][q][4 * b] + bk, v1 = acc[i][q][4 * b + 1] + bk, v2 = acc[i][q][4 * b + 2] + bk,
+                      v3 = acc[i][q][4 * b + 3] + bk;
                 if (POOL) {
                     // four rows of one pooling window: ReLU, maximum, one pooled result
                     const int pp = P0 >> 2;

@@ -281,6 +281,38 @@ def test_pooled_tile_geometries_of_the_element_stationary_kernels(device, monkey
     assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
 
 
+BIAS_SHAPES = [SMALL[i] for i in range(0, len(SMALL), 3)] + [
+    (1, 512, 7, 7, 512, 3, 3, 1, 1, 1, None),            # split across workgroups: the adding kernel applies it
+    (2, 256, 14, 14, 128, 3, 3, 1, 1, 1, (2, 2, 2)),
+    (1, 64, 13, 13, 96, 3, 3, 1, 1, 1, (3, 3, 2)),       # overlapping pooling windows (general kernel)
+]
+
+
+@pytest.mark.parametrize("variant", [None, "rows", "gen"])
+@pytest.mark.parametrize("shp", BIAS_SHAPES)
+def test_bias_is_added_before_the_relu_in_every_kernel(device, monkeypatch, shp, variant):
+    """sconv_forward_bias / sconv_pool_forward_bias against the oracle's layer-with-bias definition:
+    through the default dispatch (whatever specialised kernel the shape gets), the general vector kernel
+    and the general matrix kernel; ReLU on and off; negative biases large enough to flip signs."""
+    import oracle
+    if variant:
+        monkeypatch.setenv("SCONV_VARIANT", variant)
+    layer, x, w = _mk(340, shp)
+    rng = np.random.default_rng(340)
+    b = (rng.standard_normal(shp[4]) * 0.5).astype(np.float32)
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    for relu in (True, False):
+        y = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=relu, bias=bd)
+        torch.cuda.synchronize()
+        ref, scale = oracle.conv_bias(x, w, b, layer.stride, layer.pad, layer.groups, relu=relu)
+        assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+    if layer.pool:
+        z = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups, bias=bd)
+        torch.cuda.synchronize()
+        ref, scale = oracle.conv_pool_bias(x, w, b, layer.pool, layer.stride, layer.pad, layer.groups)
+        assert (np.abs(z.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
 def test_density_probe_counts_like_the_scan(device):
     """sconv_density counts x != 0 exactly on maps it reads whole (negative zero is a zero, a denormal is
     not), and within sampling error on larger ones."""

@@ -19,7 +19,9 @@ def test_library_exports_every_declared_symbol():
     assert {"sconv_encode", "sconv_forward", "sconv_pool_forward", "sconv_output_dims",
             "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool", "sconv_tune",
             "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace",
-            "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_env_refresh", "sconv_clear_workspaces"} <= names
+            "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_env_refresh", "sconv_clear_workspaces",
+            "sconv_forward_bias", "sconv_pool_forward_bias", "sconv_density", "sconv_set_density_hint",
+            "sconv_forward_static"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
