@@ -782,6 +782,39 @@ def run_micro(args) -> None:
         print(json.dumps(rec), flush=True)
 
 
+def run_pair(args) -> None:
+    """The single-workgroup hand-off of Section 6.4 on a LeNet-shaped pair (5x5 1->20 on 28x28 + 2x2/2
+    pooling, then 5x5 20->50 + pooling): one launch with the intermediate map in LDS, next to the two fused
+    calls one after the other (intermediate through device memory).  Parity is checked first."""
+    import torch
+    import oracle
+    import paper_1909_09927_amd as sconv
+    lend_workspace()
+    rng = np.random.default_rng(workloads.BASE_SEED + 61)
+    for N in (1, 8, 64, 256):
+        x = np.where(rng.random((N, 1, 28, 28)) < 0.3, np.abs(rng.standard_normal((N, 1, 28, 28))), 0).astype(np.float32)
+        w1 = (rng.standard_normal((20, 1, 5, 5)) * np.sqrt(2 / 25)).astype(np.float32)
+        w2 = (rng.standard_normal((50, 20, 5, 5)) * np.sqrt(2 / 500)).astype(np.float32)
+        xd, w1d, w2d = (torch.from_numpy(t).cuda() for t in (x, w1, w2))
+        first = {"pool": (2, 2, 2)}
+        y, mid = sconv.sconv_pair_forward(xd, w1d, w2d, first, first, keep_mid=True)
+        torch.cuda.synchronize()
+        ref, sc = oracle.conv_pool(mid.cpu().numpy(), w2, (2, 2, 2))
+        ok = bool((np.abs(y.cpu().numpy() - ref) <= 1e-4 * sc).all())
+        m = sconv.sconv_pool_forward(xd, w1d, (2, 2, 2))
+        z = sconv.sconv_pool_forward(m, w2d, (2, 2, 2))
+
+        def two():
+            sconv.sconv_pool_forward(xd, w1d, (2, 2, 2), out=m)
+            sconv.sconv_pool_forward(m, w2d, (2, 2, 2), out=z)
+        t_pair = _time(lambda: sconv.sconv_pair_forward(xd, w1d, w2d, first, first), args.steps, args.warmup)
+        t_two = _time(two, args.steps, args.warmup)
+        print(json.dumps({"pair": "lenet conv1+pool -> conv2+pool", "N": N, "parity_ok": ok,
+                          "zero_ratio_in": round(float((x == 0).mean()), 3),
+                          "zero_ratio_mid": round(float((mid == 0).float().mean()), 3),
+                          "one_launch_ms": round(t_pair, 5), "two_calls_ms": round(t_two, 5)}), flush=True)
+
+
 def run_copy_calibration(args) -> None:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -820,6 +853,8 @@ def main() -> None:
     ap.add_argument("--hint", action="store_true",
                     help="no tuning: probe every layer's input once (sconv_density) and give the static rules "
                          "its zero ratio (sconv_set_density_hint)")
+    ap.add_argument("--pair", action="store_true",
+                    help="two LeNet-shaped layers in one launch (hand-off in LDS) against two calls")
     ap.add_argument("--micro", action="store_true",
                     help="issue-rate microbenchmarks: vector FMAs, scalar tests, branches, computed jumps")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -847,6 +882,8 @@ def main() -> None:
         run_copy_calibration(args)
     elif args.micro:
         run_micro(args)
+    elif args.pair:
+        run_pair(args)
     elif args.shape:
         run_shape(args)
     elif args.sweep:

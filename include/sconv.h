@@ -136,6 +136,28 @@ int sconv_pool_forward_bias(const sconv_desc_t* desc, const float* x_dev, const 
                             const float* bias_dev, float* y_dev, void* hip_stream);
 
 /*
+ * Two consecutive layers in one launch with the first layer's output handed over on chip (Section 6.4:
+ * when one thread block computes all pooling results they can stay in shared memory for the next
+ * convolution layer; step 4 of the procedure of Section 5.1 then skips global memory).  One workgroup per
+ * image holds the image, both filter tensors and the intermediate map in LDS, so this covers small pairs
+ * only (4 * (C1*H*W + L1*K1' + K1*MH*MW + L2*K2') <= 160 KiB, K' = K rounded up to 64, MH x MW the first
+ * layer's stored map; e.g. LeNet: 5x5 1->20 on 28x28 + 2x2/2 pooling, then 5x5 20->50 + pooling).
+ *   first, second: the two layers; a layer with pooling fields set is conv + ReLU + max pooling (as
+ *          sconv_pool_forward), one without is conv with its SCONV_RELU flag (as sconv_forward).  The
+ *          second layer's input must be the first layer's output: N equal, C2 = K1, H2 x W2 = the first
+ *          layer's (pooled) output size.  groups must be 1 in both.
+ *   x_dev  device, in : [N][C1][H][W];  w1_dev, w2_dev device, in: the layers' filters
+ *   bias1_dev, bias2_dev device, in, optional (NULL: none): [K1], [K2], added before the ReLU
+ *   mid_dev device, out, optional (NULL: the intermediate map never leaves the chip): [N][K1][MH][MW]
+ *   y_dev  device, out: the second layer's output
+ * SCONV_EINVAL when the layers do not chain; SCONV_EUNSUPPORTED when the pair does not fit (call the
+ * layers one after the other instead).  Zeros are skipped element by element in both layers.
+ */
+int sconv_pair_forward(const sconv_desc_t* first, const sconv_desc_t* second, const float* x_dev,
+                       const float* w1_dev, const float* bias1_dev, const float* w2_dev, const float* bias2_dev,
+                       float* mid_dev, float* y_dev, void* hip_stream);
+
+/*
  * The unfused second step, for comparison with sconv_pool_forward: ReLU and max pooling of a
  * convolution tensor that sconv_forward stored (Section 5.5 followed by a pooling layer; Section 6
  * fuses the two to save this tensor's trip through memory):

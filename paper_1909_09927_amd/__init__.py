@@ -72,13 +72,14 @@ def lib() -> ctypes.CDLL:
         L.sconv_forward_static.argtypes = [P(Desc), vp, vp, vp, vp]
         L.sconv_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
         L.sconv_pool_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
+        L.sconv_pair_forward.argtypes = [P(Desc), P(Desc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.sconv_density.argtypes = [P(Desc), vp, vp, vp]
         L.sconv_set_density_hint.argtypes = [P(Desc), ctypes.c_int, ctypes.c_float]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
                   "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_forward_bias",
-                  "sconv_pool_forward_bias", "sconv_density",
+                  "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density",
                   "sconv_set_density_hint"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
@@ -295,6 +296,33 @@ def sconv_forward_static(x, w, stride=1, pad=0, groups=1, relu=False, out=None):
     if rc:
         raise SconvError(rc, "sconv_forward_static")
     return out
+
+
+def sconv_pair_forward(x, w1, w2, first, second, bias1=None, bias2=None, keep_mid=False):
+    """Two layers in one launch, the first layer's output handed over in LDS.  first / second: dicts with
+    stride, pad, pool (None or (p_h, p_w, p_s)) and relu.  Returns (y, mid or None)."""
+    import torch
+    for t, name in ((x, "x"), (w1, "w1"), (w2, "w2")):
+        _check_dev(t, torch.float32, name)
+    d1 = desc_for(x, w1, first.get("stride", 1), first.get("pad", 0), 1, first.get("pool"), first.get("relu", True))
+    oh1, ow1, ph1, pw1 = sconv_output_dims(d1)
+    mh, mw = (ph1, pw1) if first.get("pool") else (oh1, ow1)
+    d2 = make_desc(d1.N, d1.K, mh, mw, w2.shape[0], w2.shape[2], w2.shape[3], second.get("stride", 1),
+                   second.get("pad", 0), 1, second.get("pool"), second.get("relu", True))
+    oh2, ow2, ph2, pw2 = sconv_output_dims(d2)
+    yh, yw = (ph2, pw2) if second.get("pool") else (oh2, ow2)
+    y = torch.empty((d1.N, d2.K, yh, yw), dtype=torch.float32, device=x.device)
+    mid = torch.empty((d1.N, d1.K, mh, mw), dtype=torch.float32, device=x.device) if keep_mid else None
+    for b, name in ((bias1, "bias1"), (bias2, "bias2")):
+        if b is not None:
+            _check_dev(b, torch.float32, name)
+    rc = lib().sconv_pair_forward(ctypes.byref(d1), ctypes.byref(d2), x.data_ptr(), w1.data_ptr(),
+                                  bias1.data_ptr() if bias1 is not None else None, w2.data_ptr(),
+                                  bias2.data_ptr() if bias2 is not None else None,
+                                  mid.data_ptr() if mid is not None else None, y.data_ptr(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_pair_forward")
+    return y, mid
 
 
 def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=None):

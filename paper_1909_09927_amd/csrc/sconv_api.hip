@@ -660,6 +660,25 @@ extern "C" int sconv_pool_forward_bias(const sconv_desc_t* desc, const float* x_
     return run(p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_pair_forward(const sconv_desc_t* first, const sconv_desc_t* second, const float* x_dev,
+                                  const float* w1_dev, const float* bias1_dev, const float* w2_dev,
+                                  const float* bias2_dev, float* mid_dev, float* y_dev, void* hip_stream)
+{
+    if (!first || !second || !x_dev || !w1_dev || !w2_dev || !y_dev) return SCONV_EINVAL;
+    const bool pooled1 = first->pool_h > 0 || first->pool_w > 0 || first->pool_stride > 0;
+    const bool pooled2 = second->pool_h > 0 || second->pool_w > 0 || second->pool_stride > 0;
+    Problem p1, p2;
+    int rc = fill_problem(first, pooled1, &p1);
+    if (rc) return rc;
+    rc = fill_problem(second, pooled2, &p2);
+    if (rc) return rc;
+    if ((pooled1 && (int64_t)p1.ph * p1.pw > 64) || (pooled2 && (int64_t)p2.ph * p2.pw > 64)) return SCONV_EUNSUPPORTED;
+    p1.bias = bias1_dev;
+    p2.bias = bias2_dev;
+    std::lock_guard<std::mutex> lock(g_lock);
+    return launch_pair(p1, pooled1, p2, pooled2, x_dev, w1_dev, w2_dev, mid_dev, y_dev, (hipStream_t)hip_stream);
+}
+
 extern "C" int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
                                     float* y_dev, void* hip_stream)
 {

@@ -32,6 +32,12 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out);
 int launch_encode(const Problem& p, int fmt, const float* x, float* values, int32_t* index,
                   int32_t* count, hipStream_t stream);
 
+// Two layers in one launch, one workgroup per image, the first layer's output kept in LDS (and copied to
+// mid_out when that is not null).  SCONV_EUNSUPPORTED when the pair does not fit a workgroup's LDS or
+// is grouped; SCONV_EINVAL when the second layer's input is not the first layer's output.
+int launch_pair(const Problem& p1, bool pooled1, const Problem& p2, bool pooled2, const float* x, const float* w1,
+                const float* w2, float* mid_out, float* y, hipStream_t stream);
+
 // Counts examined and nonzero elements of x into counts[0], counts[1] (device); at most 4 Mi elements.
 int launch_density_probe(const Problem& p, const float* x, unsigned long long* counts, hipStream_t stream);
 

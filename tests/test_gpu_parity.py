@@ -313,6 +313,61 @@ def test_bias_is_added_before_the_relu_in_every_kernel(device, monkeypatch, shp,
         assert (np.abs(z.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
 
 
+PAIRS = [
+    # (N, C1, H, W, K1, R1, S1, stride1, pad1, pool1, K2, R2, S2, stride2, pad2, pool2)
+    (3, 1, 28, 28, 20, 5, 5, 1, 0, (2, 2, 2), 50, 5, 5, 1, 0, (2, 2, 2)),      # LeNet conv1+pool -> conv2+pool
+    (2, 3, 13, 11, 40, 3, 3, 1, 1, None, 33, 3, 3, 2, 1, None),                # no pooling, ragged filter blocks
+    (2, 8, 12, 12, 16, 3, 3, 1, 1, (3, 3, 2), 24, 1, 1, 1, 0, (2, 2, 1)),      # overlapping pooling, then 1x1
+]
+
+
+@pytest.mark.parametrize("with_bias", [False, True])
+@pytest.mark.parametrize("pair", PAIRS)
+def test_two_layers_with_the_hand_off_in_lds(device, pair, with_bias):
+    """sconv_pair_forward: the first layer (checked through its optional copy) against the oracle on x, the
+    second against the oracle on the intermediate map the GPU really produced - each layer held to the
+    bar of a layer on its own; and the output is the same bits whether or not the copy is asked for."""
+    import oracle
+    N, C1, H, W, K1, R1, S1, st1, pd1, pool1, K2, R2, S2, st2, pd2, pool2 = pair
+    rng = np.random.default_rng(350)
+    x = np.where(rng.random((N, C1, H, W)) < 0.5, np.abs(rng.standard_normal((N, C1, H, W))), 0).astype(np.float32)
+    w1 = (rng.standard_normal((K1, C1, R1, S1)) * np.sqrt(2.0 / (C1 * R1 * S1))).astype(np.float32)
+    w2 = (rng.standard_normal((K2, K1, R2, S2)) * np.sqrt(2.0 / (K1 * R2 * S2))).astype(np.float32)
+    b1 = (rng.standard_normal(K1) * 0.1).astype(np.float32) if with_bias else None
+    b2 = (rng.standard_normal(K2) * 0.1).astype(np.float32) if with_bias else None
+    first = {"stride": st1, "pad": pd1, "pool": pool1, "relu": True}
+    second = {"stride": st2, "pad": pd2, "pool": pool2, "relu": True}
+    args = (to_dev(x), to_dev(w1), to_dev(w2), first, second)
+    kw = {"bias1": to_dev(b1) if with_bias else None, "bias2": to_dev(b2) if with_bias else None}
+    y, mid = sconv.sconv_pair_forward(*args, keep_mid=True, **kw)
+    y_only, none = sconv.sconv_pair_forward(*args, keep_mid=False, **kw)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(y, y_only)
+
+    def layer(inp, w, b, stride, pad, pool):
+        zb = b if b is not None else np.zeros(w.shape[0], np.float32)
+        if pool:
+            return oracle.conv_pool_bias(inp, w, zb, pool, stride, pad, 1)
+        return oracle.conv_bias(inp, w, zb, stride, pad, 1, relu=True)
+
+    mid_h = mid.cpu().numpy()
+    ref1, sc1 = layer(x, w1, b1, st1, pd1, pool1)
+    assert mid_h.shape == ref1.shape and (np.abs(mid_h.astype(np.float64) - ref1) <= 1e-4 * sc1).all()
+    assert (mid_h == 0).any()                 # the ReLU made zeros for the second layer to skip
+    ref2, sc2 = layer(mid_h, w2, b2, st2, pd2, pool2)
+    got = y.cpu().numpy().astype(np.float64)
+    assert got.shape == ref2.shape and (np.abs(got - ref2) <= 1e-4 * sc2).all()
+
+
+def test_pair_that_does_not_fit_or_does_not_chain_is_refused(device):
+    x = torch.zeros((1, 64, 56, 56), dtype=torch.float32, device="cuda")
+    w1 = torch.zeros((64, 64, 3, 3), dtype=torch.float32, device="cuda")
+    w2 = torch.zeros((64, 64, 3, 3), dtype=torch.float32, device="cuda")
+    with pytest.raises(sconv.SconvError) as e:
+        sconv.sconv_pair_forward(x, w1, w2, {"pad": 1}, {"pad": 1})
+    assert e.value.code == sconv.SCONV_EUNSUPPORTED
+
+
 def test_density_probe_counts_like_the_scan(device):
     """sconv_density counts x != 0 exactly on maps it reads whole (negative zero is a zero, a denormal is
     not), and within sampling error on larger ones."""

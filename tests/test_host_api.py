@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
             "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace",
             "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_env_refresh", "sconv_clear_workspaces",
             "sconv_forward_bias", "sconv_pool_forward_bias", "sconv_density", "sconv_set_density_hint",
-            "sconv_forward_static"} <= names
+            "sconv_forward_static", "sconv_pair_forward"} <= names
     L = sconv.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in sconv.h but not exported"
@@ -259,6 +259,23 @@ def test_density_calls_validate_on_the_host():
     assert sconv.sconv_variant_name(big) == "tap3x3"                     # the hint moved the static choice
     assert L.sconv_set_density_hint(ctypes.byref(big), 0, -1.0) == sconv.SCONV_OK
     assert sconv.sconv_variant_name(big) == "quad3x3"
+
+
+def test_pair_call_validates_on_the_host():
+    L = sconv.lib()
+    d1 = sconv.make_desc(2, 1, 28, 28, 20, 5, 5, 1, 0, 1, (2, 2, 2))
+    d2 = sconv.make_desc(2, 20, 12, 12, 50, 5, 5, 1, 0, 1, (2, 2, 2))
+    p = ctypes.c_void_p(4096)
+    call = lambda a, b, x=p, y=p: L.sconv_pair_forward(ctypes.byref(a), ctypes.byref(b), x, p, None, p, None, None, y, None)
+    assert call(d1, d2, x=None) == sconv.SCONV_EINVAL
+    assert call(d1, d2, y=None) == sconv.SCONV_EINVAL
+    wrong = sconv.make_desc(2, 20, 11, 12, 50, 5, 5, 1, 0, 1, (2, 2, 2))     # not the first layer's output size
+    assert call(d1, wrong) == sconv.SCONV_EINVAL
+    grouped = sconv.make_desc(2, 20, 12, 12, 50, 5, 5, 1, 0, 2, (2, 2, 2))
+    assert call(d1, grouped) == sconv.SCONV_EUNSUPPORTED
+    big1 = sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)
+    big2 = sconv.make_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert call(big1, big2) == sconv.SCONV_EUNSUPPORTED
 
 
 def test_binding_refuses_host_tensors():
