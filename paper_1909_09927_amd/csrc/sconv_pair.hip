@@ -6,10 +6,9 @@
 // lanes = filters read consecutive words) and the intermediate map live in LDS; that bounds the shapes
 // this applies to (LeNet-sized pairs: conv 5x5 1->20 on 28x28 + pooling, then conv 5x5 20->50 + pooling).
 // Both layers run the same window loop: a wavefront takes one output position (one pooling window when
-// the layer pools) and 64 filters; it walks the window's columns in the scan order of Algorithm 1
-// (channel, kernel row, kernel column), reads each element once for all lanes - a broadcast LDS read, so
-// the test `x != 0` is the same for the whole wavefront and a zero costs one scalar branch - and
-// multiplies the nonzero ones with the 64 filters' values of that column (Algorithm 2's row product).
+// the layer pools) and 64 filters; it compacts the window's columns 64 at a time with ballot(x != 0), in
+// the scan order of Algorithm 1 (channel, kernel row, kernel column), and multiplies only the nonzero
+// ones with the 64 filters' values of their column (Algorithm 2's row product).
 // ReLU, the optional bias and the optional max over the pooling window follow in registers
 // (Algorithm 4's reduction); the first layer stores to LDS, the second to global memory.
 #include "sconv_internal.h"
@@ -37,6 +36,13 @@ __device__ __forceinline__ void stage_filters(const float* __restrict__ w, int K
 }
 
 // One layer out of LDS: in[C][H][W], wt[L][Kp].  Output [K][PH or OH][PW or OW] to out_lds and / or out_glob.
+//
+// The window's L = C*R*S columns are taken 64 at a time, one per lane, in the scan order of Algorithm 1:
+// every lane fetches the element its column has in this window (zero for a tap in the padding or a column
+// past L), ballot(x != 0) is the compaction - the set bits, in ascending order, are the (value, column)
+// pairs the scan would have appended - and the wavefront then walks only those: value broadcast from its
+// lane, the 64 filters' values of that column from LDS, one multiply-add per lane.  Four pairs are fetched
+// before their products are issued, so the LDS reads overlap.
 __device__ __forceinline__ void layer_from_lds(const Problem& p, bool pooled, const float* in, const float* wt, int Kp,
                                                float* out_lds, float* __restrict__ out_glob, float* __restrict__ copy_glob,
                                                int wave, int lane)
@@ -44,28 +50,48 @@ __device__ __forceinline__ void layer_from_lds(const Problem& p, bool pooled, co
     const int OHs = pooled ? p.PH : p.OH, OWs = pooled ? p.PW : p.OW;
     const int npos = OHs * OWs, kblocks = Kp / 64;
     const int wh = pooled ? p.ph : 1, ww = pooled ? p.pw : 1, ws = pooled ? p.ps : 1;
+    const int RS = p.R * p.S;
     for (int item = wave; item < npos * kblocks; item += kPairWaves) {
         const int kb = item / npos, pos = item - kb * npos;
         const int oy = pos / OWs, ox = pos - oy * OWs;
         const int k = kb * 64 + lane;
+        const float* wk = wt + k;
         float m = -INFINITY;
         for (int py = 0; py < wh; ++py)
             for (int px = 0; px < ww; ++px) {
-                const int oh = oy * ws + py, ow = ox * ws + px;
+                const int ih0 = (oy * ws + py) * p.stride - p.pad, iw0 = (ox * ws + px) * p.stride - p.pad;
                 float acc = 0.0f;
-                for (int c = 0; c < p.C; ++c)
-                    for (int r = 0; r < p.R; ++r) {
-                        const int ih = oh * p.stride - p.pad + r;
-                        if (ih < 0 || ih >= p.H) continue;          // padding rows hold no nonzero
-                        for (int s = 0; s < p.S; ++s) {
-                            const int iw = ow * p.stride - p.pad + s;
-                            if (iw < 0 || iw >= p.W) continue;
-                            // the same word for every lane: one broadcast read, a uniform test
-                            const float v = __int_as_float(__builtin_amdgcn_readfirstlane(
-                                __float_as_int(in[(c * p.H + ih) * p.W + iw])));
-                            if (v != 0.0f) acc = fmaf(v, wt[((c * p.R + r) * p.S + s) * Kp + k], acc);
+                for (int cb = 0; cb < p.L; cb += 64) {
+                    const int col = cb + lane;
+                    const int c = col / RS, rem = col - c * RS;
+                    const int r = rem / p.S, sx = rem - r * p.S;
+                    const int ih = ih0 + r, iw = iw0 + sx;
+                    const bool ok = col < p.L && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                    const float xv = ok ? in[(c * p.H + ih) * p.W + iw] : 0.0f;
+                    unsigned long long mask = __ballot(xv != 0.0f);
+                    while (mask) {
+                        // up to four nonzeros of the window; a missing one repeats the first with value 0
+                        int bit[4];
+                        float v[4], wv[4];
+                        bit[0] = __builtin_ctzll(mask);
+                        mask &= mask - 1;
+#pragma unroll
+                        for (int j = 1; j < 4; ++j) {
+                            const bool have = mask != 0;
+                            bit[j] = have ? __builtin_ctzll(mask) : -1;
+                            if (have) mask &= mask - 1;
                         }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int bj = bit[j] < 0 ? bit[0] : bit[j];
+                            const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xv), bj));
+                            v[j] = bit[j] < 0 ? 0.0f : t;
+                            wv[j] = wk[(cb + bj) * Kp];
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc = fmaf(v[j], wv[j], acc);
                     }
+                }
                 m = fmaxf(m, acc);
             }
         if (k < p.K) {
