@@ -253,9 +253,10 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  * Run-time choice of the kernel.  Which variant and decomposition is fastest depends on the zero
  * ratio of the map (Section 8's sparsity sweep: the vector kernel's time falls with the ratio, the
  * matrix kernels' only once whole groups are zero), which the host does not know.  sconv_tune runs
- * every variant and every decomposition that covers the descriptor on the caller's operands - each
- * one untimed launch and three timed ones between two events on hip_stream, the static choice and
- * the four fastest then again for about a millisecond each - and remembers the fastest (the static
+ * every variant and every decomposition that covers the descriptor on the caller's operands - a first
+ * pass of one untimed and one timed launch each (two more for a candidate within a quarter of the
+ * fastest so far) between two events on hip_stream with the operands left in the caches, then the static
+ * choice and the four fastest again for about a millisecond each - and remembers the fastest (the static
  * choice unless another measures 3 % and 1.5 us faster) for this exact descriptor (and pooled flag) in a
  * host-side table; later sconv_forward / sconv_pool_forward calls with an identical descriptor launch that plan instead of the cost
  * models' choice.  The table is per process, guarded by the library's lock, and holds no device
@@ -263,10 +264,10 @@ const char* sconv_variant_name(const sconv_desc_t* desc, int pooled);
  *   pooled != 0: tune sconv_pool_forward (y_dev is [N][K][PH][PW]), else sconv_forward.
  *   x_dev, w_dev device, in; y_dev device, out: overwritten many times, left holding the result.
  *   flush_dev device, scratch, optional (NULL with flush_bytes 0): when given, its flush_bytes
- *            bytes are overwritten before every timed launch, so that no launch finds its operands
- *            in the caches (give it at least twice the last-level cache, 512 MiB); without it the
- *            launches run back to back and plans are ranked cache-warm.  With it, the finalists
- *            are timed both ways and a plan replaces the static choice only if it wins both.  This buffer is
+ *            bytes are overwritten before every timed launch of the five finalists, so that none
+ *            finds its operands in the caches (give it at least twice the last-level cache, 512 MiB);
+ *            without it plans are ranked cache-warm only.  With it, the finalists are timed both
+ *            ways and a plan replaces the static choice only if it wins both.  This buffer is
  *            the caller's and only used during this call.  Split plans are tried only when a
  *            workspace is lent for hip_stream (sconv_set_workspace) - lend it first.
  *   best_ms host, out, optional: average launch duration of the chosen plan in milliseconds.

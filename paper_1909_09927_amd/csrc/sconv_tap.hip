@@ -438,6 +438,7 @@ struct Candidate {
         return tapt_launch_##NAME(p, pooled, pl.split_mode, x, w, y, stream);                              \
     }
 SCONV_TAPT_ADAPT(5x7k1)
+SCONV_TAPT_ADAPT(5x7k1n)
 SCONV_TAPT_ADAPT(5x7k2)
 SCONV_TAPT_ADAPT(7x7k1)
 SCONV_TAPT_ADAPT(7x7k2)
@@ -458,6 +459,7 @@ const Candidate kCandidates[] = {
     {"p4x6k1", plan_geom<P46_1>, launch_plan<P46_1>, true, 1, 0, 0, 1, true},
     {"p4x6k2", plan_geom<P46_2>, launch_plan<P46_2>, true, 2, 0, 0, 1, true},
     {"5x7k1t", plan_t_5x7k1, launch_t_5x7k1, false, 1, 0, 0, 1, false},
+    {"5x7k1tn", plan_t_5x7k1n, launch_t_5x7k1n, false, 1, 0, 0, 1, false},
     {"5x7k2t", plan_t_5x7k2, launch_t_5x7k2, false, 2, 0, 0, 1, false},
     {"7x7k1t", plan_t_7x7k1, launch_t_7x7k1, false, 1, 7, 7, 1, false},
     {"7x7k2t", plan_t_7x7k2, launch_t_7x7k2, false, 2, 7, 7, 1, false},
@@ -476,7 +478,7 @@ const Candidate kCandidates[] = {
 const char* const* tap_geoms()
 {
     static const char* const names[] = {"5x7k1", "5x7k2", "7x7k1", "7x7k2", "p4x14k1", "p4x14k2", "p4x6k1", "p4x6k2",
-                                        "s2-3x4k1", "s2-3x4k2", "5x7k1t", "5x7k2t", "7x7k1t", "7x7k2t", "p4x14k1t", "p4x6k1t",
+                                        "s2-3x4k1", "s2-3x4k2", "5x7k1t", "5x7k1tn", "5x7k2t", "7x7k1t", "7x7k2t", "p4x14k1t", "p4x6k1t",
                                         "p4x6k2t", "p2x14k2t", "s2-3x4k1t", "s2-3x4k2t", nullptr};
     return names;
 }

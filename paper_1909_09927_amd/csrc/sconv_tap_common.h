@@ -5,8 +5,9 @@
 
 #include <utility>
 
-template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_, int STRIDE_ = 1>
+template <int KPL_, int TH_, int TW_, int HH_, int HW_, bool POOL_, int STRIDE_ = 1, bool GT_ = true>
 struct Geom {
+    static constexpr bool GT = GT_;             // test four positions at once before testing each
     static constexpr int KPL = KPL_;            // filters per lane
     static constexpr int TH = TH_, TW = TW_;    // output tile
     static constexpr int HH = HH_, HW = HW_;    // 1: tile carries a halo row/column on each side;
@@ -35,6 +36,7 @@ struct TapCfg {
     int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
                         // partial sums, stored into slice blockIdx.z % NSS of y
     int RW;             // slices whose sums fit into LDS side by side during the slice reduction
+    int xcd_remap = 0;  // transposed-filter kernel: renumber the workgroups so that a filter block keeps to one XCD
 };
 
 // One input position P of the tile: test its mask bit, broadcast the value, run its products.
@@ -76,7 +78,7 @@ __device__ __forceinline__ void position_group(const unsigned (&mask)[2 * G::NX]
     constexpr int P0 = 4 * P4;
     constexpr int cnt = (P0 + 4 <= G::NPOS) ? 4 : G::NPOS - P0;
     constexpr unsigned bits = ((1u << cnt) - 1u) << (P0 % 32);   // P0 % 4 == 0: one mask word
-    if (mask[P0 / 32] & bits) {
+    if (!G::GT || (mask[P0 / 32] & bits)) {
         position<G, P0>(mask, xv, acc, wr);
         if constexpr (cnt > 1) position<G, P0 + 1>(mask, xv, acc, wr);
         if constexpr (cnt > 2) position<G, P0 + 2>(mask, xv, acc, wr);

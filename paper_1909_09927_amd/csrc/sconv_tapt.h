@@ -17,6 +17,7 @@ struct TaptPlan {
                            hipStream_t stream);
 
 SCONV_TAPT_DECLARE(5x7k1)
+SCONV_TAPT_DECLARE(5x7k1n)
 SCONV_TAPT_DECLARE(5x7k2)
 SCONV_TAPT_DECLARE(7x7k1)
 SCONV_TAPT_DECLARE(7x7k2)

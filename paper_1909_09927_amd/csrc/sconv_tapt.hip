@@ -32,7 +32,7 @@ namespace {
 
 // w[K][Cg][9] -> wt[(g * kblocks + kb) * Cg * 9 + ct][KB] with ct = c * 9 + tap, through a 64 x 64 LDS
 // tile so that both sides are accessed in runs of 64 consecutive words.
-__global__ __launch_bounds__(256) void transpose_filters_kernel(Problem p, int KB, int kblocks,
+__global__ __launch_bounds__(1024) void transpose_filters_kernel(Problem p, int KB, int kblocks,
                                                                 const float* __restrict__ w, float* __restrict__ wt)
 {
     __shared__ float tile[64][65];
@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void transpose_filters_kernel(Problem p, int K
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int kpad = kblocks * KB;            // filters per group, rounded up to whole blocks
 #pragma unroll
-    for (int r = ty; r < 64; r += 4) {        // row r: filter kk0 + r, 64 consecutive entries
+    for (int i = 0; i < 4; ++i) {             // row r: filter kk0 + r, 64 consecutive entries
+        const int r = ty + 16 * i;
         const int kk = kk0 + r, ct = ct0 + tx;
         float v = 0.0f;
         if (kk < p.Kg && ct < p.L) v = w[((size_t)g * p.Kg + kk) * p.L + ct];
@@ -50,7 +51,8 @@ __global__ __launch_bounds__(256) void transpose_filters_kernel(Problem p, int K
     }
     __syncthreads();
 #pragma unroll
-    for (int r = ty; r < 64; r += 4) {        // row r: entry ct0 + r, 64 consecutive filters
+    for (int i = 0; i < 4; ++i) {             // row r: entry ct0 + r, 64 consecutive filters
+        const int r = ty + 16 * i;
         const int ct = ct0 + r, kk = kk0 + tx;
         if (ct < p.L && kk < kpad) {
             const int kb = kk / KB, ki = kk - kb * KB;
@@ -70,12 +72,33 @@ __global__ __launch_bounds__(NWV * 64) void tapt_kernel(Problem p, TapCfg cfg, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ts = wave % cfg.NT;                  // spatial tile slot
     const int cs = wave / cfg.NT;                  // channel slice
-    const int ss = blockIdx.z % cfg.NSS;           // channel range of the workgroup
-    const int ng = blockIdx.z / cfg.NSS;
+    // Workgroups are handed to the eight XCDs in turn, in launch order.  The ones that read the same
+    // filter block are renumbered onto the same XCD (two XCDs for four blocks, ...), so that a block of
+    // the transposed filters stays in that XCD's L2 instead of being fetched into all eight.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (cfg.xcd_remap) {
+        const int kblocks = gridDim.y;
+        const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + kblocks * blockIdx.z);
+        const unsigned xcd = lin & 7u, idx = lin >> 3;
+        unsigned r;
+        if ((kblocks & 7) == 0) {
+            const unsigned q = kblocks >> 3;
+            by = (int)(xcd + 8u * (idx % q));
+            r = idx / q;
+        } else {   // kblocks is 1, 2 or 4
+            const unsigned m = 8u / kblocks;
+            by = (int)(xcd % kblocks);
+            r = idx * m + xcd / kblocks;
+        }
+        bx = (int)(r % gridDim.x);
+        bz = (int)(r / gridDim.x);
+    }
+    const int ss = bz % cfg.NSS;                   // channel range of the workgroup
+    const int ng = bz / cfg.NSS;
     const int n = ng / p.G;
     const int g = ng - n * p.G;
-    const int kb0 = blockIdx.y * G::KB;
-    const int tile = blockIdx.x * cfg.NT + ts;
+    const int kb0 = by * G::KB;
+    const int tile = bx * cfg.NT + ts;
     const bool tile_ok = tile < cfg.ntiles;
     const int ty = tile / cfg.tiles_x, tx = tile - ty * cfg.tiles_x;
     const int oh0 = ty * G::TH, ow0 = tx * G::TW;
@@ -94,7 +117,7 @@ __global__ __launch_bounds__(NWV * 64) void tapt_kernel(Problem p, TapCfg cfg, c
     }
     const float* xg = x + ((size_t)n * p.C + (size_t)g * p.Cg) * HWp;
     // the block's transposed filters: entry (c, tap) of filter lane + 64*i at wl[(c*9 + tap)*KB + 64*i]
-    const float* wl = wt + ((size_t)g * gridDim.y + blockIdx.y) * p.L * G::KB + lane;
+    const float* wl = wt + ((size_t)g * gridDim.y + by) * p.L * G::KB + lane;
 
     float acc[G::KPL][G::ACC];
 #pragma unroll
@@ -267,14 +290,18 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
     if (p.Cg % (pl.cfg.NCS * pl.nss)) return SCONV_EUNSUPPORTED;
     const dim3 tgrid((unsigned)((p.L + 63) / 64), (unsigned)((pl.kblocks * G::KB + 63) / 64), (unsigned)p.G);
     if (tgrid.y > 65535 || tgrid.z > 65535) return SCONV_EUNSUPPORTED;
-    hipLaunchKernelGGL(transpose_filters_kernel, tgrid, dim3(256), 0, stream, p, G::KB, pl.kblocks, w, wt);
+    hipLaunchKernelGGL(transpose_filters_kernel, tgrid, dim3(1024), 0, stream, p, G::KB, pl.kblocks, w, wt);
     if (launch_status() != SCONV_OK) return SCONV_ELAUNCH;
     const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
+    TapCfg cfg = pl.cfg;
+    const long long total = gx * pl.kblocks * gz;
+    const bool kb_ok = (pl.kblocks % 8) == 0 || pl.kblocks == 1 || pl.kblocks == 2 || pl.kblocks == 4;
+    cfg.xcd_remap = (kb_ok && total % 8 == 0 && total < (1LL << 32) && !env_value("SCONV_NO_XCD_REMAP")) ? 1 : 0;
     int rc;
     if (G::MAXW == 16 && pl.nwv == 16)
-        rc = launch_nwv<G, G::MAXW>(q, pl.cfg, grid, pl.lds_bytes, x, wt, out, stream);
+        rc = launch_nwv<G, G::MAXW>(q, cfg, grid, pl.lds_bytes, x, wt, out, stream);
     else
-        rc = launch_nwv<G, 8>(q, pl.cfg, grid, pl.lds_bytes, x, wt, out, stream);
+        rc = launch_nwv<G, 8>(q, cfg, grid, pl.lds_bytes, x, wt, out, stream);
     if (rc != SCONV_OK || pl.nss == 1) return rc;
     return launch_split_reduce(p, pooled, out, pl.nss, y, stream);
 }
@@ -298,6 +325,7 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
     }
 
 SCONV_TAPT_INSTANCE(5x7k1, 1, 5, 7, 1, 1, false)
+SCONV_TAPT_INSTANCE(5x7k1n, 1, 5, 7, 1, 1, false, 1, false)
 SCONV_TAPT_INSTANCE(5x7k2, 2, 5, 7, 1, 1, false)
 SCONV_TAPT_INSTANCE(7x7k1, 1, 7, 7, 0, 0, false)
 SCONV_TAPT_INSTANCE(7x7k2, 2, 7, 7, 0, 0, false)
