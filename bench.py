@@ -169,15 +169,16 @@ class DeviceLayer:
             else:
                 y = sconv.sconv_forward(xs, ws, layer.stride, layer.pad, layer.groups, relu=True)
             self.sets.append((xs, ws, y))
-        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
         self.host = (x, w)
         self.tune_wall_s = 0.0
+        self.z = None
         if HINT:
-            # set-up: one probe of the input (two small kernels, up to 4 Mi elements) and the hint
+            # set-up: one probe of the input (two small kernels, up to 4 Mi elements); every call of this
+            # layer then carries the zero ratio in its descriptor
             t0 = time.perf_counter()
-            z = sconv.zero_ratio_of(sconv.sconv_density(xd))
-            sconv.sconv_set_density_hint(d, bool(layer.pool), z)
+            self.z = sconv.zero_ratio_of(sconv.sconv_density(xd))
             self.tune_wall_s = time.perf_counter() - t0
+        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, self.z)
         if TUNE:
             # set-up, outside every timed region: the library times its variants and decompositions on
             # this layer's operands and remembers the fastest for this descriptor
@@ -205,9 +206,9 @@ class DeviceLayer:
         self.i = (self.i + 1) % len(self.sets)
         L = self.layer
         if L.pool:
-            self.sconv.sconv_pool_forward(xs, ws, L.pool, L.stride, L.pad, L.groups, out=y)
+            self.sconv.sconv_pool_forward(xs, ws, L.pool, L.stride, L.pad, L.groups, out=y, zero_ratio=self.z)
         else:
-            self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y)
+            self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y, zero_ratio=self.z)
 
 
 def ramp_up(fn, seconds: float = 0.03) -> None:
@@ -558,18 +559,23 @@ def run_shape(args) -> None:
 
 
 def _time(fn, iters, warmup) -> float:
+    """Average duration of fn in ms: the median of five back-to-back rounds of `iters` calls (one round
+    now and then catches a stall of the machine several times the kernel's length)."""
     import torch
     ramp_up(fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        fn()
-    e1.record()
-    e1.synchronize()
-    return e0.elapsed_time(e1) / iters
+    rounds = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        e1.synchronize()
+        rounds.append(e0.elapsed_time(e1) / iters)
+    return sorted(rounds)[2]
 
 
 def run_split(args) -> None:
@@ -696,14 +702,20 @@ def run_chain(args) -> None:
     outs, recs = [], []
     flush = flush_buffer() if TUNE else None
     lend_workspace()
+    zs = []
     for layer, wd in zip(workloads.CHAIN, wds):
+        # the producer's output is probed once; tuned plans are kept per density class, so two layers of
+        # one shape (512 @14x14 twice, at 41 % and 88 % zeros) each keep their own
+        z = sconv.zero_ratio_of(sconv.sconv_density(cur)) if (TUNE or HINT) else None
+        zs.append(z)
         if TUNE:
-            sconv.sconv_tune(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=flush)
+            sconv.sconv_tune(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=flush,
+                             zero_ratio=z)
         if layer.pool:
-            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups)
+            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups, zero_ratio=z)
         else:
-            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True)
-        d = sconv.desc_for(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
+            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True, zero_ratio=z)
+        d = sconv.desc_for(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, z)
         recs.append({"layer": layer.name, "N": N, "plan": sconv.sconv_plan_name(d, bool(layer.pool)),
                      "input_zero_ratio": round(float((cur == 0).float().mean()), 4),
                      "dense_flops": 2.0 * N * layer.K * layer.OH * layer.OW * layer.Cg * 9})
@@ -715,9 +727,9 @@ def run_chain(args) -> None:
         layer = workloads.CHAIN[i]
         xi, wd, y = outs[i]
         if layer.pool:
-            sconv.sconv_pool_forward(xi, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=y)
+            sconv.sconv_pool_forward(xi, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=y, zero_ratio=zs[i])
         else:
-            sconv.sconv_forward(xi, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y)
+            sconv.sconv_forward(xi, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y, zero_ratio=zs[i])
 
     def step():
         for i in range(len(outs)):
@@ -852,7 +864,7 @@ def main() -> None:
                     help="skip sconv_tune at set-up: static dispatch rules and cost models only")
     ap.add_argument("--hint", action="store_true",
                     help="no tuning: probe every layer's input once (sconv_density) and give the static rules "
-                         "its zero ratio (sconv_set_density_hint)")
+                         "its zero ratio (SCONV_ZERO_RATIO in the descriptor's flags)")
     ap.add_argument("--pair", action="store_true",
                     help="two LeNet-shaped layers in one launch (hand-off in LDS) against two calls")
     ap.add_argument("--micro", action="store_true",

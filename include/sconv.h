@@ -38,10 +38,16 @@ typedef struct {
     int32_t stride, pad, groups; /* c_s; symmetric zero padding; groups G (C%G == K%G == 0)  */
     int32_t pool_h, pool_w, pool_stride; /* p_h, p_w, p_s; read only by the pooling calls    */
     int32_t flags;               /* SCONV_RELU: sconv_forward applies max(y, 0) before the
-                                    store (Section 5.5).  The pooling path always applies it. */
+                                    store (Section 5.5).  The pooling path always applies it.
+                                    SCONV_ZERO_RATIO(z): optional, the map's zero ratio if the
+                                    caller knows it (see sconv_density) - a hint for the choice
+                                    of kernel, never for the result.                            */
 } sconv_desc_t;
 
 enum { SCONV_RELU = 1 };
+/* Zero-ratio hint: bits 8..15 of flags hold 0 (not given) or 1 + round(254 * z), z in [0, 1]. */
+enum { SCONV_ZERO_RATIO_SHIFT = 8, SCONV_ZERO_RATIO_MASK = 0xff << 8 };
+#define SCONV_ZERO_RATIO(z) ((int32_t)((1 + (int32_t)((z) * 254.0 + 0.5)) << SCONV_ZERO_RATIO_SHIFT))
 enum { SCONV_FMT_ECR = 0, SCONV_FMT_PECR = 1 };
 enum {
     SCONV_OK = 0,
@@ -95,13 +101,16 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * pipe (groups of 6, 8, 16 and 16 elements) and skip a group only when all of its elements are zero, so a
  * zero inside a group that also holds a nonzero is multiplied (0 * w adds nothing for finite w;
  * with Inf or NaN filters the variants can differ).
- * With a workspace lent for the stream (sconv_set_workspace), a launch of fewer than 128
- * workgroups ("tap3x3" and "gen": deep layers at batch 1), a "tap3x3" launch of up to 768
- * workgroups that walks 256 or more channels, or one of 100-400 tiles of "quad3x3" on a map 28 or
- * more wide, is split along the channels over up to 16 workgroups per tile; each stores the plain partial sums of its channel range into the workspace,
- * and a second kernel on the same stream adds them in a fixed order and applies ReLU (and the
- * pooling of sconv_pool_forward).  Results stay deterministic; the association of the fp32 sums
- * differs from the unsplit kernel's.
+ * A workspace (lent with sconv_set_workspace, or passed to the ..._ws forms) is used two ways.
+ * (1) Launches too small to fill the chip - fewer than 128 workgroups ("tap3x3" and "gen": deep layers
+ * at batch 1), "tap3x3" launches of up to 768 workgroups that walk 256 or more channels, 100-400 tiles of
+ * "quad3x3" on a map 28 or more wide - are split along the channels over up to 16 workgroups per tile;
+ * each stores the plain partial sums of its channel range into the workspace, and a second kernel on the
+ * same stream adds them in a fixed order and applies bias and ReLU (and, for a fused call that small, the
+ * pooling).  (2) "tap3x3" launches of 512 or more workgroups (256 for fused calls) with 128 or more
+ * channels per group first write a transposed copy of the filters, [filter block][channel][tap][64 or 128
+ * filters], into the workspace and run the form of the kernel that reads filters from it without staging
+ * them in LDS.  Results stay deterministic; the association of the fp32 sums differs between plans.
  *   x_dev device, in : [N][C][H][W]
  *   w_dev device, in : [K][C/G][R][S]
  *   y_dev device, out: [N][K][OH][OW]
@@ -114,8 +123,9 @@ int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_d
  * Sparse convolution fused with ReLU and max pooling (Section 6, Algorithm 4): the convolution
  * results of one pooling window are reduced on chip and only the pooled tensor is stored:
  *   y[n][k][ph][pw] = max over py < p_h, px < p_w of max(0, conv[n][k][ph*p_s+py][pw*p_s+px]).
- * (A small launch that is split across workgroups - only with a workspace lent, see sconv_forward -
- * passes its partial sums through that workspace; the second kernel then pools.)
+ * (A launch too small to fill the chip - fewer than 128 workgroups, and only when a workspace is there,
+ * see sconv_forward - is split across workgroups and passes its partial sums through that workspace; the
+ * second kernel then pools.  Every larger fused call is one convolution kernel.)
  *   y_dev device, out: [N][K][PH][PW]
  * SCONV_EUNSUPPORTED if p_h*p_w > 64 or a tensor has 2^31 or more elements.
  */
@@ -172,8 +182,9 @@ int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, float* y_dev,
  * Optional workspace.  Small launches (deep layers at batch 1: a handful of tiles) run 1.3-3.5x
  * faster when the channels of a tile are split over several workgroups, whose partial sums pass
  * through device scratch to a second kernel (see sconv_forward).  That scratch is the caller's:
- *   sconv_workspace_size: bytes such a plan can use for this descriptor (0: none would; at most
- *            64 MiB).  Host only.
+ *   sconv_workspace_size: bytes the plans of this descriptor can use (0: none would; at most
+ *            64 MiB of partial sums plus, for 3x3 layers, the size of the filter tensor with the
+ *            filters of a group rounded up to a multiple of 128).  Host only.
  *   sconv_set_workspace: lends ws_dev (bytes long, 16-byte aligned) to every later forward or tuning
  *            call on hip_stream of the current device, until it is replaced or withdrawn
  *            (ws_dev NULL, bytes 0).  A launch whose plan needs more than was lent, and every
@@ -279,7 +290,7 @@ int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const f
                float* y_dev, void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms);
 
 /*
- * Density probe and hint (the cheap alternative to sconv_tune).  The zero ratio of a feature map decides
+ * Density probe (the cheap alternative to sconv_tune).  The zero ratio of a feature map decides
  * which kernel is fastest (Section 8.3 plots the method's time against it; the first layers of a network
  * are far less sparse than the deep ones, Section 8.2), and the host cannot see it.
  *   sconv_density: enqueues two small kernels on hip_stream that count, with the test of Algorithm 1's
@@ -289,18 +300,18 @@ int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const f
  *            in runs of 256 spread evenly over the tensor.  Does not synchronise; the caller reads the
  *            counts after the stream has run (zero ratio = 1 - nonzero / examined).  A producer that knows
  *            its output's zero ratio some other way needs no probe.
- *   sconv_set_density_hint: remembers zero_ratio (0..1) for this descriptor and pooled flag in a
- *            host-side table; later forward calls with an identical descriptor that sconv_tune has not
- *            tuned choose their kernel variant with it: 3x3 / stride 1 / pad 1 launches that fill the
- *            matrix kernels' tiles take the matrix kernels below 68 % zeros, the vector kernel
- *            ("tap3x3") from 68 %, and "quad3x3" again from 92 % (crossovers of the zero-ratio sweeps on
- *            independent zeros).  A negative ratio forgets the hint; sconv_tune_reset forgets all.
- *            Host only; changes process state.
+ *   The hint itself is stateless: the caller puts the ratio into the descriptor of the forward (or
+ *            tuning) call, flags |= SCONV_ZERO_RATIO(z).  With it, 3x3 / stride 1 / pad 1 launches that
+ *            fill the matrix kernels' tiles take the matrix kernels below 68 % zeros (quad3x3 in its
+ *            form without zero tests), the vector kernel ("tap3x3") from 68 %, and "quad3x3" again from
+ *            92 % (crossovers of the zero-ratio sweeps on independent zeros); plans found by sconv_tune
+ *            are kept per density class (no hint; below 55 %; 55-80 %; above), so two layers of one
+ *            shape with different densities each get their own.  Without the hint the rules assume what
+ *            the paper reports for deep layers (more than 70 % zeros, Fig. 2).
  */
 int sconv_density(const sconv_desc_t* desc, const float* x_dev, unsigned long long* counts_dev, void* hip_stream);
-int sconv_set_density_hint(const sconv_desc_t* desc, int pooled, float zero_ratio);
 
-/* Forgets every tuned plan and every density hint.  Host only. */
+/* Forgets every tuned plan.  Host only. */
 int sconv_tune_reset(void);
 
 /*

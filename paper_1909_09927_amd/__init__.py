@@ -74,13 +74,11 @@ def lib() -> ctypes.CDLL:
         L.sconv_pool_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
         L.sconv_pair_forward.argtypes = [P(Desc), P(Desc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.sconv_density.argtypes = [P(Desc), vp, vp, vp]
-        L.sconv_set_density_hint.argtypes = [P(Desc), ctypes.c_int, ctypes.c_float]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
                   "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_forward_bias",
-                  "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density",
-                  "sconv_set_density_hint"):
+                  "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -90,18 +88,28 @@ def strerror(code: int) -> str:
     return lib().sconv_strerror(code).decode()
 
 
+def zero_ratio_flag(zero_ratio: Optional[float]) -> int:
+    """SCONV_ZERO_RATIO(z): the optional density hint of a descriptor's flags (0 when None)."""
+    if zero_ratio is None:
+        return 0
+    if not 0.0 <= zero_ratio <= 1.0:
+        raise ValueError("zero_ratio must lie in [0, 1]")
+    return (1 + int(zero_ratio * 254.0 + 0.5)) << 8
+
+
 def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, groups=1, pool: Optional[Tuple[int, int, int]] = None,
-              relu: bool = False) -> Desc:
+              relu: bool = False, zero_ratio: Optional[float] = None) -> Desc:
     ph, pw, ps = pool if pool is not None else (0, 0, 0)
-    return Desc(N, C, H, W, K, R, S, stride, pad, groups, ph, pw, ps, SCONV_RELU if relu else 0)
+    return Desc(N, C, H, W, K, R, S, stride, pad, groups, ph, pw, ps,
+                (SCONV_RELU if relu else 0) | zero_ratio_flag(zero_ratio))
 
 
-def desc_for(x, w, stride=1, pad=0, groups=1, pool=None, relu=False) -> Desc:
+def desc_for(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, zero_ratio=None) -> Desc:
     N, C, H, W = x.shape
     K, Cg, R, S = w.shape
     if Cg * groups != C:
         raise ValueError("filter channel count does not match C / groups")
-    return make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, relu)
+    return make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, relu, zero_ratio)
 
 
 def sconv_output_dims(desc: Desc) -> Tuple[int, int, int, int]:
@@ -189,12 +197,6 @@ def zero_ratio_of(counts) -> float:
     return 1.0 - nonzero / max(seen, 1)
 
 
-def sconv_set_density_hint(desc: Desc, pooled: bool, zero_ratio: float) -> None:
-    rc = lib().sconv_set_density_hint(ctypes.byref(desc), 1 if pooled else 0, float(zero_ratio))
-    if rc:
-        raise SconvError(rc, "sconv_set_density_hint")
-
-
 def _ws_args(ws):
     """(pointer, bytes) of an explicit workspace: None -> (None, 0)."""
     import torch
@@ -246,14 +248,15 @@ def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None, out
 _NO_WS = object()   # "no ws argument": the plain entry point (a lent workspace applies)
 
 
-def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS, bias=None):
+def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS, bias=None, zero_ratio=None):
     """Sparse convolution; returns y[N,K,OH,OW] (device, fp32).  ws: a device tensor (or None) passed as
     this call's workspace through sconv_forward_ws; left out, sconv_forward runs.  bias: a device tensor
-    [K] added before the ReLU (sconv_forward_bias; not together with ws)."""
+    [K] added before the ReLU (sconv_forward_bias; not together with ws).  zero_ratio: the map's zero
+    ratio if known (a hint for the choice of kernel, carried in the descriptor's flags)."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
-    desc = desc_for(x, w, stride, pad, groups, None, relu)
+    desc = desc_for(x, w, stride, pad, groups, None, relu, zero_ratio)
     OH, OW, _, _ = sconv_output_dims(desc)
     if out is None:
         out = torch.empty((desc.N, desc.K, OH, OW), dtype=torch.float32, device=x.device)
@@ -347,13 +350,13 @@ def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=N
     return out
 
 
-def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS, bias=None):
+def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS, bias=None, zero_ratio=None):
     """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32).
-    ws: as in sconv_forward (sconv_pool_forward_ws)."""
+    ws, bias, zero_ratio: as in sconv_forward."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
-    desc = desc_for(x, w, stride, pad, groups, pool, True)
+    desc = desc_for(x, w, stride, pad, groups, pool, True, zero_ratio)
     _, _, PH, PW = sconv_output_dims(desc)
     if out is None:
         out = torch.empty((desc.N, desc.K, PH, PW), dtype=torch.float32, device=x.device)
@@ -378,7 +381,7 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_W
     return out
 
 
-def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None, flush=None):
+def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None, flush=None, zero_ratio=None):
     """Times every kernel variant and decomposition covering this call on x and w (synchronises)
     and makes later identical calls use the fastest.  pool=None tunes sconv_forward (with this
     relu flag), else sconv_pool_forward.  flush: a device tensor the library may overwrite to evict
@@ -388,7 +391,7 @@ def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None,
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
     pooled = pool is not None
-    desc = desc_for(x, w, stride, pad, groups, pool, True if pooled else relu)
+    desc = desc_for(x, w, stride, pad, groups, pool, True if pooled else relu, zero_ratio)
     OH, OW, PH, PW = sconv_output_dims(desc)
     shape = (desc.N, desc.K, PH, PW) if pooled else (desc.N, desc.K, OH, OW)
     if out is None:

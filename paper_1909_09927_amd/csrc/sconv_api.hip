@@ -95,7 +95,7 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     if (d->stride <= 0 || d->pad < 0 || d->groups <= 0) return SCONV_EINVAL;
     if (d->C % d->groups || d->K % d->groups) return SCONV_EINVAL;
     if (d->pad >= d->R || d->pad >= d->S) return SCONV_EINVAL;
-    if (d->flags & ~SCONV_RELU) return SCONV_EINVAL;
+    if (d->flags & ~(SCONV_RELU | SCONV_ZERO_RATIO_MASK)) return SCONV_EINVAL;
     if (d->H + 2 * (int64_t)d->pad < d->R || d->W + 2 * (int64_t)d->pad < d->S) return SCONV_EINVAL;
 
     Problem p;
@@ -112,6 +112,8 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     p.OH = (int)oh64;
     p.OW = (int)ow64;
     p.relu = (d->flags & SCONV_RELU) ? 1 : 0;
+    const int zcode = (d->flags & SCONV_ZERO_RATIO_MASK) >> SCONV_ZERO_RATIO_SHIFT;   // 0: not given
+    p.zhint = zcode ? (float)(zcode - 1) / 254.0f : -1.0f;
     if (pooled) {
         if (d->pool_h <= 0 || d->pool_w <= 0 || d->pool_stride <= 0) return SCONV_EINVAL;
         if (d->pool_h > p.OH || d->pool_w > p.OW) return SCONV_EINVAL;
@@ -152,32 +154,36 @@ struct Tuned {
     float ms;
     char name[48];
 };
-typedef std::array<int32_t, 15> TuneKey;   // the descriptor's fields and the pooled flag
+typedef std::array<int32_t, 16> TuneKey;   // the descriptor's fields, the pooled flag, the density bucket
 
 static std::mutex g_lock;                  // planning, enqueueing and the tuning cache
 static std::map<TuneKey, Tuned> g_tuned;
 
-static std::map<TuneKey, float> g_density;   // zero ratio the caller reported for a descriptor
+// Density bucket of a call: 0 = no zero ratio given, 1 = below 55 % zeros, 2 = 55-80 %, 3 = above.  Tuned
+// plans are kept per bucket, so that layers of one shape with different densities keep their own.
+static int density_bucket(const Problem& p)
+{
+    if (p.zhint < 0.0f) return 0;
+    return p.zhint < 0.55f ? 1 : (p.zhint < 0.8f ? 2 : 3);
+}
 
 static TuneKey tune_key(const Problem& p, bool pooled)
 {
     return TuneKey{p.N, p.C, p.H, p.W, p.K, p.R, p.S, p.stride, p.pad, p.G,
-                   pooled ? p.ph : 0, pooled ? p.pw : 0, pooled ? p.ps : 0, p.relu, pooled ? 1 : 0};
+                   pooled ? p.ph : 0, pooled ? p.pw : 0, pooled ? p.ps : 0, p.relu, pooled ? 1 : 0,
+                   density_bucket(p)};
 }
 
 // The tuned entry for this problem, unless SCONV_VARIANT pins the variant.  Caller holds g_lock.
-// The zero ratio reported for this problem with sconv_set_density_hint; negative when none was.
-static float density_hint(const Problem& p, bool pooled)
-{
-    if (g_density.empty()) return -1.0f;
-    auto it = g_density.find(tune_key(p, pooled));
-    return it == g_density.end() ? -1.0f : it->second;
-}
-
 static const Tuned* tuned_for(const Problem& p, bool pooled)
 {
     if (env_value("SCONV_VARIANT")) return nullptr;
     auto it = g_tuned.find(tune_key(p, pooled));
+    if (it == g_tuned.end() && p.zhint >= 0.0f) {   // nothing tuned at this density: a plan tuned without one
+        Problem q = p;
+        q.zhint = -1.0f;
+        it = g_tuned.find(tune_key(q, pooled));
+    }
     return it == g_tuned.end() ? nullptr : &it->second;
 }
 
@@ -226,7 +232,7 @@ static bool small_gen_split(const Problem& p, bool pooled, bool have_ws)
 // the vector and general kernels decide on their own).  When the choice comes with a fixed
 // decomposition, *static_pin receives it (geom[0] != 0).
 //
-// z: the map's zero ratio when the caller reported one (sconv_set_density_hint), negative when unknown.
+// z: the map's zero ratio when the caller reported one (the zero-ratio field of the descriptor's flags), negative when unknown.
 // Known, it moves 3x3 / stride 1 / pad 1 launches that fill the matrix kernels' tiles along the
 // crossovers measured on the zero-ratio sweeps (independent zeros; 896 channels in 7 groups @14x14 at
 // batch 32 and 256 channels @56x56 at batch 8): below 68 % zeros whole groups are almost never empty and
@@ -348,7 +354,7 @@ static int run(const Problem& p, bool pooled, const float* x, const float* w, fl
         if (rc != SCONV_EUNSUPPORTED) return rc;
     }
     PlanPin sp;
-    const float z = density_hint(p, pooled);
+    const float z = p.zhint;
     Variant v = choose(p, pooled, have_workspace(s), &sp, z);
     int rc = SCONV_EUNSUPPORTED;
     if (sp.geom[0]) {
@@ -464,7 +470,7 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     };
     // the static rules' own choice comes first: it stays unless something measures clearly faster
     PlanPin sp;
-    Variant v_static = choose(p, pooled, have_workspace(s), &sp, density_hint(p, pooled));
+    Variant v_static = choose(p, pooled, have_workspace(s), &sp, p.zhint);
     bool have_static = try_one(v_static, sp.geom[0] ? &sp : nullptr);
     if (!have_static && sp.geom[0]) {
         v_static = choose(p, pooled);
@@ -732,20 +738,6 @@ extern "C" int sconv_density(const sconv_desc_t* desc, const float* x_dev, unsig
     return launch_density_probe(p, x_dev, counts_dev, (hipStream_t)hip_stream);
 }
 
-extern "C" int sconv_set_density_hint(const sconv_desc_t* desc, int pooled, float zero_ratio)
-{
-    Problem p;
-    int rc = fill_problem(desc, pooled != 0, &p);
-    if (rc) return rc;
-    if (zero_ratio != zero_ratio || zero_ratio > 1.0f) return SCONV_EINVAL;
-    std::lock_guard<std::mutex> lock(g_lock);
-    if (zero_ratio < 0.0f)
-        g_density.erase(tune_key(p, pooled != 0));
-    else
-        g_density[tune_key(p, pooled != 0)] = zero_ratio;
-    return SCONV_OK;
-}
-
 extern "C" int sconv_env_refresh(void)
 {
     std::lock_guard<std::mutex> lock(g_lock);
@@ -770,7 +762,7 @@ extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled != 0)) return variant_name(t->v);
-    return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, density_hint(p, pooled != 0)));
+    return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, p.zhint));
 }
 
 extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
@@ -799,6 +791,10 @@ extern "C" int sconv_workspace_size(const sconv_desc_t* desc, int pooled, size_t
     const size_t slice = (size_t)p.N * p.K * p.OH * p.OW * sizeof(float);
     size_t need = 16 * slice;
     if (need > kSplitWorkspaceCap) need = kSplitWorkspaceCap;
+    // plus the transposed copy of the filters the vector kernel's large launches read (filters per group
+    // rounded up to whole blocks of 128)
+    if (tap_supported(p, pooled != 0))
+        need += (size_t)p.G * ((p.Kg + 127) / 128 * 128) * p.L * sizeof(float) + 256;
     *bytes = (need + 255) / 256 * 256;
     return SCONV_OK;
 }
@@ -822,7 +818,6 @@ extern "C" int sconv_tune_reset(void)
 {
     std::lock_guard<std::mutex> lock(g_lock);
     g_tuned.clear();
-    g_density.clear();
     return SCONV_OK;
 }
 
@@ -837,7 +832,7 @@ extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, 
         snprintf(out, (size_t)out_size, "%s", t->name);
         return SCONV_OK;
     }
-    const Variant v = choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, density_hint(p, pooled != 0));
+    const Variant v = choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, p.zhint);
     char detail[40];
     split_scratch_select(nullptr);   // the default stream's workspace, as for a launch there
     if (v == V_TAP && describe_tap(p, pooled != 0, nullptr, detail, sizeof(detail)))

@@ -17,6 +17,7 @@ struct Problem {
     int PH, PW;          // pooled output (0 when not pooling)
     int L;               // slots per window row = Cg*R*S
     int relu;            // apply max(.,0) before the store
+    float zhint;         // the map's zero ratio as the caller reported it in the descriptor; negative: unknown
     const float* bias;   // device, [K]: added to every result of filter k before the ReLU; null = none
 };
 

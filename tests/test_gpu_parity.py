@@ -386,23 +386,44 @@ def test_density_probe_counts_like_the_scan(device):
 @pytest.mark.parametrize("shp", [(16, 64, 28, 28, 128, 3, 3, 1, 1, 1, None), (32, 128, 14, 14, 128, 3, 3, 1, 1, 1, None),
                                  (16, 64, 28, 28, 128, 3, 3, 1, 1, 1, (2, 2, 2))])
 def test_density_hint_moves_the_static_choice_and_keeps_parity(device, shp, z_hint):
-    """A reported zero ratio selects the matrix kernels (dense maps), the vector kernel (68-88 % zeros) or
-    quad3x3 (sparser still) for launches that fill the matrix tiles; whatever runs meets the oracle's bar."""
+    """A zero ratio in the descriptor's flags selects the matrix kernels (dense maps), the vector kernel
+    (68-92 % zeros) or quad3x3 (sparser still) for launches that fill the matrix tiles; whatever runs meets
+    the oracle's bar."""
     layer, x, w = _mk(330, shp, z=z_hint if z_hint < 1 else 0.95)
     xd, wd = to_dev(x), to_dev(w)
-    d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True)
     pooled = layer.pool is not None
+    d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, zero_ratio=z_hint)
+    name = sconv.sconv_variant_name(d, pooled)
+    if 0.68 <= z_hint < 0.92:
+        assert name == "tap3x3"
+    elif not pooled:
+        assert name in ("quad3x3", "wide3x3")
+    import oracle
+    if pooled:
+        y = sconv.sconv_pool_forward(xd, wd, layer.pool, layer.stride, layer.pad, layer.groups, zero_ratio=z_hint)
+        ref, scale = oracle.conv_pool(x, w, layer.pool, layer.stride, layer.pad, layer.groups)
+    else:
+        y = sconv.sconv_forward(xd, wd, layer.stride, layer.pad, layer.groups, relu=True, zero_ratio=z_hint)
+        ref, scale = oracle.conv(x, w, layer.stride, layer.pad, layer.groups, relu=True)
+    torch.cuda.synchronize()
+    assert (np.abs(y.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
+def test_tuned_plans_are_kept_per_density_class(device):
+    """Two layers of one shape with different zero ratios (as in a chain: 512 @14x14 at 41 % and at 88 %
+    zeros) are tuned with their ratio in the descriptor and keep separate plans; a call without the hint
+    still gets the static rules."""
+    shp = (4, 128, 14, 14, 128, 3, 3, 1, 1, 1, None)
     try:
-        sconv.sconv_set_density_hint(d, pooled, z_hint)
-        name = sconv.sconv_variant_name(d, pooled)
-        if 0.68 <= z_hint < 0.88:
-            assert name == "tap3x3"
-        elif not pooled:
-            assert name in ("quad3x3", "wide3x3")
-        if pooled:
-            check_pool_forward(layer, x, w)
-        else:
-            check_forward(layer, x, w, relu=True)
+        for z in (0.3, 0.9):
+            layer, x, w = _mk(331, shp, z=z)
+            xd, wd = to_dev(x), to_dev(w)
+            sconv.sconv_tune(xd, wd, 1, 1, 1, None, relu=True, zero_ratio=z)
+        d_lo = sconv.make_desc(4, 128, 14, 14, 128, 3, 3, 1, 1, 1, None, True, zero_ratio=0.35)
+        d_hi = sconv.make_desc(4, 128, 14, 14, 128, 3, 3, 1, 1, 1, None, True, zero_ratio=0.85)
+        d_no = sconv.make_desc(4, 128, 14, 14, 128, 3, 3, 1, 1, 1, None, True)
+        assert not _untuned(sconv.sconv_plan_name(d_lo)) and not _untuned(sconv.sconv_plan_name(d_hi))
+        assert _untuned(sconv.sconv_plan_name(d_no))
     finally:
         sconv.sconv_tune_reset()
 

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
             "sconv_encode_sizes", "sconv_strerror", "sconv_variant_name", "sconv_maxpool", "sconv_tune",
             "sconv_tune_reset", "sconv_plan_name", "sconv_workspace_size", "sconv_set_workspace",
             "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_env_refresh", "sconv_clear_workspaces",
-            "sconv_forward_bias", "sconv_pool_forward_bias", "sconv_density", "sconv_set_density_hint",
+            "sconv_forward_bias", "sconv_pool_forward_bias", "sconv_density",
             "sconv_forward_static", "sconv_pair_forward"} <= names
     L = sconv.lib()
     for n in names:
@@ -188,9 +188,11 @@ def test_workspace_calls_validate_on_the_host():
     n = ctypes.c_size_t(7)
     deep = sconv.make_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)
     assert L.sconv_workspace_size(ctypes.byref(deep), 0, ctypes.byref(n)) == 0
-    assert n.value == 16 * 512 * 49 * 4          # sixteen slices of the convolution tensor
+    # sixteen slices of the convolution tensor + a transposed copy of the filters (+ 256 bytes of alignment)
+    assert n.value == 16 * 512 * 49 * 4 + 512 * 512 * 9 * 4 + 256
     big = sconv.make_desc(32, 256, 56, 56, 256, 3, 3, 1, 1)
-    assert L.sconv_workspace_size(ctypes.byref(big), 0, ctypes.byref(n)) == 0 and n.value == 64 << 20
+    assert L.sconv_workspace_size(ctypes.byref(big), 0, ctypes.byref(n)) == 0
+    assert n.value == (64 << 20) + 256 * 256 * 9 * 4 + 256     # the partial sums are capped at 64 MiB
     odd = sconv.make_desc(1, 16, 40, 40, 8, 17, 17, 1, 2)     # only the window-row kernel covers it
     assert L.sconv_workspace_size(ctypes.byref(odd), 0, ctypes.byref(n)) == 0 and n.value == 0
     assert L.sconv_workspace_size(ctypes.byref(deep), 0, None) == sconv.SCONV_EINVAL
@@ -250,15 +252,17 @@ def test_density_calls_validate_on_the_host():
     assert L.sconv_density(ctypes.byref(d), None, p, None) == sconv.SCONV_EINVAL
     assert L.sconv_density(ctypes.byref(d), p, None, None) == sconv.SCONV_EINVAL
     assert L.sconv_density(ctypes.byref(d), p, ctypes.c_void_p(4100), None) == sconv.SCONV_EINVAL   # misaligned counts
-    assert L.sconv_set_density_hint(ctypes.byref(d), 0, 1.5) == sconv.SCONV_EINVAL
-    assert L.sconv_set_density_hint(ctypes.byref(d), 0, float("nan")) == sconv.SCONV_EINVAL
-    assert L.sconv_set_density_hint(ctypes.byref(d), 1, 0.5) == sconv.SCONV_EINVAL                  # no pooling fields
     big = sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)
     assert sconv.sconv_variant_name(big) == "quad3x3"
-    assert L.sconv_set_density_hint(ctypes.byref(big), 0, 0.8) == sconv.SCONV_OK
-    assert sconv.sconv_variant_name(big) == "tap3x3"                     # the hint moved the static choice
-    assert L.sconv_set_density_hint(ctypes.byref(big), 0, -1.0) == sconv.SCONV_OK
-    assert sconv.sconv_variant_name(big) == "quad3x3"
+    hinted = sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1, zero_ratio=0.8)
+    assert hinted.flags >> 8 == 1 + 203                                  # 1 + round(254 * 0.8)
+    assert sconv.sconv_variant_name(hinted) == "tap3x3"                  # the hint moved the static choice
+    assert sconv.sconv_variant_name(sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1, zero_ratio=0.2)) == "quad3x3"
+    bad = sconv.make_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)
+    bad.flags = 1 << 16                                                  # a bit no call defines
+    assert sconv.sconv_variant_name(bad) is None
+    with pytest.raises(ValueError):
+        sconv.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1, zero_ratio=1.5)
 
 
 def test_pair_call_validates_on_the_host():
