@@ -237,7 +237,7 @@ static bool small_gen_split(const Problem& p, bool pooled, bool have_ws)
 // crossovers measured on the zero-ratio sweeps (independent zeros; 896 channels in 7 groups @14x14 at
 // batch 32 and 256 channels @56x56 at batch 8): below 68 % zeros whole groups are almost never empty and
 // the matrix kernels run at their dense rate, which the vector kernel only matches from about 68 %;
-// from 92 % the 6-element granule of quad3x3 is empty often enough to lead again.
+// from 87 % (maps up to 14 wide) or 92 % the 6-element granule of quad3x3 is empty often enough to lead again.
 static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr,
                       float z = -1.0f)
 {
@@ -272,12 +272,15 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         const long long quad_tiles_z = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
                                        p.N * p.G;
         if (z >= 0.0f && quad_tiles_z >= 400 && tap_supported(p, pooled)) {
-            if (z >= 0.92f && !(pooled && p.W <= 14)) return V_QUAD;
+            // (the 6-element granule leads again from about 87 % zeros on maps up to 14 wide - 896 channels in 7
+            // groups: 92.7 against 101 us at 90 %; 512 channels: 55 against 72 at 88 % - and from 92 % on wider ones)
+            if (z >= (p.W <= 14 ? 0.87f : 0.92f) && !(pooled && p.W <= 14)) return V_QUAD;
             if (z >= 0.68f) return V_TAP;
             // a denser map: the matrix kernels (the 16-row granule on maps up to 14 wide, else quad3x3 in
             // its form without zero tests where that form applies: below 68 % independent zeros fewer than
             // one group of six in ten is empty and the tests cost more than they save)
-            if (!pooled && p.W <= 14 && p.Kg >= 128 && wide_fills) return V_WIDE;
+            // (quad3x3 from 256 channels per group up: 512 @14x14 at 41 % zeros 92 against 118 us)
+            if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills) return V_WIDE;
             if (!(pooled && p.W <= 14)) {
                 if (static_pin && p.W > 14) snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
                 return V_QUAD;
