@@ -274,7 +274,9 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         if (z >= 0.0f && quad_tiles_z >= 400 && tap_supported(p, pooled)) {
             // (the 6-element granule leads again from about 87 % zeros on maps up to 14 wide - 896 channels in 7
             // groups: 92.7 against 101 us at 90 %; 512 channels: 55 against 72 at 88 % - and from 92 % on wider ones)
-            if (z >= (p.W <= 14 ? 0.87f : 0.92f) && !(pooled && p.W <= 14)) return V_QUAD;
+            // (only where the filters fill quad3x3's blocks of 128: 160 -> 320 @14x14 at 90 % runs 70 us there
+            // against 44 on the vector kernel)
+            if (z >= (p.W <= 14 ? 0.87f : 0.92f) && !(pooled && p.W <= 14) && p.Kg % 128 == 0) return V_QUAD;
             if (z >= 0.68f) return V_TAP;
             // a denser map: the matrix kernels (the 16-row granule on maps up to 14 wide, else quad3x3 in
             // its form without zero tests where that form applies: below 68 % independent zeros fewer than
@@ -282,7 +284,8 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
             // (quad3x3 from 256 channels per group up: 512 @14x14 at 41 % zeros 92 against 118 us)
             if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills) return V_WIDE;
             if (!(pooled && p.W <= 14)) {
-                if (static_pin && p.W > 14) snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
+                // (measured from 256 channels per group up; with 64 the 7-row tiles are three times slower)
+                if (static_pin && p.W > 14 && p.Cg >= 256) snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
                 return V_QUAD;
             }
         }

@@ -446,6 +446,7 @@ SCONV_TAPT_ADAPT(p4x14k1)
 SCONV_TAPT_ADAPT(p4x6k1)
 SCONV_TAPT_ADAPT(p4x6k2)
 SCONV_TAPT_ADAPT(p2x14k2)
+SCONV_TAPT_ADAPT(p2x14k1)
 SCONV_TAPT_ADAPT(s2_3x4k1)
 SCONV_TAPT_ADAPT(s2_3x4k2)
 
@@ -467,6 +468,7 @@ const Candidate kCandidates[] = {
     {"p4x6k1t", plan_t_p4x6k1, launch_t_p4x6k1, true, 1, 0, 0, 1, false},
     {"p4x6k2t", plan_t_p4x6k2, launch_t_p4x6k2, true, 2, 0, 0, 1, false},
     {"p2x14k2t", plan_t_p2x14k2, launch_t_p2x14k2, true, 2, 0, 14, 1, false},
+    {"p2x14k1t", plan_t_p2x14k1, launch_t_p2x14k1, true, 1, 0, 14, 1, false},
     {"s2-3x4k1t", plan_t_s2_3x4k1, launch_t_s2_3x4k1, false, 1, 0, 0, 2, false},
     {"s2-3x4k2t", plan_t_s2_3x4k2, launch_t_s2_3x4k2, false, 2, 0, 0, 2, false},
     {"s2-3x4k1", plan_geom<S34_1>, launch_plan<S34_1>, false, 1, 0, 0, 2, true},
@@ -479,7 +481,7 @@ const char* const* tap_geoms()
 {
     static const char* const names[] = {"5x7k1", "5x7k2", "7x7k1", "7x7k2", "p4x14k1", "p4x14k2", "p4x6k1", "p4x6k2",
                                         "s2-3x4k1", "s2-3x4k2", "5x7k1t", "5x7k1tn", "5x7k2t", "7x7k1t", "7x7k2t", "p4x14k1t", "p4x6k1t",
-                                        "p4x6k2t", "p2x14k2t", "s2-3x4k1t", "s2-3x4k2t", nullptr};
+                                        "p4x6k2t", "p2x14k2t", "p2x14k1t", "s2-3x4k1t", "s2-3x4k2t", nullptr};
     return names;
 }
 

@@ -25,6 +25,7 @@ SCONV_TAPT_DECLARE(p4x14k1)
 SCONV_TAPT_DECLARE(p4x6k1)
 SCONV_TAPT_DECLARE(p4x6k2)
 SCONV_TAPT_DECLARE(p2x14k2)
+SCONV_TAPT_DECLARE(p2x14k1)
 SCONV_TAPT_DECLARE(s2_3x4k1)
 SCONV_TAPT_DECLARE(s2_3x4k2)
 

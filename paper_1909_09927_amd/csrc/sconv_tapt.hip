@@ -333,6 +333,7 @@ SCONV_TAPT_INSTANCE(p4x14k1, 1, 4, 14, 1, 0, true)
 SCONV_TAPT_INSTANCE(p4x6k1, 1, 4, 6, 1, 1, true)
 SCONV_TAPT_INSTANCE(p4x6k2, 2, 4, 6, 1, 1, true)
 SCONV_TAPT_INSTANCE(p2x14k2, 2, 2, 14, 1, 0, true)
+SCONV_TAPT_INSTANCE(p2x14k1, 1, 2, 14, 1, 0, true)
 SCONV_TAPT_INSTANCE(s2_3x4k1, 1, 3, 4, 1, 1, false, 2)
 SCONV_TAPT_INSTANCE(s2_3x4k2, 2, 3, 4, 1, 1, false, 2)
 
