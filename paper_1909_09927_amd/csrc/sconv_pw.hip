@@ -205,6 +205,11 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
         }
     }
     // epilogue: lane owns filter kb0 + lane; accumulator quad b, element e = tile position 4b + e
+    if (p.bias) {   // (a branch of its own: without a bias the epilogue is exactly the plain one)
+        const float bk = lane < kvalid ? p.bias[(size_t)g * p.Kg + kb0 + lane] : 0.0f;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[b] += bk;
+    }
     if (!POOL) {
         const size_t kglob0 = (size_t)g * p.Kg + kb0;
         if ((HWp % 4) == 0) {
@@ -215,10 +220,9 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
             __syncthreads();   // every wavefront is done with the filter buffers
             if (cs != 0 || !tile_ok) return;
             float* tr = lds + ts * (64 * 36);
-            const float bk = lane < kvalid ? bias_of(p, kglob0 + lane) : 0.0f;
 #pragma unroll
             for (int b = 0; b < 8; ++b) {
-                v4f v = acc[b] + bk;
+                v4f v = acc[b];
                 if (p.relu) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
@@ -242,12 +246,11 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
         }
         if (cs != 0 || !tile_ok || lane >= kvalid) return;
         const size_t kglob = kglob0 + lane;
-        const float bk = bias_of(p, kglob);
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
             const int P0 = p0 + 4 * b;     // uniform
             if (P0 >= cfg.npos) break;
-            v4f v = acc[b] + bk;
+            v4f v = acc[b];
             if (p.relu) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
@@ -266,7 +269,6 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
         // pooled output (oh0/2, ow0/2 + pc), pc < 7: columns 2pc, 2pc+1 of rows 0 and 1
         const int plane = p.PH * p.PW;
         const int phh = oh0 / 2;
-        const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + lane);
         if (phh < p.PH) {
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + lane) * plane + phh * p.PW + ow0 / 2;
 #pragma unroll
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(6, 8))
                 if (ow0 / 2 + pc < p.PW) {
                     const int b = (2 * pc) / 4, e = (2 * pc) % 4;   // e is 0 or 2
                     const float m = fmaxf(fmaxf(acc[b][e], acc[b][e + 1]), fmaxf(acc[4 + b][e], acc[4 + b][e + 1]));
-                    yk[pc] = fmaxf(m + bk, 0.0f);
+                    yk[pc] = fmaxf(m, 0.0f);
                 }
             }
         }

@@ -269,6 +269,15 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
         }
     }
     // epilogue: lane owns filters kb0 + lane + 64*i; accumulator (row, quad, e) = output column 4*quad + e
+    if (p.bias) {   // (a branch of its own: without a bias the epilogue is exactly the plain one)
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            const float bk = k < kvalid ? p.bias[(size_t)g * p.Kg + kb0 + k] : 0.0f;
+#pragma unroll
+            for (int a = 0; a < G::ACC / 4; ++a) acc[i][a] += bk;
+        }
+    }
     if (!G::POOL && cfg.tr) {
         // Stored from the accumulator layout, every lane of a store would go to a different
         // output plane, four bytes each.  Instead each output row of the tile is transposed
@@ -286,14 +295,13 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
         for (int i = 0; i < G::KPL; ++i) {
             const int kleft = kvalid - 64 * i;     // filters of this register that exist
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + 64 * i) * plane;
-            const float bk = lane < kleft ? bias_of(p, (size_t)g * p.Kg + kb0 + 64 * i + lane) : 0.0f;
 #pragma unroll
             for (int orow = 0; orow < G::TH; ++orow) {
                 const int oh = oh0 + orow;         // uniform
                 if (oh >= p.OH) break;
 #pragma unroll
                 for (int q = 0; q < G::NQ; ++q) {
-                    v4f v = acc[i][orow * G::NQ + q] + bk;
+                    v4f v = acc[i][orow * G::NQ + q];
                     if (p.relu) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
@@ -319,14 +327,13 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
-            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < G::ACC; ++a) {
                 const int orow = a / (4 * G::NQ), ocol = a % (4 * G::NQ);
                 if (ocol >= G::TW) continue;
                 const int oh = oh0 + orow, ow = ow0 + ocol;
                 if (oh < p.OH && ow < p.OW) {
-                    float v = acc[i][a / 4][a % 4] + bk;
+                    float v = acc[i][a / 4][a % 4];
                     if (p.relu) v = fmaxf(v, 0.0f);
                     yk[oh * p.OW + ow] = v;
                 }
@@ -340,7 +347,6 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
-            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < (G::TH / 2) * (G::TW / 2); ++a) {
                 const int pr = a / (G::TW / 2), pc = a % (G::TW / 2);
@@ -349,7 +355,7 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
                     const int q0 = (2 * pr) * G::NQ + (2 * pc) / 4, e = (2 * pc) % 4;   // e is 0 or 2
                     float m = fmaxf(fmaxf(acc[i][q0][e], acc[i][q0][e + 1]),
                                     fmaxf(acc[i][q0 + G::NQ][e], acc[i][q0 + G::NQ][e + 1]));
-                    yk[phh * p.PW + pww] = fmaxf(m + bk, 0.0f);
+                    yk[phh * p.PW + pww] = fmaxf(m, 0.0f);
                 }
             }
         }

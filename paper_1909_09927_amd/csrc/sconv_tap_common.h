@@ -102,6 +102,15 @@ template <class G>
 __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL][G::ACC], float* __restrict__ y,
                                            int ss, int n, int g, int kb0, int kvalid, int oh0, int ow0, int lane)
 {
+    if (p.bias) {   // (a branch of its own: without a bias the epilogue is exactly the plain one)
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int k = lane + 64 * i;
+            const float bk = k < kvalid ? p.bias[(size_t)g * p.Kg + kb0 + k] : 0.0f;
+#pragma unroll
+            for (int a = 0; a < G::ACC; ++a) acc[i][a] += bk;
+        }
+    }
     if (!G::POOL) {
         const int plane = p.OH * p.OW;
         y += (size_t)ss * p.N * p.K * plane;       // split: slice ss of the partial sums (p.relu is off)
@@ -110,12 +119,11 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
-            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < G::ACC; ++a) {
                 const int oh = oh0 + a / G::TW, ow = ow0 + a % G::TW;
                 if (oh < p.OH && ow < p.OW) {
-                    float v = acc[i][a] + bk;
+                    float v = acc[i][a];
                     if (p.relu) v = fmaxf(v, 0.0f);
                     yk[oh * p.OW + ow] = v;
                 }
@@ -129,7 +137,6 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
             const int k = lane + 64 * i;
             if (k >= kvalid) continue;
             float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + k) * plane;
-            const float bk = bias_of(p, (size_t)g * p.Kg + kb0 + k);
 #pragma unroll
             for (int a = 0; a < (G::TH / 2) * (G::TW / 2); ++a) {
                 const int pr = a / (G::TW / 2), pc = a % (G::TW / 2);
@@ -138,7 +145,7 @@ __device__ __forceinline__ void store_tile(const Problem& p, float (&acc)[G::KPL
                     const int b = (2 * pr) * G::TW + 2 * pc;
                     float m = fmaxf(fmaxf(acc[i][b], acc[i][b + 1]),
                                     fmaxf(acc[i][b + G::TW], acc[i][b + G::TW + 1]));
-                    yk[phh * p.PW + pww] = fmaxf(m + bk, 0.0f);
+                    yk[phh * p.PW + pww] = fmaxf(m, 0.0f);
                 }
             }
         }

@@ -103,6 +103,19 @@ __device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg
     // epilogue: element (q, 4*b + e) of the lane = filter 16*b + lane%16, window row
     // 64*tile + 16*q + 4*(lane/16) + e
     const int kf = lane & 15, rg = lane >> 4;
+    if (p.bias) {   // (a branch of its own: without a bias the epilogue is exactly the plain one)
+#pragma unroll
+        for (int i = 0; i < KPL; ++i)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int k = 64 * i + 16 * b + kf;
+                const float bk = k < kvalid ? p.bias[(size_t)g * p.Kg + kb0 + k] : 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][q][4 * b + e] += bk;
+            }
+    }
 #pragma unroll
     for (int i = 0; i < KPL; ++i) {
 #pragma unroll
@@ -110,13 +123,12 @@ __device__ __forceinline__ void finish_tile(const Problem& p, const WideCfg& cfg
             const int k = 64 * i + 16 * b + kf;
             if (k >= kvalid) continue;
             const size_t kglob = (size_t)g * p.Kg + kb0 + k;
-            const float bk = bias_of(p, kglob);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int P0 = tile * 64 + 16 * q + 4 * rg;
                 if (cs != q / bps || P0 >= cfg.npos) continue;
-                float v0 = acc[i][q][4 * b] + bk, v1 = acc[i][q][4 * b + 1] + bk, v2 = acc[i][q][4 * b + 2] + bk,
-                      v3 = acc[i][q][4 * b + 3] + bk;
+                float v0 = acc[i][q][4 * b], v1 = acc[i][q][4 * b + 1], v2 = acc[i][q][4 * b + 2],
+                      v3 = acc[i][q][4 * b + 3];
                 if (POOL) {
                     // four rows of one pooling window: ReLU, maximum, one pooled result
                     const int pp = P0 >> 2;
