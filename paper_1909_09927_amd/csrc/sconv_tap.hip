@@ -447,6 +447,8 @@ SCONV_TAPT_ADAPT(p4x6k1)
 SCONV_TAPT_ADAPT(p4x6k2)
 SCONV_TAPT_ADAPT(p2x14k2)
 SCONV_TAPT_ADAPT(p2x14k1)
+SCONV_TAPT_ADAPT(p2x14hk1)
+SCONV_TAPT_ADAPT(p2x14hk2)
 SCONV_TAPT_ADAPT(s2_3x4k1)
 SCONV_TAPT_ADAPT(s2_3x4k2)
 
@@ -469,6 +471,8 @@ const Candidate kCandidates[] = {
     {"p4x6k2t", plan_t_p4x6k2, launch_t_p4x6k2, true, 2, 0, 0, 1, false},
     {"p2x14k2t", plan_t_p2x14k2, launch_t_p2x14k2, true, 2, 0, 14, 1, false},
     {"p2x14k1t", plan_t_p2x14k1, launch_t_p2x14k1, true, 1, 0, 14, 1, false},
+    {"p2x14hk1t", plan_t_p2x14hk1, launch_t_p2x14hk1, true, 1, 0, 0, 1, false},
+    {"p2x14hk2t", plan_t_p2x14hk2, launch_t_p2x14hk2, true, 2, 0, 0, 1, false},
     {"s2-3x4k1t", plan_t_s2_3x4k1, launch_t_s2_3x4k1, false, 1, 0, 0, 2, false},
     {"s2-3x4k2t", plan_t_s2_3x4k2, launch_t_s2_3x4k2, false, 2, 0, 0, 2, false},
     {"s2-3x4k1", plan_geom<S34_1>, launch_plan<S34_1>, false, 1, 0, 0, 2, true},
@@ -481,7 +485,7 @@ const char* const* tap_geoms()
 {
     static const char* const names[] = {"5x7k1", "5x7k2", "7x7k1", "7x7k2", "p4x14k1", "p4x14k2", "p4x6k1", "p4x6k2",
                                         "s2-3x4k1", "s2-3x4k2", "5x7k1t", "5x7k1tn", "5x7k2t", "7x7k1t", "7x7k2t", "p4x14k1t", "p4x6k1t",
-                                        "p4x6k2t", "p2x14k2t", "p2x14k1t", "s2-3x4k1t", "s2-3x4k2t", nullptr};
+                                        "p4x6k2t", "p2x14k2t", "p2x14k1t", "p2x14hk1t", "p2x14hk2t", "s2-3x4k1t", "s2-3x4k2t", nullptr};
     return names;
 }
 
@@ -503,7 +507,9 @@ const Candidate* select_tap(const Problem& p, bool pooled, hipStream_t stream, P
     // with 128 or more channels per group tried (512 @28x28 batch 8: 231 -> 210 us; 512 @14x14 batch 32:
     // 190 -> 168; 256 @14x14 batch 32: 63 -> 55; 896 in 7 groups @14x14 batch 32: 130 -> 126), and its
     // pooled tiles beat both the staged pooled tiles and the split plain tiles (512 @14x14 + pooling at
-    // batch 8: 61 against 71 and 65 us).
+    // batch 8: 61 against 71 and 65 us; on wider maps 2x14 pooled tiles with a column halo - 64 input
+    // positions, one register - : 512 @28x28 + pooling at batch 8 202 us, 256 @28x28 at batch 16 124, 128 @56x56
+    // at batch 8 71, against 257, 146 and 78 on the matrix kernel's pooled tiles).
     int dn = 0, dc = 0, ds = 0;
     pinned_split("SCONV_TAP_SPLIT", &dn, &dc, &ds);
     if (!pin && !dn && can_split && p.stride == 1 && p.Cg >= 128 && (p.H > 7 || p.W > 7)) {
@@ -512,7 +518,7 @@ const Candidate* select_tap(const Problem& p, bool pooled, hipStream_t stream, P
         if (tile_wgs >= (pooled ? 256 : 512))   // (pooled: measured from 384 up)
             // (below about 85 % zeros the test of four positions at once rarely spares the four single
             // tests: the form without it measures 2-4 % faster when the caller reported such a ratio)
-            want = !pooled ? (p.zhint >= 0.0f && p.zhint < 0.85f ? "5x7k1tn" : "5x7k1t") : (p.W == 14 ? (p.Kg >= 128 ? "p2x14k2t" : "p4x14k1t") : "p4x6k1t");
+            want = !pooled ? (p.zhint >= 0.0f && p.zhint < 0.85f ? "5x7k1tn" : "5x7k1t") : (p.W == 14 ? (p.Kg >= 128 ? "p2x14k2t" : "p4x14k1t") : "p2x14hk1t");
         for (const Candidate& c : kCandidates) {
             if (!want || strcmp(want, c.name) != 0) continue;
             const Plan pl = c.plan(p, 0);

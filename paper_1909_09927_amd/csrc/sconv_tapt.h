@@ -26,6 +26,8 @@ SCONV_TAPT_DECLARE(p4x6k1)
 SCONV_TAPT_DECLARE(p4x6k2)
 SCONV_TAPT_DECLARE(p2x14k2)
 SCONV_TAPT_DECLARE(p2x14k1)
+SCONV_TAPT_DECLARE(p2x14hk1)
+SCONV_TAPT_DECLARE(p2x14hk2)
 SCONV_TAPT_DECLARE(s2_3x4k1)
 SCONV_TAPT_DECLARE(s2_3x4k2)
 

@@ -223,11 +223,11 @@ Plan plan_tapt(const Problem& p, int split)
     if (!pin_nwv) {
         // Measured (sconv_tune's picks on 128- to 512-channel layers): eight channel slices whenever a slice
         // keeps 16 channels - many short wavefronts even out the last round -, one tile per workgroup,
-        // two from 512 channels up; pooled tiles of 14-wide maps, few per image, sixteen slices.
+        // two from 512 channels up (plain tiles only); pooled tiles of 14-wide maps, few per image, sixteen slices.
         ncs = 1;
         const int want = (G::POOL && G::HW == 0) ? 16 : 8;
         while (ncs < want && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
-        nwv = (p.Cg >= 512 || ncs == 16) && G::MAXW == 16 ? 16 : 8;
+        nwv = ((p.Cg >= 512 && !G::POOL) || ncs == 16) && G::MAXW == 16 ? 16 : 8;
         if (ncs > nwv) ncs = nwv;
         if (split == 2) nss = 2;
         // (small launches: the channels of a tile over several workgroups as well)
@@ -334,6 +334,8 @@ SCONV_TAPT_INSTANCE(p4x6k1, 1, 4, 6, 1, 1, true)
 SCONV_TAPT_INSTANCE(p4x6k2, 2, 4, 6, 1, 1, true)
 SCONV_TAPT_INSTANCE(p2x14k2, 2, 2, 14, 1, 0, true)
 SCONV_TAPT_INSTANCE(p2x14k1, 1, 2, 14, 1, 0, true)
+SCONV_TAPT_INSTANCE(p2x14hk1, 1, 2, 14, 1, 1, true)
+SCONV_TAPT_INSTANCE(p2x14hk2, 2, 2, 14, 1, 1, true)
 SCONV_TAPT_INSTANCE(s2_3x4k1, 1, 3, 4, 1, 1, false, 2)
 SCONV_TAPT_INSTANCE(s2_3x4k2, 2, 3, 4, 1, 1, false, 2)
 

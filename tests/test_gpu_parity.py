@@ -260,7 +260,8 @@ def test_fused_pooling_with_and_without_a_workspace(device, shp, ws):
 @pytest.mark.parametrize("geom,split", [("p4x14k1", "16,16"), ("p4x14k1", "8,2"), ("p4x14k2", "8,4"), ("p4x6k1", "16,8"),
                                         ("p4x6k2", "8,8"), ("p4x14k1t", "16,16"), ("p4x14k1t", "8,1"),
                                         ("p4x6k1t", "16,4"), ("p4x6k2t", "8,8"), ("p2x14k2t", "16,16"),
-                                        ("p2x14k2t", "8,2")])
+                                        ("p2x14k2t", "8,2"), ("p2x14k1t", "16,8"), ("p2x14hk1t", "8,8"), ("p2x14hk1t", "16,2"),
+                                        ("p2x14hk2t", "8,4")])
 @pytest.mark.parametrize("shp", POOLED_DEEP)
 def test_pooled_tile_geometries_of_the_element_stationary_kernels(device, monkeypatch, shp, geom, split):
     """One kernel computes convolution, ReLU and pooling (no split: the pinned decomposition has one
