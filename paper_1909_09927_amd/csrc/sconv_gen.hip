@@ -399,7 +399,9 @@ Plan plan_geom(const Problem& p, int split)
         // down to one chunk per workgroup (measured on 1x1 832->256 @7x7: 8 ways 14.4 us, 4 ways
         // 17.0); two chunks when the adding kernel also pools (it reads every part of a window:
         // 512->256 @28x28 + pool 15.6 against 19.7 us)
-        const int keep = split == 2 ? 4 : 2;
+        // (kernels of 3x3 and more: two chunks, sconv_tune's pick on four batch-1 layers - 3x3 128 stride 2
+        // @56x56 17.1 against 19.7 us, 160->320 @14x14 16.2 against 18.9)
+        const int keep = (split == 2 || p.R * p.S >= 9) ? 4 : 2;
         while (want < 16 && best.wgs1 * want < 256 && want * keep <= nchunks) want *= 2;
         if (want > 1 && !split_fits(want)) want = 1;
         if (want == 1 && split == 2) return Plan();
