@@ -248,11 +248,15 @@ int sconv_forward_static(const sconv_desc_t* desc, const float* x_dev, const flo
  * more filters and fewer than 256 channels per group), "tap3x3" (3x3 / pad 1, stride 1 or 2,
  * channels a multiple of 16; preferred for the deep layers - maps up to 14 wide with 256 or more
  * channels per group, maps up to 28 wide with 512 or more - and for launches too small to fill the
- * matrix kernels' tiles; when a workspace is lent on a stream of the current device, launches of
- * 100-400 "quad3x3" tiles on maps 28 or more wide are "quad3x3", split, instead),
+ * matrix kernels' tiles; with a workspace lent on a stream of the current device also for fused calls
+ * on wider maps with 128 or more channels per group, while launches of 100-400 "quad3x3" tiles on maps
+ * 28 or more wide are then "quad3x3", split, instead),
  * "gen" (every other shape with a kernel of at most 15x15; any pooling window of up to 64
- * results; also 1x1 layers of 512 or more channels per group and few tiles, which it splits
- * across workgroups), "rows" (everything else).  The environment variable SCONV_VARIANT ("rows", "tap",
+ * results; also, for its split across workgroups, 1x1 layers of 512 or more channels per group and few
+ * tiles and - with a workspace - 3x3 launches of fewer than 128 tile-workgroups with 64-160 channels per
+ * group), "rows" (everything else).  A zero ratio in the descriptor's flags (SCONV_ZERO_RATIO) moves
+ * the choice among "quad3x3", "wide3x3" and "tap3x3" for launches that fill the matrix kernels' tiles
+ * (see sconv_density).  The environment variable SCONV_VARIANT ("rows", "tap",
  * "quad", "wide", "gen" or unset) pins the choice for profiling; a plan remembered by sconv_tune comes
  * before the static rules.
  * Returns NULL for an invalid descriptor.  Nothing is enqueued, but the call asks the HIP runtime for
