@@ -813,6 +813,64 @@ def run_micro(args) -> None:
         print(json.dumps(rec), flush=True)
 
 
+def run_variants(args) -> None:
+    """How well the static choice of kernel generalises: --count random 3x3 / stride 1 / pad 1 layers that
+    are not benchmark shapes (64-512 channels and filters, maps 7-56 wide, batch 2-32, 40-90 % independent
+    zeros, a quarter of them with fused 2x2/2 pooling, 3-120 dense GFLOP), each timed with the static
+    choice (zero ratio in the descriptor with --hint, unknown without) and with every 3x3 variant pinned
+    (that variant's own static plan).  One JSON line per shape, then a summary of default / best variant."""
+    import torch
+    import paper_1909_09927_amd as sconv
+    global TUNE, HINT
+    TUNE = False
+    rng = np.random.default_rng(args.seed)
+    shapes = []
+    while len(shapes) < args.count:
+        C = int(rng.choice([64, 96, 128, 192, 256, 384, 512]))
+        K = int(rng.choice([64, 128, 192, 256, 384, 512]))
+        H = int(rng.choice([7, 10, 14, 20, 28, 40, 56]))
+        W = H if rng.random() < 0.7 else int(rng.choice([7, 14, 28, 56]))
+        N = int(rng.choice([2, 4, 8, 16, 32]))
+        z = float(rng.choice([0.4, 0.5, 0.6, 0.7, 0.8, 0.9]))
+        pool = (2, 2, 2) if rng.random() < 0.25 else None
+        dense = 2.0 * N * K * H * W * C * 9
+        if N * C * H * W * 4 > 400e6 or dense > 1.2e11 or dense < 3e9:
+            continue
+        shapes.append((N, C, H, W, K, pool, z))
+    ratios = []
+    for N, C, H, W, K, pool, z in shapes:
+        layer = workloads.Layer(f"rand-{C}to{K}x{H}x{W}" + ("-pool" if pool else ""), C=C, H=H, W=W, K=K, R=3, S=3,
+                                stride=1, pad=1, groups=1, pool=pool, zero_ratio=z)
+        r2 = np.random.default_rng(1234)
+        x = workloads.make_feature_map(r2, N, layer)
+        w = workloads.make_filters(r2, layer)
+        wk = layer_work(layer, N, x)
+        rec = {"shape": [N, C, H, W, K], "pool": bool(pool), "zero_ratio": z}
+        for var in (None, "tap", "quad", "wide"):
+            if var:
+                os.environ["SCONV_VARIANT"] = var
+            else:
+                os.environ.pop("SCONV_VARIANT", None)
+            sconv.sconv_env_refresh()
+            dl = DeviceLayer(layer, N, x, w, copies_for([wk]))
+            if var is None or dl.variant.startswith(var):
+                rec[(var or "default") + "_us"] = round(time_layer(dl, 40, 5) * 1e3, 1)
+                if var is None:
+                    rec["default_plan"] = dl.plan
+            del dl
+            torch.cuda.empty_cache()
+        os.environ.pop("SCONV_VARIANT", None)
+        sconv.sconv_env_refresh()
+        best = min(rec[k] for k in ("tap_us", "quad_us", "wide_us") if k in rec)
+        rec["default_over_best_variant"] = round(rec["default_us"] / best, 3)
+        ratios.append(rec["default_over_best_variant"])
+        print(json.dumps(rec), flush=True)
+    print(json.dumps({"shapes": len(ratios), "hint": HINT, "seed": args.seed,
+                      "mean_default_over_best": round(float(np.mean(ratios)), 3),
+                      "worst_default_over_best": round(float(np.max(ratios)), 3),
+                      "within_1.1": int(sum(r <= 1.1 for r in ratios))}), flush=True)
+
+
 def run_pair(args) -> None:
     """The single-workgroup hand-off of Section 6.4 on a LeNet-shaped pair (5x5 1->20 on 28x28 + 2x2/2
     pooling, then 5x5 20->50 + pooling): one launch with the intermediate map in LDS, next to the two fused
@@ -884,6 +942,10 @@ def main() -> None:
     ap.add_argument("--hint", action="store_true",
                     help="no tuning: probe every layer's input once (sconv_density) and give the static rules "
                          "its zero ratio (SCONV_ZERO_RATIO in the descriptor's flags)")
+    ap.add_argument("--variants", action="store_true",
+                    help="random 3x3 shapes outside the benchmark set: the static choice against every pinned variant")
+    ap.add_argument("--seed", type=int, default=23, help="--variants: seed of the shape draw")
+    ap.add_argument("--count", type=int, default=40, help="--variants: number of shapes")
     ap.add_argument("--pair", action="store_true",
                     help="two LeNet-shaped layers in one launch (hand-off in LDS) against two calls")
     ap.add_argument("--micro", action="store_true",
@@ -915,6 +977,8 @@ def main() -> None:
         run_micro(args)
     elif args.pair:
         run_pair(args)
+    elif args.variants:
+        run_variants(args)
     elif args.shape:
         run_shape(args)
     elif args.sweep:

@@ -306,10 +306,11 @@ int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_dev, const f
  *            its output's zero ratio some other way needs no probe.
  *   The hint itself is stateless: the caller puts the ratio into the descriptor of the forward (or
  *            tuning) call, flags |= SCONV_ZERO_RATIO(z).  With it, 3x3 / stride 1 / pad 1 launches that
- *            fill the matrix kernels' tiles take the matrix kernels below 68 % zeros (quad3x3 in its
- *            form without zero tests), the vector kernel ("tap3x3") from 68 %, and "quad3x3" again from
- *            87 % (maps up to 14 wide) or 92 % (crossovers of the zero-ratio sweeps on independent
- *            zeros); plans found by sconv_tune
+ *            fill the matrix kernels' tiles take, below 68 % zeros, the matrix kernel whose tiles fit
+ *            the map ("quad3x3" on maps wider than 16 whose width fills its 28-column tiles, "wide3x3"
+ *            up to 60 % on the others) or else the vector kernel, the vector kernel ("tap3x3") from
+ *            68 %, and "quad3x3" again from 92 % (crossovers of the zero-ratio sweeps on independent
+ *            zeros and of 80 random shapes with each variant pinned); plans found by sconv_tune
  *            are kept per density class (no hint; below 55 %; 55-80 %; above), so two layers of one
  *            shape with different densities each get their own.  Without the hint the rules assume what
  *            the paper reports for deep layers (more than 70 % zeros, Fig. 2).

@@ -237,7 +237,7 @@ static bool small_gen_split(const Problem& p, bool pooled, bool have_ws)
 // crossovers measured on the zero-ratio sweeps (independent zeros; 896 channels in 7 groups @14x14 at
 // batch 32 and 256 channels @56x56 at batch 8): below 68 % zeros whole groups are almost never empty and
 // the matrix kernels run at their dense rate, which the vector kernel only matches from about 68 %;
-// from 87 % (maps up to 14 wide) or 92 % the 6-element granule of quad3x3 is empty often enough to lead again.
+// from 92 % the 6-element granule of quad3x3 is empty often enough to lead again.
 static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr,
                       float z = -1.0f)
 {
@@ -272,22 +272,35 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         const long long quad_tiles_z = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
                                        p.N * p.G;
         if (z >= 0.0f && quad_tiles_z >= 400 && tap_supported(p, pooled)) {
-            // (the 6-element granule leads again from about 87 % zeros on maps up to 14 wide - 896 channels in 7
-            // groups: 92.7 against 101 us at 90 %; 512 channels: 55 against 72 at 88 % - and from 92 % on wider ones)
-            // (only where the filters fill quad3x3's blocks of 128: 160 -> 320 @14x14 at 90 % runs 70 us there
-            // against 44 on the vector kernel)
-            if (z >= (p.W <= 14 ? 0.87f : 0.92f) && !(pooled && p.W <= 14) && p.Kg % 128 == 0) return V_QUAD;
+            // (the 6-element granule leads again from about 92 % zeros, where the filters fill quad3x3's blocks
+            // of 128; between 87 and 92 % it is ahead on some 14-wide maps - 512 channels at 88 %: 55 against 72 us -
+            // and far behind on others - 384 -> 128 @40x14 at 90 %: 156 against 91 -, so the vector kernel keeps those)
+            if (z >= 0.92f && !(pooled && p.W <= 14) && p.Kg % 128 == 0) return V_QUAD;
             if (z >= 0.68f) return V_TAP;
-            // a denser map: the matrix kernels (the 16-row granule on maps up to 14 wide, else quad3x3 in
-            // its form without zero tests where that form applies: below 68 % independent zeros fewer than
-            // one group of six in ten is empty and the tests cost more than they save)
-            // (quad3x3 from 256 channels per group up: 512 @14x14 at 41 % zeros 92 against 118 us)
-            if (!pooled && p.W <= 14 && p.Kg >= 128 && p.Cg < 256 && wide_fills) return V_WIDE;
-            if (!(pooled && p.W <= 14)) {
-                // (measured from 256 channels per group up; with 64 the 7-row tiles are three times slower)
-                if (static_pin && p.W > 14 && p.Cg >= 256) snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
+            // A denser map.  Below 68 % independent zeros fewer than one group of six in ten is empty: the
+            // matrix kernels run at their dense rate, but only where their tiles fit the map.  quad3x3's
+            // tiles are 28 columns wide (16 on maps up to 16 wide); measured on 40 random shapes with each
+            // variant pinned: on maps wider than 16 whose width fills the 28-column tiles it leads (256 @56x56,
+            // 512 @28x28 at 40-60 % zeros: 1.07-1.3x ahead of the vector kernel); on badly filling widths
+            // (20: 246 us against 149 on the 16-row granule and 180 on the vector kernel; 40: 141 against 87)
+            // and on maps up to 16 wide it does not: there the 16-row granule (up to 60 % zeros, fewer than 256
+            // channels per group on the small maps) or the vector kernel (512 @14x14 at 50 %: 98 against 118 on
+            // quad3x3 and 124 on wide3x3; quad3x3 only below 45 %: 88 against 117 at 41 %).
+            const double fitw = p.W > 16 ? (double)((p.OW + 27) / 28 * 28) / p.OW : 16.0 / p.OW;
+            if (p.W > 16 && fitw <= 1.15 && !(pooled && p.W <= 14)) {
+                // the form without zero tests, from 256 channels per group up and where its 7-row tiles make
+                // 512 or more tile-wavefronts (256 @56x56 at batch 8: 247 against 263 us; with 64 channels
+                // or 128 tile-wavefronts it is 1.6-3x slower than the model's own tiles)
+                const long long t7 = (long long)((p.OH + 6) / 7) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) * p.N * p.G;
+                // (and only on maps its tiles divide: 384 channels @40x56 ran 605 against 417 us with it)
+                if (static_pin && (p.Cg == 256 || p.Cg == 512) && t7 >= 512 && p.OH % 7 == 0 && p.OW % 28 == 0)
+                    snprintf(static_pin->geom, sizeof(static_pin->geom), "q32t7d");
                 return V_QUAD;
             }
+            if (p.W <= 7) return V_TAP;   // (no column halo on such maps: 128 -> 512 @20x7 at 60 % 57 against 76 on wide3x3)
+            if (p.W <= 16 && p.Cg >= 256 && z < 0.45f && !pooled) return V_QUAD;
+            if (z <= 0.6f && (p.W > 16 || p.Cg < 256) && p.Kg >= 128 && wide_fills) return V_WIDE;
+            if (p.Cg >= 128) return V_TAP;
         }
         // Maps up to 14 wide with 256 or more channels per group are the deep layers, whose zero
         // ratio the paper puts above 0.7 (Fig. 2): there per-element skipping on the vector pipe
@@ -315,6 +328,13 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // filters: the vector kernel's 2x14 pooled tiles measure 1.1-1.27x faster than the matrix kernel's at
         // 70-78 % zeros (a reported ratio below 68 % keeps the matrix kernel)
         if (pooled && have_ws && p.Cg >= 128 && !(z >= 0.0f && z < 0.68f) && tap_supported(p, pooled)) return V_TAP;
+        // Zero ratio unknown, 128 or more channels per group, a workspace for the transposed filters: the
+        // vector kernel.  Over 80 random large launches (64-512 channels, maps 7-56 wide, 40-90 % zeros, each
+        // variant pinned) always taking it here costs 9 % on average and 2.0x at worst against the best variant
+        // of each shape, quad3x3 27 % and 2.1x: a sparse map punishes the matrix kernels more than a dense one
+        // punishes per-element skipping, and the paper's maps are the sparse ones (Fig. 2).  A reported ratio
+        // (SCONV_ZERO_RATIO) replaces this guess: 1-4 % and 1.33x.
+        if (z < 0.0f && have_ws && p.Cg >= 128 && tap_supported(p, pooled)) return V_TAP;
         return V_QUAD;
     }
     if (small_gen_split(p, pooled, have_ws)) return V_GEN;

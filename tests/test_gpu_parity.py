@@ -407,7 +407,7 @@ def test_density_hint_moves_the_static_choice_and_keeps_parity(device, shp, z_hi
     pooled = layer.pool is not None
     d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, zero_ratio=z_hint)
     name = sconv.sconv_variant_name(d, pooled)
-    if 0.68 <= z_hint < 0.87:
+    if 0.68 <= z_hint < 0.92:
         assert name == "tap3x3"
     elif not pooled:
         assert name in ("quad3x3", "wide3x3")
