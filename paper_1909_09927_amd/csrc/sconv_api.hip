@@ -300,7 +300,7 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
             if (p.W <= 7) return V_TAP;   // (no column halo on such maps: 128 -> 512 @20x7 at 60 % 57 against 76 on wide3x3)
             if (p.W <= 16 && p.Cg >= 256 && z < 0.45f && !pooled) return V_QUAD;
             if (z <= 0.6f && (p.W > 16 || p.Cg < 256) && p.Kg >= 128 && wide_fills) return V_WIDE;
-            if (p.Cg >= 128) return V_TAP;
+            if (p.Cg >= 128 || fitw > 1.15) return V_TAP;
         }
         // Maps up to 14 wide with 256 or more channels per group are the deep layers, whose zero
         // ratio the paper puts above 0.7 (Fig. 2): there per-element skipping on the vector pipe
@@ -335,6 +335,9 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // punishes per-element skipping, and the paper's maps are the sparse ones (Fig. 2).  A reported ratio
         // (SCONV_ZERO_RATIO) replaces this guess: 1-4 % and 1.33x.
         if (z < 0.0f && have_ws && p.Cg >= 128 && tap_supported(p, pooled)) return V_TAP;
+        // Maps whose width fills quad3x3's 28-column tiles badly (20, 40: a quarter or more of the tile columns
+        // empty), whatever the channel count: 96 @40x40 at 60 / 90 % zeros 127 / 50 against 193 / 100 us
+        if (p.W > 16 && (p.OW + 27) / 28 * 28 * 100 > p.OW * 115 && tap_supported(p, pooled)) return V_TAP;
         return V_QUAD;
     }
     if (small_gen_split(p, pooled, have_ws)) return V_GEN;
