@@ -936,6 +936,54 @@ def test_random_shapes_through_the_default_dispatch(device, shp):
     check_forward(layer, x, w, relu=False, integer_exact=True)
 
 
+def _random_large_3x3(count, seed):
+    """3x3 / stride 1 / pad 1 layers large enough for the rules that read the zero ratio and for the
+    transposed-filter kernel (hundreds of tiles, 64-384 channels), small enough for the whole-tensor oracle."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        C = int(rng.choice([64, 96, 128, 192, 256, 384]))
+        K = int(rng.choice([64, 100, 128, 192, 256]))
+        H = int(rng.choice([7, 10, 14, 20, 28, 40]))
+        W = H if rng.random() < 0.6 else int(rng.choice([7, 14, 20, 28]))
+        N = int(rng.choice([4, 8, 16]))
+        if 2.0 * N * K * H * W * C * 9 > 2e10 or N * H * W < 400:
+            continue
+        pool = (2, 2, 2) if rng.random() < 0.35 else None
+        out.append((N, C, H, W, K, 3, 3, 1, 1, 1, pool))
+    return out
+
+
+@pytest.mark.parametrize("shp", _random_large_3x3(24, 99))
+def test_random_large_layers_with_zero_ratio_hint_bias_and_explicit_workspace(device, shp):
+    """Random 3x3 layers of benchmark size through every way of calling them: with the zero ratio reported in
+    the descriptor (low, true and high - the hint may pick any variant, never a wrong result), with a bias,
+    and with the workspace passed as an argument or withheld; whole tensors against the oracle."""
+    import oracle
+    rng = np.random.default_rng(sum(shp[:5]))
+    z_true = float(rng.choice([0.45, 0.6, 0.75, 0.9]))
+    layer, x, w = _mk(360, shp, z=z_true)
+    b = (rng.standard_normal(shp[4]) * 0.3).astype(np.float32)
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    own = torch.empty(48 << 20, dtype=torch.uint8, device="cuda")
+    if layer.pool:
+        ref, scale = oracle.conv_pool(x, w, layer.pool, 1, 1, 1)
+        refb, scaleb = oracle.conv_pool_bias(x, w, b, layer.pool, 1, 1, 1)
+        call = lambda **kw: sconv.sconv_pool_forward(xd, wd, layer.pool, 1, 1, 1, **kw)
+    else:
+        ref, scale = oracle.conv(x, w, 1, 1, 1, relu=True)
+        refb, scaleb = oracle.conv_bias(x, w, b, 1, 1, 1, relu=True)
+        call = lambda **kw: sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, **kw)
+    outs = [(call(zero_ratio=zr), ref, scale, f"hint {zr}") for zr in (0.2, z_true, 0.97)]
+    outs.append((call(ws=own), ref, scale, "own workspace"))
+    outs.append((call(ws=None), ref, scale, "no workspace"))
+    outs.append((call(bias=bd), refb, scaleb, "bias"))
+    torch.cuda.synchronize()
+    for got, r, sc, what in outs:
+        err = np.abs(got.cpu().numpy().astype(np.float64) - r)
+        assert (err <= 1e-4 * sc).all(), f"{what}: {int((err > 1e-4 * sc).sum())} outputs beyond the bar"
+
+
 @pytest.mark.parametrize("shp", [
     (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),      # tap / quad / wide / gen all apply
     (1, 128, 28, 28, 128, 1, 1, 1, 0, 1, (2, 2, 2)),     # quad1x1 / gen
