@@ -2,8 +2,9 @@
  * sconv: zero-skipping direct convolution (+ fused ReLU / max-pooling) for AMD MI355X (gfx950).
  *
  * C ABI of the GPU library.  All tensors are fp32 and contiguous; every pointer marked
- * "device" is HIP device memory owned by the caller.  The library allocates, frees and keeps
- * no device memory.  Every entry point that launches work enqueues it on the given HIP stream
+ * "device" is HIP device memory owned by the caller.  The library allocates and frees no device
+ * memory (the only device memory of its own is the fixed 16 MiB array behind sconv_forward_static,
+ * part of the loaded library).  Every entry point that launches work enqueues it on the given HIP stream
  * (a hipStream_t passed as void*; NULL = the default stream) and returns without synchronising.
  * Outputs are overwritten, never accumulated into.  Calls may come from several host threads
  * (planning and enqueueing are serialised inside the library); the only state kept between calls
