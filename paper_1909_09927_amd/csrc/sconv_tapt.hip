@@ -234,6 +234,8 @@ Plan plan_tapt(const Problem& p, int split)
         while (split >= 1 && nss < 16 && tile_waves * ncs * nss < 2 * 1024 && p.Cg / (ncs * nss * 2) >= 16) nss *= 2;
     }
     if (nwv != 8 && !(nwv == 16 && G::MAXW == 16)) return best;
+    // (16 wavefronts leave 128 registers: two filters per lane on a 5x7 tile do not fit without spilling)
+    if (nwv == 16 && G::KPL * G::ACC > 60) return best;
     if (ncs < 1 || ncs > nwv || (ncs & (ncs - 1)) || nss < 1 || p.Cg % (ncs * nss)) return best;
     if (nss > 1 && (split == 0 || G::POOL || wt_bytes(p, G::KB) + nss * part_bytes > split_scratch_bytes() ||
                     (long long)p.N * p.G * nss > 65535))
