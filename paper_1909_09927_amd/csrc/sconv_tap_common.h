@@ -36,7 +36,7 @@ struct TapCfg {
     int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
                         // partial sums, stored into slice blockIdx.z % NSS of y
     int RW;             // slices whose sums fit into LDS side by side during the slice reduction
-    int xcd_remap = 0;  // transposed-filter kernel: renumber the workgroups so that a filter block keeps to one XCD
+    int xcd_remap = 0;  // transposed-filter kernel: XCD groups along the filter blocks (1, 2, 4, 8; 0 = as launched)
 };
 
 // One input position P of the tile: test its mask bit, broadcast the value, run its products.

@@ -72,26 +72,21 @@ __global__ __launch_bounds__(NWV * 64) void tapt_kernel(Problem p, TapCfg cfg, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ts = wave % cfg.NT;                  // spatial tile slot
     const int cs = wave / cfg.NT;                  // channel slice
-    // Workgroups are handed to the eight XCDs in turn, in launch order.  The ones that read the same
-    // filter block are renumbered onto the same XCD (two XCDs for four blocks, ...), so that a block of
-    // the transposed filters stays in that XCD's L2 instead of being fetched into all eight.
+    // Workgroups are handed to the eight XCDs in turn, in launch order.  They are renumbered so that an XCD
+    // works on few filter blocks AND few images: the eight XCDs form xcd_remap groups along the filter blocks
+    // times 8 / xcd_remap groups along grid z (images), so that an XCD's L2 has to hold 1 / xcd_remap of the
+    // transposed filters and xcd_remap / 8 of the input instead of everything being fetched into all eight.
     int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
     if (cfg.xcd_remap) {
-        const int kblocks = gridDim.y;
-        const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + kblocks * blockIdx.z);
+        const unsigned a = (unsigned)cfg.xcd_remap, bgroups = 8u / a;
+        const unsigned kper = gridDim.y / a;                 // filter blocks per XCD
+        const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
         const unsigned xcd = lin & 7u, idx = lin >> 3;
-        unsigned r;
-        if ((kblocks & 7) == 0) {
-            const unsigned q = kblocks >> 3;
-            by = (int)(xcd + 8u * (idx % q));
-            r = idx / q;
-        } else {   // kblocks is 1, 2 or 4
-            const unsigned m = 8u / kblocks;
-            by = (int)(xcd % kblocks);
-            r = idx * m + xcd / kblocks;
-        }
-        bx = (int)(r % gridDim.x);
-        bz = (int)(r / gridDim.x);
+        const unsigned xa = xcd % a, xb = xcd / a;
+        bx = (int)(idx % gridDim.x);
+        const unsigned t = idx / gridDim.x;
+        by = (int)(xa * kper + t % kper);
+        bz = (int)((t / kper) * bgroups + xb);
     }
     const int ss = bz % cfg.NSS;                   // channel range of the workgroup
     const int ng = bz / cfg.NSS;
@@ -296,9 +291,22 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
     if (launch_status() != SCONV_OK) return SCONV_ELAUNCH;
     const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
     TapCfg cfg = pl.cfg;
-    const long long total = gx * pl.kblocks * gz;
-    const bool kb_ok = (pl.kblocks % 8) == 0 || pl.kblocks == 1 || pl.kblocks == 2 || pl.kblocks == 4;
-    cfg.xcd_remap = (kb_ok && total % 8 == 0 && total < (1LL << 32) && !env_value("SCONV_NO_XCD_REMAP")) ? 1 : 0;
+    // XCD groups along the filter blocks (a) and along grid z (8 / a): the split that makes an XCD fetch the
+    // least - filters / a + input * a / 8 - among those that divide the grid evenly and leave an XCD at most
+    // 2.5 MB of filters, so that they stay in its 4 MB L2 while the input streams through
+    cfg.xcd_remap = 0;
+    if (!env_value("SCONV_NO_XCD_REMAP") && gx * pl.kblocks * gz < (1LL << 32)) {
+        const double wbytes = (double)p.K * p.L * 4.0, xbytes = (double)p.N * p.C * p.H * p.W * 4.0;
+        double best = 0.0;
+        for (int a = 1; a <= 8; a *= 2) {
+            if (pl.kblocks % a || gz % (8 / a)) continue;
+            const double fetched = wbytes / a + xbytes * a / 8.0 + (wbytes / a > 2.5e6 ? 1e12 / a : 0.0);
+            if (!cfg.xcd_remap || fetched < best) {
+                cfg.xcd_remap = a;
+                best = fetched;
+            }
+        }
+    }
     int rc;
     if (G::MAXW == 16 && pl.nwv == 16)
         rc = launch_nwv<G, G::MAXW>(q, cfg, grid, pl.lds_bytes, x, wt, out, stream);
