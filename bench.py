@@ -778,6 +778,8 @@ MICRO_MODES = [
     (7, "readlane_fma5", "v_readlane + s_nop 1 + 5 v_fmac on the broadcast value", 1),
     (8, "far_taken", "branch ~1.5 KB out of line, 5 v_fmac there, branch back", 1),
     (9, "ff1_setpc", "s_ff1 + s_bitset0 + s_lshl + s_getpc + s_add + s_addc + s_setpc", 1),
+    (10, "mfma_4x4x1", "8 independent v_mfma_f32_4x4x1 (256 multiply-adds each; 8 clocks at the published rate)", 8),
+    (11, "mfma_16x16x1", "4 independent v_mfma_f32_16x16x1 (1024 multiply-adds each; 32 clocks at the published rate)", 4),
 ]
 
 
@@ -811,6 +813,19 @@ def run_micro(args) -> None:
             rec[f"clocks_per_wavefront_at_{w}_per_simd"] = round(clocks, 2)
             rec[f"clocks_per_simd_at_{w}_per_simd"] = round(clocks / w, 2)
         print(json.dumps(rec), flush=True)
+    # streaming read of 1 GiB (past the 256 MiB last-level cache) with 2, 4 and 8 workgroups per compute unit
+    lib.sconv_micro_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.sconv_micro_read.restype = ctypes.c_int
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    rec = {"micro": "read_stream", "pattern": "16-byte loads, four in flight per thread, over 1 GiB", "bytes": 1 << 30}
+    for wpc in (2, 4, 8):
+        def go():
+            rc = lib.sconv_micro_read(src.data_ptr(), 1 << 30, cus * wpc, out.data_ptr(), stream)
+            if rc:
+                sys.exit(f"sconv_micro_read failed: {rc}")
+        ms = _time(go, 10, 3)
+        rec[f"TBps_at_{wpc}_workgroups_per_cu"] = round((1 << 30) / (ms * 1e-3) / 1e12, 2)
+    print(json.dumps(rec), flush=True)
 
 
 def run_variants(args) -> None:

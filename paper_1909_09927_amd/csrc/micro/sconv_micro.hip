@@ -21,11 +21,66 @@ enum {
     MICRO_READLANE_FMA5 = 7,  // v_readlane + s_nop 1 + 5 v_fmac reading the broadcast value
     MICRO_FAR_TAKEN = 8,      // branch out of line (about 3 KB away), 5 v_fmac there, branch back
     MICRO_FF1_SETPC = 9,      // s_ff1 + s_bitset0 + s_lshl + s_add + s_addc + s_setpc (threaded dispatch)
-    MICRO_MODES = 10
+    MICRO_MFMA_4X4X1 = 10,    // 8 independent v_mfma_f32_4x4x1 (16 blocks, 256 multiply-adds each) per repeat
+    MICRO_MFMA_16X16X1 = 11,  // 4 independent v_mfma_f32_16x16x1 (4 blocks, 1024 multiply-adds each) per repeat
+    MICRO_MODES = 12
 };
 }
 
 namespace {
+
+typedef float mv4f __attribute__((ext_vector_type(4)));
+typedef float mv16f __attribute__((ext_vector_type(16)));
+
+// Matrix-pipe issue rate: independent accumulators, operands that change with the lane (not zeros).
+template <int MODE>
+__global__ __launch_bounds__(256) void micro_mfma_kernel(int iters, float* out)
+{
+    const float a = 1.0f + threadIdx.x * 0.001f, b = 0.5f + threadIdx.x * 0.002f;
+    float r = 0.0f;
+    if constexpr (MODE == MICRO_MFMA_4X4X1) {
+        mv4f acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = mv4f{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < iters; ++i)
+#pragma unroll
+            for (int rep = 0; rep < 64; ++rep)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, acc[j], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r += acc[j][0] + acc[j][3];
+    } else {
+        mv16f acc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+        for (int i = 0; i < iters; ++i)
+#pragma unroll
+            for (int rep = 0; rep < 64; ++rep)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b, acc[j], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r += acc[j][0] + acc[j][15];
+    }
+    if (out) out[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+// Streaming read: every thread sums 16-byte loads, `unroll` of them in flight, over a buffer of `n16` 16-byte
+// words; one result per thread so that nothing is optimised away.
+__global__ __launch_bounds__(256) void micro_read_kernel(const mv4f* __restrict__ src, long long n16, float* out)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    mv4f s0 = {0, 0, 0, 0}, s1 = s0, s2 = s0, s3 = s0;
+    long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const mv4f a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        s0 += a; s1 += b; s2 += c; s3 += d;
+    }
+    for (; i < n16; i += stride) s0 += src[i];
+    const mv4f s = s0 + s1 + s2 + s3;
+    out[blockIdx.x * 256 + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
 
 template <int MODE>
 __global__ __launch_bounds__(256) void micro_kernel(int iters, unsigned m, float* out)
@@ -130,6 +185,22 @@ extern "C" int sconv_micro_launch(int mode, int iters, int blocks, float* out_de
     case MICRO_READLANE_FMA5: return launch<MICRO_READLANE_FMA5>(iters, 0, blocks, out_dev, s);
     case MICRO_FAR_TAKEN: return launch<MICRO_FAR_TAKEN>(iters, 1, blocks, out_dev, s);
     case MICRO_FF1_SETPC: return launch<MICRO_FF1_SETPC>(iters, 0, blocks, out_dev, s);
+    case MICRO_MFMA_4X4X1:
+        hipLaunchKernelGGL(micro_mfma_kernel<MICRO_MFMA_4X4X1>, dim3(blocks), dim3(256), 0, s, iters, out_dev);
+        return hipGetLastError() == hipSuccess ? 0 : -3;
+    case MICRO_MFMA_16X16X1:
+        hipLaunchKernelGGL(micro_mfma_kernel<MICRO_MFMA_16X16X1>, dim3(blocks), dim3(256), 0, s, iters, out_dev);
+        return hipGetLastError() == hipSuccess ? 0 : -3;
     default: return -1;
     }
+}
+
+// Enqueues a streaming read of `bytes` bytes (a multiple of 16) at src_dev by `blocks` workgroups of 256
+// threads; out_dev: blocks * 256 floats.  Returns 0, -1 or -3.
+extern "C" int sconv_micro_read(const float* src_dev, size_t bytes, int blocks, float* out_dev, void* hip_stream)
+{
+    if (!src_dev || !out_dev || blocks <= 0 || bytes < 16 || bytes % 16) return -1;
+    hipLaunchKernelGGL(micro_read_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                       reinterpret_cast<const mv4f*>(src_dev), (long long)(bytes / 16), out_dev);
+    return hipGetLastError() == hipSuccess ? 0 : -3;
 }
