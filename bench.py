@@ -606,6 +606,7 @@ def run_split(args) -> None:
     tensor's round trip through memory).  Same buffers every launch (warm caches)."""
     import torch
     import paper_1909_09927_amd as sconv
+    lend_workspace()
     for ci, cfg in enumerate(workloads.CONFIGS):
         if ci == 0:
             continue
