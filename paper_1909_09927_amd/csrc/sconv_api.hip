@@ -25,7 +25,7 @@ const PlanPin* current_pin() { return g_pin; }
 static const char* const kEnvNames[] = {
     "SCONV_VARIANT", "SCONV_TAP_GEOM", "SCONV_QUAD_GEOM", "SCONV_WIDE_GEOM", "SCONV_GEN_GEOM", "SCONV_PW_GEOM",
     "SCONV_TAP_SPLIT", "SCONV_QUAD_SPLIT", "SCONV_WIDE_SPLIT", "SCONV_GEN_SPLIT", "SCONV_PW_SPLIT",
-    "SCONV_ENCODE", "SCONV_TRACE_PLAN", "SCONV_NO_XCD_REMAP"};
+    "SCONV_ENCODE", "SCONV_TRACE_PLAN", "SCONV_NO_XCD_REMAP", "SCONV_ENCODE_TR16"};
 constexpr int kEnvCount = (int)(sizeof(kEnvNames) / sizeof(kEnvNames[0]));
 static std::mutex g_env_lock;
 static std::atomic<bool> g_env_read{false};

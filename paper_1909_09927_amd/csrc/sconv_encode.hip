@@ -133,12 +133,14 @@ __global__ __launch_bounds__(kEncodeBlock) void encode_kernel(Problem p, int pec
 // in LDS a chunk of channels at a time - instead of once per window in pieces of S elements (a
 // 3x3 window row touches 21 cache lines per 64 columns; a 1x1 row 64).  Each wavefront then scans
 // its row out of LDS exactly as above; the row's ring and counts persist across the channel chunks.
-constexpr int TR = 16;                 // rows per workgroup
-constexpr int kTileBlock = 1024;       // 16 wavefronts: one row each
-constexpr int RPW = TR / (kTileBlock / 64);
+constexpr int kTileBlock = 1024;       // 16 wavefronts: TR / 16 rows each
 constexpr int STAGE = 4096;            // staged input elements per chunk (16 KB)
 constexpr int PER_THREAD = STAGE / kTileBlock;
 
+// TR rows per workgroup: 16 (one per wavefront), or 32 for 1x1 layers, whose rows are short (256-512
+// columns): the set-up of a tile and its three barriers then serve twice the output, and a channel's box is
+// a run of 32 positions (a whole 128-byte line) instead of 16.
+template <int TR>
 __global__ __launch_bounds__(kTileBlock) void encode_tile_kernel(Problem p, int pecr, int rows_per_ng,
                                                                    int tiles_per_ng, const float* __restrict__ x,
                                                                    float* __restrict__ values,
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(kTileBlock) void encode_tile_kernel(Problem p, int 
     __shared__ float ring_v[TR][128];
     __shared__ int32_t ring_i[TR][128];
     __shared__ int s_ih0[TR], s_iw0[TR];
+    constexpr int RPW = TR / (kTileBlock / 64);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -298,15 +301,6 @@ int launch_encode(const Problem& p, int fmt, const float* x, float* values, int3
     const long long rows_per_ng = pecr ? (long long)p.PH * p.PW * p.ph * p.pw : (long long)p.OH * p.OW;
     const long long rows = (long long)p.N * p.G * rows_per_ng;
     if (rows == 0) return SCONV_OK;
-    // The tiled kernel needs the box of a tile's windows to fit its staging buffer.  The rows of a
-    // tile are consecutive: in ECR order they span at most (TR-1)/OW + 2 output rows, in PECR order
-    // (TR-1)/(ph*pw*PW) + 2 rows of pooling windows; the box is never wider than the padded map.
-    const long long span_oh = pecr ? (long long)((TR - 1) / ((long long)p.ph * p.pw * p.PW) + 1) * p.ps + p.ph - 1
-                                   : (long long)(TR - 1) / p.OW + 1;
-    const long long bh_max = std::min<long long>(span_oh, p.OH - 1) * p.stride + p.R;
-    const long long bw_max = std::min<long long>((long long)(p.OW - 1) * p.stride + p.S, p.W + 2LL * p.pad);
-    const long long tiles_per_ng = (rows_per_ng + TR - 1) / TR;
-    const long long tiles = tiles_per_ng * p.N * p.G;
     // Measured: staging pays on large maps (56x56: 1.2-1.45x; the window-per-wavefront kernel's
     // pieces of S elements then miss the caches) and on 1x1 layers with long channel loops; on maps
     // of 28x28 and below the plain kernel's gathers hit the caches and its lack of barriers wins
@@ -316,10 +310,26 @@ int launch_encode(const Problem& p, int fmt, const float* x, float* values, int3
     bool tiled = large_map || long_1x1;
     if (const char* pin = env_value("SCONV_ENCODE"))   // tuning aid and tests: "tile" or "rows"
         tiled = !strcmp(pin, "tile");
-    if (tiled && bh_max * bw_max <= STAGE && tiles < (1ll << 31) && rows_per_ng < (1ll << 31)) {
-        hipLaunchKernelGGL(encode_tile_kernel, dim3((unsigned)tiles), dim3(kTileBlock), 0, stream, p, pecr ? 1 : 0,
+    // The tiled kernel needs the box of a tile's windows to fit its staging buffer.  The rows of a
+    // tile are consecutive: in ECR order they span at most (TR-1)/OW + 2 output rows, in PECR order
+    // (TR-1)/(ph*pw*PW) + 2 rows of pooling windows; the box is never wider than the padded map.
+    auto try_tiled = [&](int TR, auto kernel) -> int {
+        const long long span_oh = pecr ? (long long)((TR - 1) / ((long long)p.ph * p.pw * p.PW) + 1) * p.ps + p.ph - 1
+                                       : (long long)(TR - 1) / p.OW + 1;
+        const long long bh_max = std::min<long long>(span_oh, p.OH - 1) * p.stride + p.R;
+        const long long bw_max = std::min<long long>((long long)(p.OW - 1) * p.stride + p.S, p.W + 2LL * p.pad);
+        const long long tiles_per_ng = (rows_per_ng + TR - 1) / TR;
+        const long long tiles = tiles_per_ng * p.N * p.G;
+        if (bh_max * bw_max > STAGE || tiles >= (1ll << 31) || rows_per_ng >= (1ll << 31)) return SCONV_EUNSUPPORTED;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(kTileBlock), 0, stream, p, pecr ? 1 : 0,
                            (int)rows_per_ng, (int)tiles_per_ng, x, values, index, count);
         return launch_status();
+    };
+    if (tiled) {
+        int rc = SCONV_EUNSUPPORTED;
+        if (p.R == 1 && p.S == 1 && !env_value("SCONV_ENCODE_TR16")) rc = try_tiled(32, encode_tile_kernel<32>);
+        if (rc == SCONV_EUNSUPPORTED) rc = try_tiled(16, encode_tile_kernel<16>);
+        if (rc != SCONV_EUNSUPPORTED) return rc;
     }
     const long long blocks = (rows + kEncodeBlock / 64 - 1) / (kEncodeBlock / 64);
     if (blocks >= (1ll << 31)) return SCONV_EUNSUPPORTED;
