@@ -483,10 +483,11 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
     int err = SCONV_OK;
     // First pass, cheap: one untimed launch (does the candidate apply?), one timed launch with the operands
     // still in the caches; only a candidate within a quarter of the fastest so far is timed twice more.
-    float fastest = -1.0f;
+    float fastest = -1.0f, last_t = -1.0f;
     const Flush no_flush_first = {nullptr, 0};
     auto try_one = [&](Variant v, const PlanPin* pin) {
         float t = time_candidate(v, pin, p, pooled, x, w, y, s, e0, e1, 1, no_flush_first, &err);
+        last_t = t;
         if (t < 0.0f) return false;
         if (fastest < 0.0f || t <= 1.25f * fastest) {
             const float t2 = time_candidate(v, pin, p, pooled, x, w, y, s, e0, e1, 2, no_flush_first, &err);
@@ -520,6 +521,9 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
             // (a plain geometry serves a fused call only with its channels split: start there)
             const bool unsplit_ok = try_one(f.v, &pin);
             if (!unsplit_ok && !(pooled && f.nss_hi > 1)) continue;
+            // a geometry whose own split is twice as slow as the fastest plan so far is not worth its
+            // other decompositions
+            if (unsplit_ok && fastest > 0.0f && last_t > 2.0f * fastest) continue;
             for (int nss = unsplit_ok ? 1 : 2; nss <= f.nss_hi && err == SCONV_OK; nss *= 2) {
                 bool any = false;   // a split the launch is too large for applies with no nwv, ncs
                 for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
