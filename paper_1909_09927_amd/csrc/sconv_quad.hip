@@ -278,6 +278,54 @@ __global__ __launch_bounds__(NWV * 64) void quad_kernel(Problem p, TapCfg cfg, c
             for (int a = 0; a < G::ACC / 4; ++a) acc[i][a] += bk;
         }
     }
+    if (!G::POOL && cfg.tr == 2) {
+        // Every wavefront of the workgroup stores.  After the reduction slice 0 holds the finished tile and
+        // the other slices' wavefronts would idle while it issues all the stores (on a launch of a single
+        // round of workgroups that is the tail of the whole kernel).  Slice 0 lays the tile out in LDS as
+        // [filter register][row][filter][column]; after one barrier the NCS wavefronts of the tile store its
+        // rows in turn, each store a group of RP lanes writing the run one filter has in that row.
+        constexpr int TS = 4 * G::NQ + 8;          // row stride: 16-byte aligned, spreads the banks
+        constexpr int FPI = 64 / G::RP;            // filters per store instruction
+        __syncthreads();   // every wavefront is done with the filter buffers and the reduction
+        float* tr = lds + ts * (G::KPL * G::TH * 64 * TS);
+        if (cs == 0 && tile_ok) {
+#pragma unroll
+            for (int i = 0; i < G::KPL; ++i)
+#pragma unroll
+                for (int orow = 0; orow < G::TH; ++orow)
+#pragma unroll
+                    for (int q = 0; q < G::NQ; ++q) {
+                        v4f v = acc[i][orow * G::NQ + q];
+                        if (p.relu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                        }
+                        *reinterpret_cast<v4f*>(tr + ((i * G::TH + orow) * 64 + lane) * TS + 4 * q) = v;
+                    }
+        }
+        __syncthreads();
+        if (!tile_ok) return;
+        const int plane = p.OH * p.OW;
+        const int col = lane % G::RP, fsub = lane / G::RP;
+        const bool col_ok = col < G::TW && ow0 + col < p.OW;
+#pragma unroll
+        for (int i = 0; i < G::KPL; ++i) {
+            const int kleft = kvalid - 64 * i;     // filters of this register that exist
+            float* yk = y + ((size_t)n * p.K + (size_t)g * p.Kg + kb0 + 64 * i) * plane;
+#pragma unroll
+            for (int orow = 0; orow < G::TH; ++orow) {
+                const int oh = oh0 + orow;         // uniform
+                if ((orow & (cfg.NCS - 1)) != cs || oh >= p.OH) continue;
+                const float* trr = tr + (i * G::TH + orow) * 64 * TS;
+#pragma unroll
+                for (int kk = 0; kk < G::RP; ++kk) {
+                    const int k = kk * FPI + fsub;
+                    if (col_ok && k < kleft) yk[(size_t)k * plane + oh * p.OW + ow0 + col] = trr[k * TS + col];
+                }
+            }
+        }
+        return;
+    }
     if (!G::POOL && cfg.tr) {
         // Stored from the accumulator layout, every lane of a store would go to a different
         // output plane, four bytes each.  Instead each output row of the tile is transposed
@@ -473,6 +521,13 @@ Plan plan_geom(const Problem& p)
                 best.cfg.NCS = ncs;
                 best.cfg.CPW = G::CCH / ncs;
                 best.cfg.tr = (size_t)nt * 64 * (4 * G::NQ + 8) * sizeof(float) <= lds_bytes ? 1 : 0;
+                // whole tiles laid out in LDS so that every slice's wavefront stores rows: where that needs
+                // no more LDS than the plan has (7-row tiles keep one workgroup per compute unit anyway)
+                const size_t all_bytes = (size_t)nt * G::KPL * G::TH * 64 * (4 * G::NQ + 8) * sizeof(float);
+                if (!G::POOL && ncs > 1 && all_bytes <= (G::TH >= 7 ? (size_t)160 * 1024 : lds_bytes)) {
+                    best.cfg.tr = 2;
+                    if (all_bytes > lds_bytes) lds_bytes = all_bytes;
+                }
                 best.nwv = nwv;
                 best.kblocks = kblocks;
                 best.lds_bytes = lds_bytes;
