@@ -53,6 +53,8 @@ SKIP_GRANULE = {"rows": 1, "tap3x3": 1, "quad3x3": 6, "quad1x1": 32, "wide3x3": 
 FP32_UNPACKED_PEAK_TF = 78.6  # same without packed fp32 instructions (this build keeps them off)
 TUNE = True                   # --no-tune: the static dispatch rules and cost models only
 HINT = False                  # --hint: no tuning; the density probe's zero ratio is given to the static rules
+PREP = False                  # --prepared: every layer's calls bring the filters in the prepared layout
+                              # (sconv_filter_prep, written once at set-up as an inference engine would)
 CACHE_BYTES = 512 << 20       # rotate buffers until their total passes twice the 256 MiB last-level cache
 
 
@@ -165,15 +167,18 @@ def lend_workspace() -> None:
 class DeviceLayer:
     """One layer's operands on the device, in `copies` rotating sets."""
 
-    def __init__(self, layer, N, x, w, copies):
+    def __init__(self, layer, N, x, w, copies, prepared=None):
         import torch
         import paper_1909_09927_amd as sconv
         self.layer, self.N = layer, N
         self.sconv = sconv
         lend_workspace()
+        self.prepared = PREP if prepared is None else prepared
+        self.workspace = _workspaces[torch.cuda.current_stream().cuda_stream]
         xd = torch.from_numpy(x).cuda()
         wd = torch.from_numpy(w).cuda()
         self.sets = []
+        self.preps = []        # per buffer set: the prepared copy of that set's filters (None: no such layout)
         for i in range(copies):
             xs = xd if i == 0 else xd.clone()
             ws = wd if i == 0 else wd.clone()
@@ -182,6 +187,10 @@ class DeviceLayer:
             else:
                 y = sconv.sconv_forward(xs, ws, layer.stride, layer.pad, layer.groups, relu=True)
             self.sets.append((xs, ws, y))
+            self.preps.append(sconv.sconv_filter_prep(ws, layer.groups, layer.stride, layer.pad)
+                              if self.prepared else None)
+        if self.preps[0] is None:
+            self.prepared = False
         self.host = (x, w)
         self.tune_wall_s = 0.0
         self.z = None
@@ -191,14 +200,18 @@ class DeviceLayer:
             t0 = time.perf_counter()
             self.z = sconv.zero_ratio_of(sconv.sconv_density(xd))
             self.tune_wall_s = time.perf_counter() - t0
-        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, self.z)
+        d = sconv.desc_for(xd, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, self.z, self.prepared)
         if TUNE:
             # set-up, outside every timed region: the library times its variants and decompositions on
             # this layer's operands and remembers the fastest for this descriptor
             xs, ws, y = self.sets[0]
             t0 = time.perf_counter()
-            sconv.sconv_tune(xs, ws, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, out=y,
-                             flush=flush_buffer())
+            if self.prepared:
+                sconv.sconv_tune(xs, ws, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, out=y,
+                                 flush=flush_buffer(), wprep=self.preps[0], ws=self.workspace)
+            else:
+                sconv.sconv_tune(xs, ws, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, out=y,
+                                 flush=flush_buffer())
             self.tune_wall_s = time.perf_counter() - t0
         self.variant = sconv.sconv_variant_name(d, bool(layer.pool))
         self.plan = sconv.sconv_plan_name(d, bool(layer.pool))
@@ -221,9 +234,18 @@ class DeviceLayer:
 
     def run(self):
         xs, ws, y = self.sets[self.i]
+        wp = self.preps[self.i]
         self.i = (self.i + 1) % len(self.sets)
         L = self.layer
-        if L.pool:
+        if self.prepared:
+            # the ..._prep calls: prepared filters and the workspace as arguments of the call
+            if L.pool:
+                self.sconv.sconv_pool_forward(xs, ws, L.pool, L.stride, L.pad, L.groups, out=y, zero_ratio=self.z,
+                                              wprep=wp, ws=self.workspace)
+            else:
+                self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y, zero_ratio=self.z,
+                                         wprep=wp, ws=self.workspace)
+        elif L.pool:
             self.sconv.sconv_pool_forward(xs, ws, L.pool, L.stride, L.pad, L.groups, out=y, zero_ratio=self.z)
         else:
             self.sconv.sconv_forward(xs, ws, L.stride, L.pad, L.groups, relu=True, out=y, zero_ratio=self.z)
@@ -305,7 +327,8 @@ def layer_record(dl: DeviceLayer, work: dict, ms: float) -> dict:
     issued = work["dense_flops"] * (1.0 - skipped) if g > 1 or dense_form else work["nz_flops"]
     rounds = getattr(dl, "round_ms", (float("nan"), float("nan")))
     return {
-        "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "plan": dl.plan, "ms": round(ms, 5),
+        "layer": dl.layer.name, "N": dl.N, "variant": dl.variant, "plan": dl.plan,
+        "prepared_filters": bool(getattr(dl, "prepared", False)), "ms": round(ms, 5),
         "ms_min_max_of_5_rounds": [round(rounds[0], 5), round(rounds[1], 5)],
         "pipe": "mfma" if dl.variant in MFMA_VARIANTS else "valu",
         "dense_fallback": dense_form, "skip_granule_elements": g,
@@ -483,6 +506,37 @@ def run_headline(args) -> None:
         "roofline": roof,
         "paper_context": paper_context(),
     }
+    if not PREP and not args.no_prepared:
+        # The same step with the filters handed over in the prepared layout (written once at set-up, as an
+        # inference engine holding constant filters would): saves the per-call transposition of the vector
+        # kernel's transposed-filter form.  Reported beside the headline, never as `value`.
+        pdls = [DeviceLayer(layer, N, x, w, copies, prepared=True) for layer, x, w in host]
+        pfail = 0
+        if not args.no_parity:
+            for li, dl in enumerate(pdls):
+                pfail += dl.parity(5252 + li)["failed"]
+        if pfail:
+            print(json.dumps({"error": "parity check of the prepared-filter plans failed",
+                              "plans": [dl.plan for dl in pdls]}), flush=True)
+            sys.exit(3)
+
+        def pstep():
+            for dl in pdls:
+                dl.run()
+
+        ramp_up(pstep, 0.1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pstep()
+        torch.cuda.synchronize()
+        pms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["prepared_filters"] = {
+            "ms_per_step": round(pms, 4), "value": round(dense_total / (pms * 1e-3) / 1e9, 1),
+            "plans": [dl.plan for dl in pdls], "parity_failed": pfail,
+            "note": "same step, filters passed in the prepared layout (sconv_filter_prep once at set-up); "
+                    "not the headline value"}
+        del pdls
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ci, N)
         out["cpu_baseline_one_thread"] = cpu_baseline_one_thread(ci)
@@ -955,6 +1009,10 @@ def main() -> None:
                     help="skip the sampled comparison with the CPU oracle that precedes the timed region")
     ap.add_argument("--no-tune", action="store_true",
                     help="skip sconv_tune at set-up: static dispatch rules and cost models only")
+    ap.add_argument("--prepared", action="store_true",
+                    help="every layer's calls bring prepared filters (sconv_filter_prep at set-up)")
+    ap.add_argument("--no-prepared", action="store_true",
+                    help="headline: skip the extra prepared-filter measurement")
     ap.add_argument("--hint", action="store_true",
                     help="no tuning: probe every layer's input once (sconv_density) and give the static rules "
                          "its zero ratio (SCONV_ZERO_RATIO in the descriptor's flags)")
@@ -975,7 +1033,8 @@ def main() -> None:
                     help="zero pattern of the input for --sweep / --layer: independent zeros, or dead "
                          "planes plus spatial patches at the same overall ratio")
     args = ap.parse_args()
-    global TUNE, HINT
+    global TUNE, HINT, PREP
+    PREP = args.prepared
     HINT = args.hint
     TUNE = not args.no_tune and not args.hint and not os.environ.get("SCONV_VARIANT")
     if args.gpus != 1:

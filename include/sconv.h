@@ -45,7 +45,9 @@ typedef struct {
                                     of kernel, never for the result.                            */
 } sconv_desc_t;
 
-enum { SCONV_RELU = 1 };
+enum { SCONV_RELU = 1,
+       SCONV_PREPARED_FILTERS = 2 /* read by sconv_variant_name / sconv_plan_name only: name the plan of a
+                                     ..._prep call that brings prepared filters; the forward calls ignore it */ };
 /* Zero-ratio hint: bits 8..15 of flags hold 0 (not given) or 1 + round(254 * z), z in [0, 1]. */
 enum { SCONV_ZERO_RATIO_SHIFT = 8, SCONV_ZERO_RATIO_MASK = 0xff << 8 };
 #define SCONV_ZERO_RATIO(z) ((int32_t)((1 + (int32_t)((z) * 254.0 + 0.5)) << SCONV_ZERO_RATIO_SHIFT))
@@ -219,6 +221,48 @@ int sconv_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* 
                      void* ws_dev, size_t ws_bytes, void* hip_stream);
 int sconv_pool_forward_ws(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, float* y_dev,
                           void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Prepared filters.  The vector kernel's fastest form for large 3x3 launches ("tap3x3", see sconv_forward)
+ * has every wavefront read the nine taps of 64 consecutive filters of one channel in nine 256-byte loads,
+ * which needs the filters in the layout [group][block of 64 filters][channel][tap][64] (blocks of a group
+ * padded with zeros to an even count).  The plain calls write that copy into the workspace before every
+ * such launch (about 10 us for 512 x 512 x 3 x 3 filters).  The paper's setting is inference: the filters
+ * are transferred to the GPU once, before the first kernel (step 0 of the procedure in Section 5.1), and stay
+ * as they are while feature maps flow through.  A caller in that setting writes the copy once and passes it
+ * with every call.
+ *   sconv_filter_prep_size: bytes of the prepared copy for this descriptor's filters (a multiple of 256);
+ *            0 when no kernel reads the layout for it (anything but 3x3 / stride 1 / pad 1 with channels
+ *            per group a multiple of 16).  Depends on K, C, groups, R, S only.  Host only.
+ *   sconv_filter_prep: enqueues the kernel that writes the copy of w_dev into wprep_dev (device, out,
+ *            256-byte aligned, wprep_bytes >= the size above).  SCONV_EUNSUPPORTED when the size is 0.
+ *   sconv_forward_prep / sconv_pool_forward_prep: sconv_forward / sconv_pool_forward (Sections 5 and 6)
+ *            with every optional operand as an argument of the call:
+ *              wprep_dev device, in, optional (NULL with wprep_bytes 0): the prepared copy of w_dev - the
+ *                    caller guarantees it was written from the same filters; a descriptor whose plans do not
+ *                    read the layout ignores it.  With it the transposed-filter form needs no workspace.
+ *              bias_dev  device, in, optional (NULL: none): as sconv_forward_bias.
+ *              ws_dev    device, scratch, optional (NULL with ws_bytes 0): as sconv_forward_ws; a workspace
+ *                    lent with sconv_set_workspace is ignored for this call.
+ *            w_dev is still required: kernels that do not read the prepared layout read it.
+ *            Nothing is remembered after the call returns.
+ *   sconv_tune_prep: sconv_tune for calls that bring prepared filters (plans are remembered separately for
+ *            calls with and without them: the transposed-filter form is about 10 us cheaper with them), the
+ *            workspace being an argument as well.
+ * Errors as the plain calls, plus SCONV_EINVAL for a misaligned, half-given or too small wprep_dev.
+ */
+int sconv_filter_prep_size(const sconv_desc_t* desc, size_t* bytes);
+int sconv_filter_prep(const sconv_desc_t* desc, const float* w_dev, void* wprep_dev, size_t wprep_bytes,
+                      void* hip_stream);
+int sconv_forward_prep(const sconv_desc_t* desc, const float* x_dev, const float* w_dev, const void* wprep_dev,
+                       size_t wprep_bytes, const float* bias_dev, float* y_dev, void* ws_dev, size_t ws_bytes,
+                       void* hip_stream);
+int sconv_pool_forward_prep(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                            const void* wprep_dev, size_t wprep_bytes, const float* bias_dev, float* y_dev,
+                            void* ws_dev, size_t ws_bytes, void* hip_stream);
+int sconv_tune_prep(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
+                    const void* wprep_dev, size_t wprep_bytes, float* y_dev, void* ws_dev, size_t ws_bytes,
+                    void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms);
 
 /*
  * sconv_forward for callers that cannot allocate or lend device memory: code under HIP graph capture,

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsconv.so")
 
 SCONV_RELU = 1
+SCONV_PREPARED_FILTERS = 2
 FMT_ECR = 0
 FMT_PECR = 1
 SCONV_OK, SCONV_EINVAL, SCONV_EUNSUPPORTED, SCONV_ELAUNCH, SCONV_ETOOLARGE = 0, -1, -2, -3, -4
@@ -74,11 +75,19 @@ def lib() -> ctypes.CDLL:
         L.sconv_pool_forward_bias.argtypes = [P(Desc), vp, vp, vp, vp, vp]
         L.sconv_pair_forward.argtypes = [P(Desc), P(Desc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.sconv_density.argtypes = [P(Desc), vp, vp, vp]
+        sz = ctypes.c_size_t
+        L.sconv_filter_prep_size.argtypes = [P(Desc), P(sz)]
+        L.sconv_filter_prep.argtypes = [P(Desc), vp, vp, sz, vp]
+        L.sconv_forward_prep.argtypes = [P(Desc), vp, vp, vp, sz, vp, vp, vp, sz, vp]
+        L.sconv_pool_forward_prep.argtypes = [P(Desc), vp, vp, vp, sz, vp, vp, vp, sz, vp]
+        L.sconv_tune_prep.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, sz, vp, vp, sz, vp, sz, vp,
+                                      P(ctypes.c_float)]
         for f in ("sconv_output_dims", "sconv_encode_sizes", "sconv_encode", "sconv_forward",
                   "sconv_pool_forward", "sconv_maxpool", "sconv_tune", "sconv_tune_reset", "sconv_plan_name",
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
                   "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_forward_bias",
-                  "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density"):
+                  "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density", "sconv_filter_prep_size",
+                  "sconv_filter_prep", "sconv_forward_prep", "sconv_pool_forward_prep", "sconv_tune_prep"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -98,18 +107,20 @@ def zero_ratio_flag(zero_ratio: Optional[float]) -> int:
 
 
 def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, groups=1, pool: Optional[Tuple[int, int, int]] = None,
-              relu: bool = False, zero_ratio: Optional[float] = None) -> Desc:
+              relu: bool = False, zero_ratio: Optional[float] = None, prepared: bool = False) -> Desc:
+    """prepared: SCONV_PREPARED_FILTERS, read by the two naming calls only."""
     ph, pw, ps = pool if pool is not None else (0, 0, 0)
     return Desc(N, C, H, W, K, R, S, stride, pad, groups, ph, pw, ps,
-                (SCONV_RELU if relu else 0) | zero_ratio_flag(zero_ratio))
+                (SCONV_RELU if relu else 0) | (SCONV_PREPARED_FILTERS if prepared else 0) |
+                zero_ratio_flag(zero_ratio))
 
 
-def desc_for(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, zero_ratio=None) -> Desc:
+def desc_for(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, zero_ratio=None, prepared=False) -> Desc:
     N, C, H, W = x.shape
     K, Cg, R, S = w.shape
     if Cg * groups != C:
         raise ValueError("filter channel count does not match C / groups")
-    return make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, relu, zero_ratio)
+    return make_desc(N, C, H, W, K, R, S, stride, pad, groups, pool, relu, zero_ratio, prepared)
 
 
 def sconv_output_dims(desc: Desc) -> Tuple[int, int, int, int]:
@@ -248,11 +259,39 @@ def sconv_encode(x, w_shape, fmt: int, stride=1, pad=0, groups=1, pool=None, out
 _NO_WS = object()   # "no ws argument": the plain entry point (a lent workspace applies)
 
 
-def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS, bias=None, zero_ratio=None):
+def sconv_filter_prep(w, groups=1, stride=1, pad=1, out=None):
+    """The prepared (transposed) copy of the filters w[K,C/G,R,S] that the ..._prep calls read (a byte tensor
+    in device memory), or None when no kernel reads the layout for such a layer."""
+    import torch
+    _check_dev(w, torch.float32, "w")
+    K, Cg, R, S = w.shape
+    desc = make_desc(1, Cg * groups, max(R, 8), max(S, 8), K, R, S, stride, pad, groups)
+    n = ctypes.c_size_t()
+    rc = lib().sconv_filter_prep_size(ctypes.byref(desc), ctypes.byref(n))
+    if rc:
+        raise SconvError(rc, "sconv_filter_prep_size")
+    if n.value == 0:
+        return None
+    if out is None:
+        out = torch.empty(n.value, dtype=torch.uint8, device=w.device)
+    rc = lib().sconv_filter_prep(ctypes.byref(desc), w.data_ptr(), out.data_ptr(), out.numel(), _stream())
+    if rc:
+        raise SconvError(rc, "sconv_filter_prep")
+    return out
+
+
+def _opt_ptr(t):
+    return (t.data_ptr(), t.numel() * t.element_size()) if t is not None else (None, 0)
+
+
+def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_WS, bias=None, zero_ratio=None,
+                  wprep=None):
     """Sparse convolution; returns y[N,K,OH,OW] (device, fp32).  ws: a device tensor (or None) passed as
     this call's workspace through sconv_forward_ws; left out, sconv_forward runs.  bias: a device tensor
     [K] added before the ReLU (sconv_forward_bias; not together with ws).  zero_ratio: the map's zero
-    ratio if known (a hint for the choice of kernel, carried in the descriptor's flags)."""
+    ratio if known (a hint for the choice of kernel, carried in the descriptor's flags).  wprep: the prepared
+    copy of w (sconv_filter_prep); with it sconv_forward_prep runs, taking bias and ws (None when left out:
+    a lent workspace does not apply) as arguments of the call."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -264,7 +303,15 @@ def sconv_forward(x, w, stride=1, pad=0, groups=1, relu=False, out=None, ws=_NO_
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, OH, OW):
             raise ValueError("out has the wrong shape")
-    if bias is not None:
+    if wprep is not None:
+        if bias is not None:
+            _check_dev(bias, torch.float32, "bias")
+        wp, wb = _ws_args(None if ws is _NO_WS else ws)
+        pp, pb = _opt_ptr(wprep)
+        rc = lib().sconv_forward_prep(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), pp, pb,
+                                      bias.data_ptr() if bias is not None else None, out.data_ptr(), wp, wb,
+                                      _stream())
+    elif bias is not None:
         _check_dev(bias, torch.float32, "bias")
         if ws is not _NO_WS or tuple(bias.shape) != (desc.K,):
             raise ValueError("bias must be [K] and cannot be combined with an explicit workspace")
@@ -350,9 +397,10 @@ def sconv_maxpool(conv, x_shape, w_shape, pool, stride=1, pad=0, groups=1, out=N
     return out
 
 
-def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS, bias=None, zero_ratio=None):
+def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_WS, bias=None, zero_ratio=None,
+                       wprep=None):
     """Sparse convolution + ReLU + max pooling in one pass; returns y[N,K,PH,PW] (device, fp32).
-    ws, bias, zero_ratio: as in sconv_forward."""
+    ws, bias, zero_ratio, wprep: as in sconv_forward."""
     import torch
     _check_dev(x, torch.float32, "x")
     _check_dev(w, torch.float32, "w")
@@ -364,7 +412,15 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_W
         _check_dev(out, torch.float32, "out")
         if tuple(out.shape) != (desc.N, desc.K, PH, PW):
             raise ValueError("out has the wrong shape")
-    if bias is not None:
+    if wprep is not None:
+        if bias is not None:
+            _check_dev(bias, torch.float32, "bias")
+        wp, wb = _ws_args(None if ws is _NO_WS else ws)
+        pp, pb = _opt_ptr(wprep)
+        rc = lib().sconv_pool_forward_prep(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), pp, pb,
+                                           bias.data_ptr() if bias is not None else None, out.data_ptr(), wp, wb,
+                                           _stream())
+    elif bias is not None:
         _check_dev(bias, torch.float32, "bias")
         if ws is not _NO_WS or tuple(bias.shape) != (desc.K,):
             raise ValueError("bias must be [K] and cannot be combined with an explicit workspace")
@@ -381,11 +437,13 @@ def sconv_pool_forward(x, w, pool, stride=1, pad=0, groups=1, out=None, ws=_NO_W
     return out
 
 
-def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None, flush=None, zero_ratio=None):
+def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None, flush=None, zero_ratio=None,
+               wprep=None, ws=None):
     """Times every kernel variant and decomposition covering this call on x and w (synchronises)
     and makes later identical calls use the fastest.  pool=None tunes sconv_forward (with this
     relu flag), else sconv_pool_forward.  flush: a device tensor the library may overwrite to evict
-    the caches before every timed launch (cold ranking); None ranks cache-warm.
+    the caches before every timed launch (cold ranking); None ranks cache-warm.  wprep: tune the calls that
+    bring this prepared copy of w (sconv_tune_prep, with ws as its workspace argument).
     Returns (milliseconds of the chosen plan, plan name)."""
     import torch
     _check_dev(x, torch.float32, "x")
@@ -406,8 +464,15 @@ def sconv_tune(x, w, stride=1, pad=0, groups=1, pool=None, relu=False, out=None,
         if not (isinstance(flush, torch.Tensor) and flush.is_cuda and flush.is_contiguous()):
             raise TypeError("flush must be a contiguous tensor in device memory")
         fptr, fbytes = flush.data_ptr(), flush.numel() * flush.element_size()
-    rc = lib().sconv_tune(ctypes.byref(desc), 1 if pooled else 0, x.data_ptr(), w.data_ptr(), out.data_ptr(),
-                          fptr, fbytes, _stream(), ctypes.byref(ms))
+    if wprep is not None:
+        wp, wb = _ws_args(ws)
+        pp, pb = _opt_ptr(wprep)
+        rc = lib().sconv_tune_prep(ctypes.byref(desc), 1 if pooled else 0, x.data_ptr(), w.data_ptr(), pp, pb,
+                                   out.data_ptr(), wp, wb, fptr, fbytes, _stream(), ctypes.byref(ms))
+        desc.flags |= SCONV_PREPARED_FILTERS
+    else:
+        rc = lib().sconv_tune(ctypes.byref(desc), 1 if pooled else 0, x.data_ptr(), w.data_ptr(), out.data_ptr(),
+                              fptr, fbytes, _stream(), ctypes.byref(ms))
     if rc:
         raise SconvError(rc, "sconv_tune")
     return float(ms.value), sconv_plan_name(desc, pooled)

@@ -95,7 +95,7 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     if (d->stride <= 0 || d->pad < 0 || d->groups <= 0) return SCONV_EINVAL;
     if (d->C % d->groups || d->K % d->groups) return SCONV_EINVAL;
     if (d->pad >= d->R || d->pad >= d->S) return SCONV_EINVAL;
-    if (d->flags & ~(SCONV_RELU | SCONV_ZERO_RATIO_MASK)) return SCONV_EINVAL;
+    if (d->flags & ~(SCONV_RELU | SCONV_PREPARED_FILTERS | SCONV_ZERO_RATIO_MASK)) return SCONV_EINVAL;
     if (d->H + 2 * (int64_t)d->pad < d->R || d->W + 2 * (int64_t)d->pad < d->S) return SCONV_EINVAL;
 
     Problem p;
@@ -114,6 +114,7 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
     p.relu = (d->flags & SCONV_RELU) ? 1 : 0;
     const int zcode = (d->flags & SCONV_ZERO_RATIO_MASK) >> SCONV_ZERO_RATIO_SHIFT;   // 0: not given
     p.zhint = zcode ? (float)(zcode - 1) / 254.0f : -1.0f;
+    p.wprep = nullptr;
     if (pooled) {
         if (d->pool_h <= 0 || d->pool_w <= 0 || d->pool_stride <= 0) return SCONV_EINVAL;
         if (d->pool_h > p.OH || d->pool_w > p.OW) return SCONV_EINVAL;
@@ -154,7 +155,8 @@ struct Tuned {
     float ms;
     char name[48];
 };
-typedef std::array<int32_t, 16> TuneKey;   // the descriptor's fields, the pooled flag, the density bucket
+typedef std::array<int32_t, 17> TuneKey;   // the descriptor's fields, the pooled flag, the density bucket,
+                                           // whether the call brings prepared filters
 
 static std::mutex g_lock;                  // planning, enqueueing and the tuning cache
 static std::map<TuneKey, Tuned> g_tuned;
@@ -171,7 +173,7 @@ static TuneKey tune_key(const Problem& p, bool pooled)
 {
     return TuneKey{p.N, p.C, p.H, p.W, p.K, p.R, p.S, p.stride, p.pad, p.G,
                    pooled ? p.ph : 0, pooled ? p.pw : 0, pooled ? p.ps : 0, p.relu, pooled ? 1 : 0,
-                   density_bucket(p)};
+                   density_bucket(p), p.wprep ? 1 : 0};
 }
 
 // The tuned entry for this problem, unless SCONV_VARIANT pins the variant.  Caller holds g_lock.
@@ -241,6 +243,9 @@ static bool small_gen_split(const Problem& p, bool pooled, bool have_ws)
 static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanPin* static_pin = nullptr,
                       float z = -1.0f)
 {
+    // the vector kernel's transposed-filter form needs the transposed filters: brought by the call, or room
+    // for them in a workspace
+    const bool have_wt = have_ws || p.wprep != nullptr;
     if (static_pin) memset(static_pin, 0, sizeof(*static_pin));
     const char* pin = env_value("SCONV_VARIANT");
     if (pin && !strcmp(pin, "rows")) return V_ROWS;
@@ -268,7 +273,13 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // Maps of 7x7 and below are one whole-map tile of the vector kernel (no halo, no ragged
         // tiles); it measures 1.4-1.8x faster there than either matrix kernel.
         if (p.H <= 7 && p.W <= 7 && tap_supported(p, pooled)) return V_TAP;
-        if (small_gen_split(p, pooled, have_ws)) return V_GEN;
+        // With prepared filters the vector kernel's transposed-filter form, split over workgroups, leads on
+        // small launches of 64 M multiply-adds or more with 128 or more channels per group (896 in 7 groups
+        // @14x14 at batch 1: 16.9 against 21.9 us on the general kernel; 160 -> 320 @14x14: 13.8 against 16.2;
+        // 512 @28x28: 40 against 47 on the matrix kernel's split tiles; 256 @56x56 stays there: 46 against 49).
+        const bool prep_small_tap = p.wprep && have_ws && p.stride == 1 && p.Cg >= 128 && tap_supported(p, pooled) &&
+                                    (double)p.N * p.K * p.OH * p.OW * p.Cg * 9.0 >= 64e6;
+        if (!prep_small_tap && small_gen_split(p, pooled, have_ws)) return V_GEN;
         const long long quad_tiles_z = (long long)((p.OH + 1) / 2) * ((p.OW + 27) / 28) * ((p.Kg + 63) / 64) *
                                        p.N * p.G;
         if (z >= 0.0f && quad_tiles_z >= 400 && tap_supported(p, pooled)) {
@@ -307,7 +318,7 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // measures 1.0-1.15x faster than the 6-element granule from 70 % zeros up (and 1.1x slower
         // at 60 %).
         if (p.W <= 14 && p.Cg >= 256 && tap_supported(p, pooled)) return V_TAP;
-        if (have_ws && small_quad_split(p, pooled, static_pin)) return V_QUAD;
+        if (have_ws && !(prep_small_tap && p.Cg >= 512) && small_quad_split(p, pooled, static_pin)) return V_QUAD;
         // The same one stage earlier, 512 channels on maps up to 28 wide: 1.14x faster at 75 % zeros.
         if (p.W <= 28 && p.Cg >= 512 && !pooled && tap_supported(p, pooled)) return V_TAP;
         // Maps up to 14 wide with 128 or more filters per group and shorter channel loops: the
@@ -327,14 +338,14 @@ static Variant choose(const Problem& p, bool pooled, bool have_ws = false, PlanP
         // Fused pooling on wider maps, 128 or more channels per group, a workspace for the transposed
         // filters: the vector kernel's 2x14 pooled tiles measure 1.1-1.27x faster than the matrix kernel's at
         // 70-78 % zeros (a reported ratio below 68 % keeps the matrix kernel)
-        if (pooled && have_ws && p.Cg >= 128 && !(z >= 0.0f && z < 0.68f) && tap_supported(p, pooled)) return V_TAP;
+        if (pooled && have_wt && p.Cg >= 128 && !(z >= 0.0f && z < 0.68f) && tap_supported(p, pooled)) return V_TAP;
         // Zero ratio unknown, 128 or more channels per group, a workspace for the transposed filters: the
         // vector kernel.  Over 80 random large launches (64-512 channels, maps 7-56 wide, 40-90 % zeros, each
         // variant pinned) always taking it here costs 9 % on average and 2.0x at worst against the best variant
         // of each shape, quad3x3 27 % and 2.1x: a sparse map punishes the matrix kernels more than a dense one
         // punishes per-element skipping, and the paper's maps are the sparse ones (Fig. 2).  A reported ratio
         // (SCONV_ZERO_RATIO) replaces this guess: 1-4 % and 1.33x.
-        if (z < 0.0f && have_ws && p.Cg >= 128 && tap_supported(p, pooled)) return V_TAP;
+        if (z < 0.0f && have_wt && p.Cg >= 128 && tap_supported(p, pooled)) return V_TAP;
         // Maps whose width fills quad3x3's 28-column tiles badly (20, 40: a quarter or more of the tile columns
         // empty), whatever the channel count: 96 @40x40 at 60 / 90 % zeros 127 / 50 against 193 / 100 us
         if (p.W > 16 && (p.OW + 27) / 28 * 28 * 100 > p.OW * 115 && tap_supported(p, pooled)) return V_TAP;
@@ -510,6 +521,11 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         v_static = choose(p, pooled);
         have_static = try_one(v_static, nullptr);
     }
+    // A fused call keeps the convolution tensor on chip (Section 6.4): plans that split its channels over
+    // workgroups - plain tiles whose partial sums pass through the workspace to a kernel that pools - are
+    // candidates only for launches too small to fill the chip, as in the static rules.
+    const long long fused_tile_wgs = (long long)((p.OH + 4) / 5) * ((p.OW + 6) / 7) * ((p.Kg + 63) / 64) * p.N * p.G;
+    const bool fused_split_ok = !pooled || fused_tile_wgs < 128;
     for (const Family& f : fams) {
         if (!f.ok || err != SCONV_OK) continue;
         for (const char* const* g = f.geoms; *g && err == SCONV_OK; ++g) {
@@ -520,11 +536,13 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
             snprintf(pin.geom, sizeof(pin.geom), "%s", *g);
             // (a plain geometry serves a fused call only with its channels split: start there)
             const bool unsplit_ok = try_one(f.v, &pin);
-            if (!unsplit_ok && !(pooled && f.nss_hi > 1)) continue;
+            // (that plan comes again below under its explicit decomposition, which is what the record names)
+            if (unsplit_ok) cands.pop_back();
+            if (!unsplit_ok && !(pooled && f.nss_hi > 1 && fused_split_ok)) continue;
             // a geometry whose own split is twice as slow as the fastest plan so far is not worth its
             // other decompositions
             if (unsplit_ok && fastest > 0.0f && last_t > 2.0f * fastest) continue;
-            for (int nss = unsplit_ok ? 1 : 2; nss <= f.nss_hi && err == SCONV_OK; nss *= 2) {
+            for (int nss = unsplit_ok ? 1 : 2; nss <= (fused_split_ok ? f.nss_hi : 1) && err == SCONV_OK; nss *= 2) {
                 bool any = false;   // a split the launch is too large for applies with no nwv, ncs
                 for (int nwv = f.nwv_lo; nwv <= f.nwv_hi && err == SCONV_OK; nwv *= 2) {
                     for (int ncs = 1; ncs <= nwv && err == SCONV_OK; ncs *= 2) {
@@ -726,6 +744,79 @@ extern "C" int sconv_pool_forward_bias(const sconv_desc_t* desc, const float* x_
     return run(p, true, x_dev, w_dev, y_dev, (hipStream_t)hip_stream);
 }
 
+extern "C" int sconv_filter_prep_size(const sconv_desc_t* desc, size_t* bytes)
+{
+    if (!bytes) return SCONV_EINVAL;
+    Problem p;
+    bool pooled = desc && (desc->pool_h > 0 || desc->pool_w > 0 || desc->pool_stride > 0);
+    int rc = fill_problem(desc, pooled, &p);
+    if (rc) return rc;
+    // only the vector kernel's transposed-filter form reads the layout
+    *bytes = tap_supported(p, pooled) && p.stride == 1 ? filter_prep_bytes(p) : 0;
+    return SCONV_OK;
+}
+
+extern "C" int sconv_filter_prep(const sconv_desc_t* desc, const float* w_dev, void* wprep_dev, size_t wprep_bytes,
+                                 void* hip_stream)
+{
+    if (!w_dev || !wprep_dev) return SCONV_EINVAL;
+    if (reinterpret_cast<uintptr_t>(wprep_dev) % 256) return SCONV_EINVAL;
+    size_t need = 0;
+    int rc = sconv_filter_prep_size(desc, &need);
+    if (rc) return rc;
+    if (need == 0) return SCONV_EUNSUPPORTED;
+    if (wprep_bytes < need) return SCONV_EINVAL;
+    Problem p;
+    bool pooled = desc->pool_h > 0 || desc->pool_w > 0 || desc->pool_stride > 0;
+    rc = fill_problem(desc, pooled, &p);
+    if (rc) return rc;
+    return launch_filter_prep(p, w_dev, static_cast<float*>(wprep_dev), (hipStream_t)hip_stream);
+}
+
+// Checks the optional operands of the ..._prep calls and attaches them to the problem.
+static int attach_prep(Problem* p, bool pooled, const void* wprep_dev, size_t wprep_bytes, const float* bias_dev,
+                       void* ws_dev, size_t ws_bytes)
+{
+    if ((ws_dev == nullptr) != (ws_bytes == 0) || reinterpret_cast<uintptr_t>(ws_dev) % 16) return SCONV_EINVAL;
+    if ((wprep_dev == nullptr) != (wprep_bytes == 0) || reinterpret_cast<uintptr_t>(wprep_dev) % 256) return SCONV_EINVAL;
+    p->bias = bias_dev;
+    if (wprep_dev) {
+        // a descriptor no kernel reads the layout for ignores it; one that does needs all of it
+        if (tap_supported(*p, pooled) && p->stride == 1) {
+            if (wprep_bytes < filter_prep_bytes(*p)) return SCONV_EINVAL;
+            p->wprep = static_cast<const float*>(wprep_dev);
+        }
+    }
+    return SCONV_OK;
+}
+
+extern "C" int sconv_forward_prep(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                  const void* wprep_dev, size_t wprep_bytes, const float* bias_dev, float* y_dev,
+                                  void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, false, &p);
+    if (rc) return rc;
+    rc = attach_prep(&p, false, wprep_dev, wprep_bytes, bias_dev, ws_dev, ws_bytes);
+    if (rc) return rc;
+    return run_with(p, false, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int sconv_pool_forward_prep(const sconv_desc_t* desc, const float* x_dev, const float* w_dev,
+                                       const void* wprep_dev, size_t wprep_bytes, const float* bias_dev,
+                                       float* y_dev, void* ws_dev, size_t ws_bytes, void* hip_stream)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, true, &p);
+    if (rc) return rc;
+    if ((int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    rc = attach_prep(&p, true, wprep_dev, wprep_bytes, bias_dev, ws_dev, ws_bytes);
+    if (rc) return rc;
+    return run_with(p, true, x_dev, w_dev, y_dev, ws_dev, ws_bytes, (hipStream_t)hip_stream);
+}
+
 extern "C" int sconv_pair_forward(const sconv_desc_t* first, const sconv_desc_t* second, const float* x_dev,
                                   const float* w1_dev, const float* bias1_dev, const float* w2_dev,
                                   const float* bias2_dev, float* mid_dev, float* y_dev, void* hip_stream)
@@ -793,10 +884,19 @@ extern "C" int sconv_maxpool(const sconv_desc_t* desc, const float* conv_dev, fl
     return launch_maxpool(p, conv_dev, y_dev, (hipStream_t)hip_stream);
 }
 
+// SCONV_PREPARED_FILTERS in a descriptor handed to the two naming calls: plan as for a call that brings
+// prepared filters.  Nothing is launched from such a Problem; the pointer only has to be non-null.
+static void mark_prepared_for_naming(const sconv_desc_t* desc, bool pooled, Problem* p)
+{
+    static const float placeholder = 0.0f;
+    if ((desc->flags & SCONV_PREPARED_FILTERS) && tap_supported(*p, pooled) && p->stride == 1) p->wprep = &placeholder;
+}
+
 extern "C" const char* sconv_variant_name(const sconv_desc_t* desc, int pooled)
 {
     Problem p;
     if (fill_problem(desc, pooled != 0, &p)) return NULL;
+    mark_prepared_for_naming(desc, pooled != 0, &p);
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled != 0)) return variant_name(t->v);
     return variant_name(choose(p, pooled != 0, split_workspace_lent(nullptr, true), nullptr, p.zhint));
@@ -812,6 +912,24 @@ extern "C" int sconv_tune(const sconv_desc_t* desc, int pooled, const float* x_d
     if (rc) return rc;
     if (pooled && (int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
     return tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, Flush{flush_dev, flush_bytes}, best_ms);
+}
+
+extern "C" int sconv_tune_prep(const sconv_desc_t* desc, int pooled, const float* x_dev, const float* w_dev,
+                               const void* wprep_dev, size_t wprep_bytes, float* y_dev, void* ws_dev, size_t ws_bytes,
+                               void* flush_dev, size_t flush_bytes, void* hip_stream, float* best_ms)
+{
+    if (!x_dev || !w_dev || !y_dev) return SCONV_EINVAL;
+    if ((flush_dev == nullptr) != (flush_bytes == 0)) return SCONV_EINVAL;
+    Problem p;
+    int rc = fill_problem(desc, pooled != 0, &p);
+    if (rc) return rc;
+    if (pooled && (int64_t)p.ph * p.pw > 64) return SCONV_EUNSUPPORTED;
+    rc = attach_prep(&p, pooled != 0, wprep_dev, wprep_bytes, nullptr, ws_dev, ws_bytes);
+    if (rc) return rc;
+    split_scratch_given(ws_dev, ws_bytes, true);
+    rc = tune(p, pooled != 0, x_dev, w_dev, y_dev, (hipStream_t)hip_stream, Flush{flush_dev, flush_bytes}, best_ms);
+    split_scratch_given(nullptr, 0, false);
+    return rc;
 }
 
 extern "C" int sconv_workspace_size(const sconv_desc_t* desc, int pooled, size_t* bytes)
@@ -864,6 +982,7 @@ extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, 
     Problem p;
     int rc = fill_problem(desc, pooled != 0, &p);
     if (rc) return rc;
+    mark_prepared_for_naming(desc, pooled != 0, &p);
     std::lock_guard<std::mutex> lock(g_lock);
     if (const Tuned* t = tuned_for(p, pooled != 0)) {
         snprintf(out, (size_t)out_size, "%s", t->name);

@@ -348,13 +348,11 @@ Plan plan_geom(const Problem& p, int split)
     const int nss = pin_nss ? pin_nss : 1;
     if (nss > 1 && (split == 0 || !split_fits(nss))) return best;
     if (pin_nss == 1 && split == 2) return best;
-    // A fused call with a pooling window other than 2x2 / stride 2 on a launch that is not small:
-    // the kernel that pools whole windows inside a 64-row tile fills its tiles poorly, and the plain
-    // kernel split two ways with the pooling in the adding kernel measures faster (384->256 3x3 /
-    // pad 1 in 2 groups @13x13 + 3x3 / stride 2 pooling, batch 32: 92 against 105 us with this
-    // pricing's decomposition, 67 with the one sconv_tune finds).
-    const bool odd_window = split == 2 && !(p.ph == 2 && p.pw == 2 && p.ps == 2);
-    if (!pin_nss && split == 2 && !small && !odd_window) return best;
+    // A fused call that is not small keeps its one kernel, the convolution tensor on chip (Section 6.4),
+    // also where the plain kernel split two ways with the pooling in the adding kernel measures faster
+    // (overlapping 3x3 / stride 2 windows fill the 64-row tiles poorly: 384->256 3x3 in 2 groups @13x13 + that
+    // pooling at batch 32, 105 us fused against 92 split); only a pinned decomposition asks for that.
+    if (!pin_nss && split == 2 && !small) return best;
     for (int nwv = 4; nwv <= 8; nwv *= 2) {
         if (KPL == 2 && nwv == 4) continue;      // 32 staging registers per thread: not built
         for (int ncs = 1; ncs <= 4; ncs *= 2) {
@@ -407,11 +405,6 @@ Plan plan_geom(const Problem& p, int split)
         if (want == 1 && split == 2) return Plan();
         best.nss = want;
         if (want > 1) best.cost = best.cost / want + 9000.0;
-    }
-    if (!pin_nss && odd_window && !small && best.cost >= 0.0) {
-        if (nchunks < 2 || !split_fits(2)) return Plan();
-        best.nss = 2;
-        best.cost = best.cost / 2 + 9000.0;
     }
     return best;
 }

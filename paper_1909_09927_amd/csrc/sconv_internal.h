@@ -19,6 +19,9 @@ struct Problem {
     int relu;            // apply max(.,0) before the store
     float zhint;         // the map's zero ratio as the caller reported it in the descriptor; negative: unknown
     const float* bias;   // device, [K]: added to every result of filter k before the ReLU; null = none
+    const float* wprep;  // device: the filters in the transposed layout (filter_prep_bytes), written by the
+                         // caller beforehand with sconv_filter_prep; null = none (a kernel that wants the layout
+                         // writes it into the workspace before its launch)
 };
 
 // The bias of filter kglob (0 when the call carries none).
@@ -125,6 +128,13 @@ int launch_split_reduce(const Problem& p, bool pooled, const float* part, int ns
 // copy per device.  Looks its address up on the current device at the first call there.
 constexpr size_t kStaticScratchBytes = size_t(16) << 20;
 int split_static_scratch(float** ptr, size_t* bytes);
+
+// Transposed layout of 3x3 filters for kernels whose 64 lanes read 64 consecutive filters of one (channel,
+// tap) in one load: w[K][Cg][9] -> wt[group][block of 64 filters][channel * 9 + tap][64], the blocks of a
+// group padded with zeros to an even count (so that a lane pair of filters k, k + 64 always has both blocks).
+// filter_prep_bytes: size of the copy, a multiple of 256; launch_filter_prep enqueues the kernel that writes it.
+size_t filter_prep_bytes(const Problem& p);
+int launch_filter_prep(const Problem& p, const float* w, float* wt, hipStream_t stream);
 
 // Candidate geometry names of the variants (for sconv_tune); null-terminated arrays.
 const char* const* pw_geoms();

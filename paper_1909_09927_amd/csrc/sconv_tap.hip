@@ -512,16 +512,35 @@ const Candidate* select_tap(const Problem& p, bool pooled, hipStream_t stream, P
     // at batch 8 71, against 257, 146 and 78 on the matrix kernel's pooled tiles).
     int dn = 0, dc = 0, ds = 0;
     pinned_split("SCONV_TAP_SPLIT", &dn, &dc, &ds);
-    if (!pin && !dn && can_split && p.stride == 1 && p.Cg >= 128 && (p.H > 7 || p.W > 7)) {
+    // With prepared filters (the call brings the transposed copy: no transposition before the launch) the same
+    // kernel also leads on smaller launches and on whole-map tiles - 512 @7x7 at batch 32: 64 against 72 us,
+    // 2048 in 16 groups @7x7: 58 against 70, 384 @5x5 in 2 groups: 18 against 22 - and, split over workgroups,
+    // on batch-1 layers of 64 M multiply-adds or more (512 @28x28: 40 against 46 us on the matrix kernel's
+    // split tiles, 512 @14x14: 20.5 against 24.6, 256 @14x14: 13.6 against 15.8; smaller ones are level or
+    // behind the staged kernel: two launches take 13.5 us whatever they hold).
+    const bool prep = p.wprep != nullptr;
+    const bool whole_map = p.H <= 7 && p.W <= 7;
+    if (!pin && !dn && (can_split || prep) && p.stride == 1 && p.Cg >= 128 && !(whole_map && (pooled || !prep))) {
         const long long tile_wgs = (long long)((p.OH + 4) / 5) * ((p.OW + 6) / 7) * ((p.Kg + 63) / 64) * p.N * p.G;
+        const double macs = (double)p.N * p.K * p.OH * p.OW * p.Cg * 9.0;
         const char* want = nullptr;
-        if (tile_wgs >= (pooled ? 256 : 512))   // (pooled: measured from 384 up)
+        // split argument of the plan: 0 none, 1 allowed, 2 plain tiles serving a fused call
+        int mode = prep && can_split && !pooled ? 1 : 0;
+        if (tile_wgs >= (prep ? 128 : (pooled ? 256 : 512)))   // (pooled: measured from 384 up)
             // (below about 85 % zeros the test of four positions at once rarely spares the four single
             // tests: the form without it measures 2-4 % faster when the caller reported such a ratio)
-            want = !pooled ? (p.zhint >= 0.0f && p.zhint < 0.85f ? "5x7k1tn" : "5x7k1t") : (p.W == 14 ? (p.Kg >= 128 ? "p2x14k2t" : "p4x14k1t") : "p2x14hk1t");
+            want = !pooled ? (p.H == 7 && p.W == 7 ? "7x7k1t" : (p.zhint >= 0.0f && p.zhint < 0.85f ? "5x7k1tn" : "5x7k1t"))
+                           : (p.W == 14 ? (p.Kg >= 128 && !prep ? "p2x14k2t" : (prep ? "p2x14k1t" : "p4x14k1t")) : "p2x14hk1t");
+        else if (prep && can_split && macs >= 64e6) {
+            // (5x7 tiles also on 7x7 maps: two tiles per image instead of one)
+            want = p.zhint >= 0.0f && p.zhint < 0.85f ? "5x7k1tn" : "5x7k1t";
+            mode = pooled ? 2 : 1;
+        }
         for (const Candidate& c : kCandidates) {
             if (!want || strcmp(want, c.name) != 0) continue;
-            const Plan pl = c.plan(p, 0);
+            if (c.need_h && p.H != c.need_h) continue;
+            if (c.need_w && p.W != c.need_w) continue;
+            const Plan pl = c.plan(p, mode);
             if (pl.cost >= 0.0) {
                 best = &c;
                 best_plan = pl;

@@ -36,6 +36,7 @@ struct TapCfg {
     int NSS;            // workgroups splitting the channels of a tile; above 1 the results are raw
                         // partial sums, stored into slice blockIdx.z % NSS of y
     int RW;             // slices whose sums fit into LDS side by side during the slice reduction
+    int wt_blocks = 0;  // transposed-filter kernel: blocks of 64 filters per group in the transposed layout
     int xcd_remap = 0;  // transposed-filter kernel: XCD groups along the filter blocks (1, 2, 4, 8; 0 = as launched)
 };
 

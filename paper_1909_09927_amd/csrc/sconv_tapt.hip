@@ -11,10 +11,12 @@
 // wavefront's own prefetch, which one channel's products cover.
 //
 // The price: filters must be readable 64 lanes = 64 consecutive filters at a time, which the
-// [K][C/G][3][3] layout is not (consecutive filters lie 36*C/G bytes apart).  A first small kernel
-// writes a transposed copy, [group][filter block][channel][tap][KB], zero-filled past the group's
-// last filter, into the caller's workspace (9.4 MB for 512 x 512 filters, about 5 us); without a
-// workspace the plans of this file do not apply and the staged kernel runs.
+// [K][C/G][3][3] layout is not (consecutive filters lie 36*C/G bytes apart).  The kernel reads a
+// transposed copy, [group][block of 64 filters][channel][tap][64], zero-filled past the group's last
+// filter.  A caller whose filters stay the same from call to call writes it once (sconv_filter_prep) and
+// passes it with every call; otherwise a first small kernel writes it into the caller's workspace before
+// every launch (9.4 MB for 512 x 512 filters, about 10 us); with neither the plans of this file do not
+// apply and the staged kernel runs.
 #include <stdio.h>
 #include <string.h>
 
@@ -30,11 +32,12 @@ namespace {
 
 #include "sconv_tap_common.h"
 
-// w[K][Cg][9] -> wt[(g * kblocks + kb) * Cg * 9 + ct][KB] with ct = c * 9 + tap, through a 64 x 64 LDS
+// w[K][Cg][9] -> wt[(g * kblocks + kb) * Cg * 9 + ct][64] with ct = c * 9 + tap, through a 64 x 64 LDS
 // tile so that both sides are accessed in runs of 64 consecutive words.
-__global__ __launch_bounds__(1024) void transpose_filters_kernel(Problem p, int KB, int kblocks,
+__global__ __launch_bounds__(1024) void transpose_filters_kernel(Problem p, int kblocks,
                                                                 const float* __restrict__ w, float* __restrict__ wt)
 {
+    constexpr int KB = 64;
     __shared__ float tile[64][65];
     const int ct0 = blockIdx.x * 64;          // first (channel, tap) entry of the tile
     const int kk0 = blockIdx.y * 64;          // first filter of the tile inside the group's padded range
@@ -112,7 +115,9 @@ __global__ __launch_bounds__(NWV * 64) void tapt_kernel(Problem p, TapCfg cfg, c
     }
     const float* xg = x + ((size_t)n * p.C + (size_t)g * p.Cg) * HWp;
     // the block's transposed filters: entry (c, tap) of filter lane + 64*i at wl[(c*9 + tap)*KB + 64*i]
-    const float* wl = wt + ((size_t)g * gridDim.y + by) * p.L * G::KB + lane;
+    // (filter register i of the lane: block by * KPL + i, cfg.wt_blocks blocks per group)
+    const float* wl = wt + ((size_t)g * cfg.wt_blocks + (size_t)by * G::KPL) * p.L * 64 + lane;
+    const size_t wblock = (size_t)p.L * 64;
 
     float acc[G::KPL][G::ACC];
 #pragma unroll
@@ -133,11 +138,12 @@ __global__ __launch_bounds__(NWV * 64) void tapt_kernel(Problem p, TapCfg cfg, c
         }
     };
     auto load_w = [&](int c, float (&dst)[G::KPL][9]) {
-        const float* base = wl + (size_t)c * 9 * G::KB;
 #pragma unroll
-        for (int j = 0; j < 9; ++j)
+        for (int i = 0; i < G::KPL; ++i) {
+            const float* base = wl + i * wblock + (size_t)c * 9 * 64;
 #pragma unroll
-            for (int i = 0; i < G::KPL; ++i) dst[i][j] = base[j * G::KB + 64 * i];
+            for (int j = 0; j < 9; ++j) dst[i][j] = base[j * 64];
+        }
     };
 
     float xn[G::NX], wn[G::KPL][9];
@@ -187,13 +193,26 @@ int launch_nwv(const Problem& p, const TapCfg& cfg, dim3 grid, size_t lds_bytes,
     return launch_status();
 }
 
-size_t wt_bytes(const Problem& p, int KB)
-{
-    const size_t kblocks = (p.Kg + KB - 1) / KB;
-    return ((size_t)p.G * kblocks * p.L * KB * sizeof(float) + 255) / 256 * 256;
-}
+int prep_blocks(const Problem& p) { return (p.Kg + 127) / 128 * 2; }
+
+// bytes of the workspace a launch keeps for the transposed filters: none when the caller brought them
+size_t wt_bytes(const Problem& p) { return p.wprep ? 0 : filter_prep_bytes(p); }
 
 }  // namespace
+
+size_t filter_prep_bytes(const Problem& p)
+{
+    return ((size_t)p.G * prep_blocks(p) * p.L * 64 * sizeof(float) + 255) / 256 * 256;
+}
+
+int launch_filter_prep(const Problem& p, const float* w, float* wt, hipStream_t stream)
+{
+    const int kblocks = prep_blocks(p);
+    const dim3 tgrid((unsigned)((p.L + 63) / 64), (unsigned)kblocks, (unsigned)p.G);
+    if (tgrid.y > 65535 || tgrid.z > 65535) return SCONV_EUNSUPPORTED;
+    hipLaunchKernelGGL(transpose_filters_kernel, tgrid, dim3(1024), 0, stream, p, kblocks, w, wt);
+    return launch_status();
+}
 
 // Decomposition of one launch of the transposed-filter kernel: wavefronts per workgroup nwv = NT tiles
 // x NCS channel slices (slices only add up through LDS at the end), NSS workgroups per tile along the
@@ -203,7 +222,8 @@ template <class G>
 Plan plan_tapt(const Problem& p, int split)
 {
     Plan best;
-    if (!split_scratch_possible(nullptr) || split_scratch_bytes() < wt_bytes(p, G::KB)) return best;
+    // the transposed filters come with the call, or are written into the workspace first
+    if (!p.wprep && (!split_scratch_possible(nullptr) || split_scratch_bytes() < wt_bytes(p))) return best;
     TapCfg cfg;
     cfg.tiles_y = (p.OH + G::TH - 1) / G::TH;
     cfg.tiles_x = (p.OW + G::TW - 1) / G::TW;
@@ -220,19 +240,32 @@ Plan plan_tapt(const Problem& p, int split)
         // keeps 16 channels - many short wavefronts even out the last round -, one tile per workgroup,
         // two from 512 channels up (plain tiles only); pooled tiles of 14-wide maps, few per image, sixteen slices.
         ncs = 1;
-        const int want = (G::POOL && G::HW == 0) ? 16 : 8;
+        // (a whole-map tile is the only tile of its image: all wavefronts of its workgroup are slices of it)
+        const int want = ((G::POOL && G::HW == 0) || (cfg.ntiles == 1 && p.Cg >= 512 && G::MAXW == 16)) ? 16 : 8;
         while (ncs < want && p.Cg / (ncs * 2) >= 16 && p.Cg % (ncs * 2) == 0) ncs *= 2;
         nwv = ((p.Cg >= 512 && !G::POOL) || ncs == 16) && G::MAXW == 16 ? 16 : 8;
         if (ncs > nwv) ncs = nwv;
+        if (cfg.ntiles == 1 && ncs >= 8) nwv = ncs;
         if (split == 2) nss = 2;
-        // (small launches: the channels of a tile over several workgroups as well)
-        while (split >= 1 && nss < 16 && tile_waves * ncs * nss < 2 * 1024 && p.Cg / (ncs * nss * 2) >= 16) nss *= 2;
+        // (small launches: the channels of a tile over several workgroups as well, until 3072 to 4096 wavefronts -
+        // about half of what the chip holds - share the work; a wavefront keeps 16 channels, or 4 when the launch has
+        // fewer than 1024 wavefronts to begin with - sconv_tune's picks with prepared filters: 512 @28x28 at batch 1
+        // 8 slices x 4 workgroups, 512 @14x14 and 256 @14x14 x 8, 512 @7x7 x 16, 2048 in 16 groups @7x7 x 4;
+        // 192 -> 384 @7x7 at batch 32, 24 channels per wavefront, unsplit)
+        // (the smallest stop at 3072: 512 @14x14 at batch 1 runs 20.5 us 8 ways and 23.5 us 16 ways)
+        const int keep = tile_waves * ncs < 1024 ? 4 : 16;
+        const long long fill = tile_waves * ncs < 1024 ? 3072 : 4096;
+        while (split >= 1 && split_scratch_possible(nullptr) && nss < 16 && tile_waves * ncs * nss < fill &&
+               p.Cg / (ncs * nss * 2) >= keep && p.Cg % (ncs * nss * 2) == 0)
+            nss *= 2;
+        // (and then one tile per workgroup: with two, half of the workgroups)
+        if (nss > 1 && nwv > ncs && ncs >= 8) nwv = ncs;
     }
     if (nwv != 8 && !(nwv == 16 && G::MAXW == 16)) return best;
     // (16 wavefronts leave 128 registers: two filters per lane on a 5x7 tile do not fit without spilling)
     if (nwv == 16 && G::KPL * G::ACC > 60) return best;
     if (ncs < 1 || ncs > nwv || (ncs & (ncs - 1)) || nss < 1 || p.Cg % (ncs * nss)) return best;
-    if (nss > 1 && (split == 0 || G::POOL || wt_bytes(p, G::KB) + nss * part_bytes > split_scratch_bytes() ||
+    if (nss > 1 && (split == 0 || G::POOL || !split_scratch_possible(nullptr) || wt_bytes(p) + nss * part_bytes > split_scratch_bytes() ||
                     (long long)p.N * p.G * nss > 65535))
         return best;
     if (nss == 1 && split == 2) return best;
@@ -269,14 +302,14 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
     const long long gz = (long long)p.N * p.G * pl.nss;
     if (gz > 65535 || pl.kblocks > 65535 || gx >= (1LL << 31)) return SCONV_EUNSUPPORTED;
     float* ws = split_scratch(stream);
-    const size_t wtb = wt_bytes(p, G::KB);
-    if (!ws || split_scratch_bytes() < wtb) return SCONV_EUNSUPPORTED;
-    float* wt = ws;
-    float* part = ws + wtb / sizeof(float);
+    const size_t wtb = wt_bytes(p);
+    if (!p.wprep && (!ws || split_scratch_bytes() < wtb)) return SCONV_EUNSUPPORTED;
+    const float* wt = p.wprep ? p.wprep : ws;
+    float* part = ws ? ws + wtb / sizeof(float) : nullptr;
     Problem q = p;
     float* out = y;
     if (pl.nss > 1) {
-        if (G::POOL || wtb + (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes())
+        if (G::POOL || !part || wtb + (size_t)pl.nss * p.N * p.K * p.OH * p.OW * sizeof(float) > split_scratch_bytes())
             return SCONV_EUNSUPPORTED;
         out = part;
         q.relu = 0;
@@ -285,12 +318,12 @@ int launch_tapt(const Plan& pl, const Problem& p, bool pooled, const float* x, c
         return SCONV_EUNSUPPORTED;
     }
     if (p.Cg % (pl.cfg.NCS * pl.nss)) return SCONV_EUNSUPPORTED;
-    const dim3 tgrid((unsigned)((p.L + 63) / 64), (unsigned)((pl.kblocks * G::KB + 63) / 64), (unsigned)p.G);
-    if (tgrid.y > 65535 || tgrid.z > 65535) return SCONV_EUNSUPPORTED;
-    hipLaunchKernelGGL(transpose_filters_kernel, tgrid, dim3(1024), 0, stream, p, G::KB, pl.kblocks, w, wt);
-    if (launch_status() != SCONV_OK) return SCONV_ELAUNCH;
+    if (!p.wprep) {
+        if (const int trc = launch_filter_prep(p, w, ws, stream)) return trc;
+    }
     const dim3 grid((unsigned)gx, (unsigned)pl.kblocks, (unsigned)gz);
     TapCfg cfg = pl.cfg;
+    cfg.wt_blocks = prep_blocks(p);
     // XCD groups along the filter blocks (a) and along grid z (8 / a): the split that makes an XCD fetch the
     // least - filters / a + input * a / 8 - among those that divide the grid evenly and leave an XCD at most
     // 2.5 MB of filters, so that they stay in its 4 MB L2 while the input streams through

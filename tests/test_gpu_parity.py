@@ -478,6 +478,117 @@ def test_transposed_filter_kernel(device, monkeypatch, shp, split):
         pytest.skip("no geometry of this kernel fits the shape with this decomposition")
 
 
+def _prep_reference(w, groups):
+    """The prepared layout written out on the host: [group][block of 64 filters, even count][channel * 9 + tap][64]."""
+    K, Cg, R, S = w.shape
+    Kg = K // groups
+    blocks = (Kg + 127) // 128 * 2
+    out = np.zeros((groups, blocks, Cg * R * S, 64), dtype=np.float32)
+    for g in range(groups):
+        for k in range(Kg):
+            out[g, k // 64, :, k % 64] = w[g * Kg + k].reshape(-1)
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("shp", TAPT[:3] + [(1, 32, 8, 8, 200, 3, 3, 1, 1, 1, None)])
+def test_filter_prep_writes_the_documented_layout(device, shp):
+    """sconv_filter_prep is a permutation with zero padding: bit for bit the layout the header documents."""
+    layer, x, w = _mk(325, shp)
+    got = sconv.sconv_filter_prep(to_dev(w), groups=shp[9])
+    torch.cuda.synchronize()
+    ref = _prep_reference(w, shp[9])
+    got = got.cpu().numpy().view(np.float32)
+    assert got.size >= ref.size and np.array_equal(got[:ref.size].view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("split", [None, "8,1", "8,8", "16,4", "8,2,2"])
+@pytest.mark.parametrize("shp", TAPT[:3] + [TAPT[4], (4, 128, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)),
+                                           (2, 128, 28, 28, 128, 3, 3, 1, 1, 1, (2, 2, 2))])
+def test_prepared_filters_through_the_transposed_filter_kernel(device, monkeypatch, shp, split):
+    """Calls that bring prepared filters (sconv_forward_prep / sconv_pool_forward_prep): the transposed-filter
+    kernel reads the caller's copy - with a workspace (split plans), and without any - and must meet the oracle
+    like every other path; bias through the same call; integer inputs bit for bit."""
+    import oracle
+    pooled = shp[10] is not None
+    if split is None:
+        monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    else:
+        parts = [int(t) for t in split.split(",")]
+        if (shp[1] // shp[9]) % (parts[1] * (parts[2] if len(parts) > 2 else 1)):
+            pytest.skip("the slices do not divide the channels")
+        monkeypatch.setenv("SCONV_VARIANT", "tap")
+        monkeypatch.setenv("SCONV_TAP_SPLIT", split)
+    geoms = [None] if split is None else (
+        (["p2x14k1t", "p2x14k2t", "p4x14k1t"] if shp[3] == 14 else ["p2x14hk1t", "p4x6k1t"]) if pooled
+        else ["5x7k1t", "5x7k1tn", "5x7k2t"] + (["7x7k1t"] if shp[2] == 7 else []))
+    own = torch.empty(48 << 20, dtype=torch.uint8, device="cuda")
+    ran = 0
+    for geom in geoms:
+        if geom and "k2" in geom and shp[4] // shp[9] <= 64:
+            continue
+        if geom:
+            monkeypatch.setenv("SCONV_TAP_GEOM", geom)
+        for integer in (False, True):
+            layer, x, w = _mk(326 + integer, shp, integer=integer)
+            b = (np.arange(shp[4]) % 5 - 2).astype(np.float32)
+            xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+            wp = sconv.sconv_filter_prep(wd, groups=shp[9])
+            assert wp is not None
+            if pooled:
+                ref, scale = oracle.conv_pool(x, w, layer.pool, 1, 1, shp[9])
+                refb, scaleb = oracle.conv_pool_bias(x, w, b, layer.pool, 1, 1, shp[9])
+                call = lambda **kw: sconv.sconv_pool_forward(xd, wd, layer.pool, 1, 1, shp[9], wprep=wp, **kw)
+            else:
+                ref, scale = oracle.conv(x, w, 1, 1, shp[9], relu=True)
+                refb, scaleb = oracle.conv_bias(x, w, b, 1, 1, shp[9], relu=True)
+                call = lambda **kw: sconv.sconv_forward(xd, wd, 1, 1, shp[9], relu=True, wprep=wp, **kw)
+            outs = []
+            for what, kw, r, sc in (("no workspace", {}, ref, scale), ("own workspace", {"ws": own}, ref, scale),
+                                    ("bias", {"ws": own, "bias": bd}, refb, scaleb)):
+                try:
+                    outs.append((call(**kw), r, sc, what))
+                except sconv.SconvError as e:
+                    # a pinned split across workgroups needs the workspace: without one the pinned plan does
+                    # not apply and the pinned variant has nothing else to offer
+                    assert e.code == sconv.SCONV_EUNSUPPORTED and split is not None, what
+            torch.cuda.synchronize()
+            for got, r, sc, what in outs:
+                g = got.cpu().numpy().astype(np.float64)
+                if integer:
+                    assert np.array_equal(g, r), f"{geom} {what}: integer inputs must be exact"
+                else:
+                    err = np.abs(g - r)
+                    assert (err <= 1e-4 * sc).all(), f"{geom} {what}: {int((err > 1e-4 * sc).sum())} beyond the bar"
+            ran += len(outs)
+    if not ran:
+        pytest.skip("no geometry of this kernel fits the shape with this decomposition")
+
+
+def test_prepared_filters_are_ignored_where_no_kernel_reads_them_and_tuned_separately(device):
+    """A 1x1 layer has no prepared layout (size 0, the forward call runs as without); plans tuned for calls
+    with prepared filters are kept apart from those without."""
+    import oracle
+    layer, x, w = _mk(328, (2, 64, 14, 14, 64, 1, 1, 1, 0, 1, None))
+    assert sconv.sconv_filter_prep(to_dev(w), pad=0) is None
+    shp = (8, 128, 14, 14, 128, 3, 3, 1, 1, 1, None)
+    layer, x, w = _mk(329, shp)
+    xd, wd = to_dev(x), to_dev(w)
+    wp = sconv.sconv_filter_prep(wd)
+    own = torch.empty(48 << 20, dtype=torch.uint8, device="cuda")
+    try:
+        ms, plan = sconv.sconv_tune(xd, wd, 1, 1, 1, None, relu=True, wprep=wp, ws=own)
+        d_prep = sconv.make_desc(*shp[:10], None, True, prepared=True)
+        d_plain = sconv.make_desc(*shp[:10], None, True)
+        assert sconv.sconv_plan_name(d_prep) == plan and not _untuned(plan)
+        assert _untuned(sconv.sconv_plan_name(d_plain))
+        got = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, wprep=wp, ws=own)
+        torch.cuda.synchronize()
+        ref, scale = oracle.conv(x, w, 1, 1, 1, relu=True)
+        assert (np.abs(got.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+    finally:
+        sconv.sconv_tune_reset()
+
+
 @pytest.mark.parametrize("variant", ["rows", "tap", "quad", "wide", "gen", None])
 @pytest.mark.parametrize("shp", [
     (2, 32, 19, 23, 70, 3, 3, 1, 1, 1, (2, 2, 2)),

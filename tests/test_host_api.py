@@ -90,7 +90,7 @@ def test_output_dims_and_sizes():
 
 BAD = [
     dict(N=0), dict(C=0), dict(H=-1), dict(K=0), dict(R=0), dict(S=0), dict(stride=0),
-    dict(pad=-1), dict(groups=0), dict(groups=3), dict(K=30, groups=4), dict(pad=3), dict(flags=2),
+    dict(pad=-1), dict(groups=0), dict(groups=3), dict(K=30, groups=4), dict(pad=3), dict(flags=4),
     dict(H=1, pad=0),
 ]
 
@@ -288,3 +288,37 @@ def test_binding_refuses_host_tensors():
     w = torch.zeros(2, 2, 3, 3)
     with pytest.raises(TypeError):
         sconv.sconv_forward(x, w, pad=1)
+
+
+def test_filter_prep_size_and_argument_checks():
+    """Prepared filters: [group][block of 64 filters, even count][channel * 9 + tap][64] floats; only 3x3 /
+    stride 1 / pad 1 layers with channels per group a multiple of 16 have a kernel that reads them."""
+    L = sconv.lib()
+    n = ctypes.c_size_t(123)
+    d = sconv.make_desc(4, 512, 28, 28, 512, 3, 3, 1, 1)
+    assert L.sconv_filter_prep_size(ctypes.byref(d), ctypes.byref(n)) == 0
+    assert n.value == 512 * 512 * 9 * 4                       # 8 blocks of 64: nothing to pad
+    d = sconv.make_desc(1, 128, 14, 14, 192, 3, 3, 1, 1, groups=2)   # 96 filters per group -> 2 blocks
+    assert L.sconv_filter_prep_size(ctypes.byref(d), ctypes.byref(n)) == 0
+    assert n.value == 2 * 2 * (64 * 9) * 64 * 4
+    for other in (sconv.make_desc(1, 64, 14, 14, 64, 1, 1), sconv.make_desc(1, 64, 14, 14, 64, 3, 3, 2, 1),
+                  sconv.make_desc(1, 24, 14, 14, 64, 3, 3, 1, 1), sconv.make_desc(1, 64, 14, 14, 64, 5, 5, 1, 2)):
+        assert L.sconv_filter_prep_size(ctypes.byref(other), ctypes.byref(n)) == 0 and n.value == 0
+        p = ctypes.c_void_p(256)
+        assert L.sconv_filter_prep(ctypes.byref(other), p, p, 1 << 20, None) == sconv.SCONV_EUNSUPPORTED
+    assert L.sconv_filter_prep_size(ctypes.byref(d), None) == sconv.SCONV_EINVAL
+    p, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)
+    need = 2 * 2 * (64 * 9) * 64 * 4
+    assert L.sconv_filter_prep(ctypes.byref(d), None, p, need, None) == sconv.SCONV_EINVAL
+    assert L.sconv_filter_prep(ctypes.byref(d), p, None, need, None) == sconv.SCONV_EINVAL
+    assert L.sconv_filter_prep(ctypes.byref(d), p, odd, need, None) == sconv.SCONV_EINVAL      # misaligned
+    assert L.sconv_filter_prep(ctypes.byref(d), p, p, need - 1, None) == sconv.SCONV_EINVAL    # too small
+    # the forward call: a half-given, misaligned or too small prepared copy is refused before any launch
+    for f in (L.sconv_forward_prep, L.sconv_pool_forward_prep):
+        dd = sconv.make_desc(1, 128, 14, 14, 192, 3, 3, 1, 1, groups=2, pool=(2, 2, 2))
+        assert f(ctypes.byref(dd), p, p, p, 0, None, p, None, 0, None) == sconv.SCONV_EINVAL
+        assert f(ctypes.byref(dd), p, p, None, need, None, p, None, 0, None) == sconv.SCONV_EINVAL
+        assert f(ctypes.byref(dd), p, p, odd, need, None, p, None, 0, None) == sconv.SCONV_EINVAL
+        assert f(ctypes.byref(dd), p, p, p, need - 256, None, p, None, 0, None) == sconv.SCONV_EINVAL
+        assert f(ctypes.byref(dd), p, p, p, need, None, p, p, 0, None) == sconv.SCONV_EINVAL   # half-given workspace
+        assert f(ctypes.byref(dd), None, p, p, need, None, p, None, 0, None) == sconv.SCONV_EINVAL
