@@ -776,20 +776,25 @@ def run_chain(args) -> None:
     outs, recs = [], []
     flush = flush_buffer() if TUNE else None
     lend_workspace()
+    wspace = _workspaces[torch.cuda.current_stream().cuda_stream]
+    # --prepared: every layer's filters once in the prepared layout, passed with each call (with the workspace)
+    preps = [sconv.sconv_filter_prep(wd, l.groups, l.stride, l.pad) if PREP else None
+             for l, wd in zip(workloads.CHAIN, wds)]
+    extra = [({"wprep": wp, "ws": wspace} if wp is not None else {}) for wp in preps]
     zs = []
-    for layer, wd in zip(workloads.CHAIN, wds):
+    for (layer, wd), kw in zip(zip(workloads.CHAIN, wds), extra):
         # the producer's output is probed once; tuned plans are kept per density class, so two layers of
         # one shape (512 @14x14 twice, at 41 % and 88 % zeros) each keep their own
         z = sconv.zero_ratio_of(sconv.sconv_density(cur)) if (TUNE or HINT) else None
         zs.append(z)
         if TUNE:
             sconv.sconv_tune(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, relu=True, flush=flush,
-                             zero_ratio=z)
+                             zero_ratio=z, **kw)
         if layer.pool:
-            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups, zero_ratio=z)
+            y = sconv.sconv_pool_forward(cur, wd, layer.pool, layer.stride, layer.pad, layer.groups, zero_ratio=z, **kw)
         else:
-            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True, zero_ratio=z)
-        d = sconv.desc_for(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, z)
+            y = sconv.sconv_forward(cur, wd, layer.stride, layer.pad, layer.groups, relu=True, zero_ratio=z, **kw)
+        d = sconv.desc_for(cur, wd, layer.stride, layer.pad, layer.groups, layer.pool, True, z, bool(kw))
         recs.append({"layer": layer.name, "N": N, "plan": sconv.sconv_plan_name(d, bool(layer.pool)),
                      "input_zero_ratio": round(float((cur == 0).float().mean()), 4),
                      "dense_flops": 2.0 * N * layer.K * layer.OH * layer.OW * layer.Cg * 9})
@@ -801,9 +806,11 @@ def run_chain(args) -> None:
         layer = workloads.CHAIN[i]
         xi, wd, y = outs[i]
         if layer.pool:
-            sconv.sconv_pool_forward(xi, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=y, zero_ratio=zs[i])
+            sconv.sconv_pool_forward(xi, wd, layer.pool, layer.stride, layer.pad, layer.groups, out=y, zero_ratio=zs[i],
+                                     **extra[i])
         else:
-            sconv.sconv_forward(xi, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y, zero_ratio=zs[i])
+            sconv.sconv_forward(xi, wd, layer.stride, layer.pad, layer.groups, relu=True, out=y, zero_ratio=zs[i],
+                                **extra[i])
 
     def step():
         for i in range(len(outs)):
@@ -817,7 +824,8 @@ def run_chain(args) -> None:
         total += rec["dense_equiv_gflops"] * ms
         print(json.dumps(rec), flush=True)
     ms = _time(step, args.steps, args.warmup)
-    print(json.dumps({"chain": [l.name for l in workloads.CHAIN], "N": N, "ms_per_pass": round(ms, 5),
+    print(json.dumps({"chain": [l.name for l in workloads.CHAIN], "N": N, "prepared_filters": PREP,
+                      "ms_per_pass": round(ms, 5),
                       "dense_equiv_gflops": round(total / ms, 1),
                       "output_zero_ratio": round(float((cur == 0).float().mean()), 4)}), flush=True)
 

@@ -123,7 +123,10 @@ int fill_problem(const sconv_desc_t* d, bool pooled, Problem* out)
         p.PW = (p.OW - p.pw) / p.ps + 1;
         p.relu = 1;
     }
-    int64_t L = (int64_t)p.Cg * p.R * p.S;
+    // (factor by factor: Cg * R * S of three values near 2^31 does not fit 64 bits)
+    const int64_t CR = (int64_t)p.Cg * p.R;
+    if (CR >= (int64_t(1) << 24)) return SCONV_EUNSUPPORTED;
+    const int64_t L = CR * p.S;
     if (L >= (int64_t(1) << 24)) return SCONV_EUNSUPPORTED;
     p.L = (int)L;
     if (!mul_fits_31(p.N, p.C, p.H, p.W) || !mul_fits_31(p.K, p.Cg, p.R, p.S) ||
