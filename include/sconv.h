@@ -113,7 +113,8 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * pooling).  (2) "tap3x3" launches of 512 or more workgroups (256 for fused calls) with 128 or more
  * channels per group first write a transposed copy of the filters, [filter block][channel][tap][64 or 128
  * filters], into the workspace and run the form of the kernel that reads filters from it without staging
- * them in LDS.  Results stay deterministic; the association of the fp32 sums differs between plans.
+ * them in LDS (a caller with constant filters writes that copy once and passes it: the ..._prep calls below).
+ * Results stay deterministic; the association of the fp32 sums differs between plans.
  *   x_dev device, in : [N][C][H][W]
  *   w_dev device, in : [K][C/G][R][S]
  *   y_dev device, out: [N][K][OH][OW]
@@ -128,7 +129,8 @@ int sconv_forward(const sconv_desc_t* desc, const float* x_dev, const float* w_d
  *   y[n][k][ph][pw] = max over py < p_h, px < p_w of max(0, conv[n][k][ph*p_s+py][pw*p_s+px]).
  * (A launch too small to fill the chip - fewer than 128 workgroups, and only when a workspace is there,
  * see sconv_forward - is split across workgroups and passes its partial sums through that workspace; the
- * second kernel then pools.  Every larger fused call is one convolution kernel.)
+ * second kernel then pools.  Every larger fused call is one convolution kernel, whatever the pooling window,
+ * also after sconv_tune: it does not offer a split to such a call.)
  *   y_dev device, out: [N][K][PH][PW]
  * SCONV_EUNSUPPORTED if p_h*p_w > 64 or a tensor has 2^31 or more elements.
  */
