@@ -1181,6 +1181,59 @@ def test_tuned_plan_is_replayed_from_a_graph_and_yields_to_a_pinned_variant(devi
         sconv.sconv_tune_reset()
 
 
+def test_prepared_calls_keep_no_state_two_streams_and_a_graph(device, monkeypatch):
+    """The ..._prep calls take everything as arguments: two streams, each with its own workspace and its own layer,
+    run interleaved without touching each other; and such a call can be captured and replayed (no memset, no
+    allocation, no host state)."""
+    import oracle
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    shapes = [(4, 128, 14, 14, 192, 3, 3, 1, 1, 1, (2, 2, 2)), (1, 256, 14, 14, 256, 3, 3, 1, 1, 1, None)]
+    cases = []
+    for i, shp in enumerate(shapes):
+        layer, x, w = _mk(340 + i, shp)
+        xd, wd = to_dev(x), to_dev(w)
+        cases.append((layer, x, w, xd, wd, sconv.sconv_filter_prep(wd), torch.empty(32 << 20, dtype=torch.uint8, device="cuda"),
+                      torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    outs = [None, None]
+    for rep in range(4):                       # interleaved launches on the two streams
+        for i, (layer, x, w, xd, wd, wp, ws, st) in enumerate(cases):
+            with torch.cuda.stream(st):
+                if layer.pool:
+                    outs[i] = sconv.sconv_pool_forward(xd, wd, layer.pool, 1, 1, 1, wprep=wp, ws=ws, out=outs[i])
+                else:
+                    outs[i] = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, wprep=wp, ws=ws, out=outs[i])
+    torch.cuda.synchronize()
+    for i, (layer, x, w, *_rest) in enumerate(cases):
+        if layer.pool:
+            ref, scale = oracle.conv_pool(x, w, layer.pool, 1, 1, 1)
+        else:
+            ref, scale = oracle.conv(x, w, 1, 1, 1, relu=True)
+        assert (np.abs(outs[i].cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+    # capture the batch-1 layer (its plan splits the channels over workgroups: workspace traffic inside the graph)
+    layer, x, w, xd, wd, wp, ws, st = cases[1]
+    graph = torch.cuda.CUDAGraph()
+    out = torch.empty_like(outs[1])
+    with torch.cuda.stream(st):
+        sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, wprep=wp, ws=ws, out=out)
+        st.synchronize()
+        with torch.cuda.graph(graph, stream=st):
+            sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, wprep=wp, ws=ws, out=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        _, xn, _ = _mk(345 + rep, shapes[1])
+        xd.copy_(torch.from_numpy(xn))
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = sconv.sconv_forward(xd, wd, 1, 1, 1, relu=True, wprep=wp, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+        ref, scale = oracle.conv(xn, w, 1, 1, 1, relu=True)
+        assert (np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-4 * scale).all()
+
+
 def test_small_launches_on_wide_maps_take_the_split_matrix_plan_when_a_workspace_is_lent(device, monkeypatch):
     """A 3x3 launch of 200-400 matrix-kernel tiles on a 28-wide map goes to quad3x3 with its channels
     split across workgroups when the stream has a workspace, and to the vector kernel when it has
