@@ -1181,6 +1181,52 @@ def test_tuned_plan_is_replayed_from_a_graph_and_yields_to_a_pinned_variant(devi
         sconv.sconv_tune_reset()
 
 
+def _random_prepared_3x3(count, seed):
+    """3x3 / stride 1 / pad 1 layers over the ranges the static rules for prepared calls branch on: batch 1 to 32,
+    maps 5 to 28 wide (7x7 and smaller whole-map tiles among them), 128 to 512 channels per group, groups, fused
+    pooling; small enough for the whole-tensor oracle."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        G = int(rng.choice([1, 1, 1, 2, 4]))
+        Cg = int(rng.choice([128, 160, 192, 256, 384, 512]))
+        Kg = int(rng.choice([64, 96, 128, 192, 256]))
+        H = int(rng.choice([5, 6, 7, 10, 14, 20, 28]))
+        W = H if rng.random() < 0.7 else int(rng.choice([7, 14, 28]))
+        N = int(rng.choice([1, 1, 2, 4, 8, 32]))
+        if 2.0 * N * Kg * G * H * W * Cg * 9 > 1.2e10:
+            continue
+        pool = (2, 2, 2) if (rng.random() < 0.3 and H >= 6 and W >= 6) else None
+        out.append((N, Cg * G, H, W, Kg * G, 3, 3, 1, 1, G, pool))
+    return out
+
+
+@pytest.mark.parametrize("shp", _random_prepared_3x3(20, 4711))
+def test_random_layers_with_prepared_filters_through_the_static_rules(device, monkeypatch, shp):
+    """Prepared calls through the default dispatch (no pins): with a workspace (small launches split over workgroups),
+    without one, and with the zero ratio reported; whole tensors against the oracle."""
+    import oracle
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    G = shp[9]
+    layer, x, w = _mk(350, shp, z=0.8)
+    xd, wd = to_dev(x), to_dev(w)
+    wp = sconv.sconv_filter_prep(wd, groups=G)
+    assert wp is not None
+    own = torch.empty(48 << 20, dtype=torch.uint8, device="cuda")
+    if layer.pool:
+        ref, scale = oracle.conv_pool(x, w, layer.pool, 1, 1, G)
+        call = lambda **kw: sconv.sconv_pool_forward(xd, wd, layer.pool, 1, 1, G, wprep=wp, **kw)
+    else:
+        ref, scale = oracle.conv(x, w, 1, 1, G, relu=True)
+        call = lambda **kw: sconv.sconv_forward(xd, wd, 1, 1, G, relu=True, wprep=wp, **kw)
+    outs = [(call(ws=own), "workspace"), (call(), "no workspace"), (call(ws=own, zero_ratio=0.8), "hint 0.8"),
+            (call(ws=own, zero_ratio=0.3), "hint 0.3")]
+    torch.cuda.synchronize()
+    for got, what in outs:
+        err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+        assert (err <= 1e-4 * scale).all(), f"{what}: {int((err > 1e-4 * scale).sum())} outputs beyond the bar"
+
+
 def test_prepared_calls_keep_no_state_two_streams_and_a_graph(device, monkeypatch):
     """The ..._prep calls take everything as arguments: two streams, each with its own workspace and its own layer,
     run interleaved without touching each other; and such a call can be captured and replayed (no memset, no
