@@ -111,8 +111,8 @@ int sconv_encode(const sconv_desc_t* desc, int fmt, const float* x_dev, float* v
  * each stores the plain partial sums of its channel range into the workspace, and a second kernel on the
  * same stream adds them in a fixed order and applies bias and ReLU (and, for a fused call that small, the
  * pooling).  (2) "tap3x3" launches of 512 or more workgroups (256 for fused calls) with 128 or more
- * channels per group first write a transposed copy of the filters, [filter block][channel][tap][64 or 128
- * filters], into the workspace and run the form of the kernel that reads filters from it without staging
+ * channels per group first write a transposed copy of the filters, [block of 64 filters][channel][tap][64],
+ * into the workspace and run the form of the kernel that reads filters from it without staging
  * them in LDS (a caller with constant filters writes that copy once and passes it: the ..._prep calls below).
  * Results stay deterministic; the association of the fp32 sums differs between plans.
  *   x_dev device, in : [N][C][H][W]
