@@ -29,7 +29,7 @@ class Shape(ctypes.Structure):
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, OpenMP over (n, k) in oracle_conv only)."""
+    """Compile the oracle with gcc (plain -O2; OpenMP over (n, k) in oracle_conv and over the rows in oracle_spmv)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]

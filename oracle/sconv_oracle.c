@@ -171,6 +171,8 @@ void oracle_spmv(const oracle_shape_t* s, int64_t rows, const float* values, con
     const int Cg = s->C / s->groups, Kg = s->K / s->groups;
     const int64_t L = (int64_t)Cg * s->R * s->S;
     const int64_t rows_per_group = rows / ((int64_t)s->N * s->groups);
+    /* rows are independent; every (row, filter) sum is still formed by one thread, in slot order */
+#pragma omp parallel for schedule(static)
     for (int64_t row = 0; row < rows; ++row) {
         int g = (int)((row / rows_per_group) % s->groups);
         for (int kk = 0; kk < Kg; ++kk) {
