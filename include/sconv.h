@@ -368,6 +368,21 @@ int sconv_density(const sconv_desc_t* desc, const float* x_dev, unsigned long lo
 int sconv_tune_reset(void);
 
 /*
+ * The plan table as text, so that a deployment tunes once (sconv_tune costs 0.02-0.3 s a layer) and later
+ * processes load the result instead of measuring again.  Plans are tied to the descriptor (batch size
+ * included), the density class of its zero-ratio field and whether the call brings prepared filters - not to
+ * pointers - and a plan that does not apply where it is loaded (no workspace for a split plan, say) falls back
+ * to the static rules at the call, as a tuned plan always does.  Host only.
+ *   sconv_tune_export: writes one line per remembered plan into out (NUL-terminated).  needed (optional)
+ *            receives the bytes required, terminator included; out NULL with out_size 0 asks for the size
+ *            only.  SCONV_EINVAL when out_size is too small (nothing written).
+ *   sconv_tune_import: adds the plans of such a text to the table, replacing entries with the same key.
+ *            SCONV_EINVAL for a line it cannot read or a plan no kernel knows (nothing is imported then).
+ */
+int sconv_tune_export(char* out, size_t out_size, size_t* needed);
+int sconv_tune_import(const char* text);
+
+/*
  * Writes the plan the forward calls would launch for this descriptor into out (NUL-terminated,
  * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices;
  * geometry "-": the variant has one; "dense" and names ending in d: the form without zero tests), or

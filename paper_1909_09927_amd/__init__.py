@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.sconv_variant_name.restype = ctypes.c_char_p
         L.sconv_tune.argtypes = [P(Desc), ctypes.c_int, vp, vp, vp, vp, ctypes.c_size_t, vp, P(ctypes.c_float)]
         L.sconv_tune_reset.argtypes = []
+        L.sconv_tune_export.argtypes = [ctypes.c_char_p, ctypes.c_size_t, P(ctypes.c_size_t)]
+        L.sconv_tune_import.argtypes = [ctypes.c_char_p]
         L.sconv_plan_name.argtypes = [P(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
         L.sconv_strerror.argtypes = [ctypes.c_int]
         L.sconv_strerror.restype = ctypes.c_char_p
@@ -87,7 +89,8 @@ def lib() -> ctypes.CDLL:
                   "sconv_workspace_size", "sconv_set_workspace", "sconv_clear_workspaces", "sconv_env_refresh",
                   "sconv_forward_ws", "sconv_pool_forward_ws", "sconv_forward_static", "sconv_forward_bias",
                   "sconv_pool_forward_bias", "sconv_pair_forward", "sconv_density", "sconv_filter_prep_size",
-                  "sconv_filter_prep", "sconv_forward_prep", "sconv_pool_forward_prep", "sconv_tune_prep"):
+                  "sconv_filter_prep", "sconv_forward_prep", "sconv_pool_forward_prep", "sconv_tune_prep",
+                  "sconv_tune_export", "sconv_tune_import"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -154,6 +157,23 @@ def sconv_plan_name(desc: Desc, pooled: bool = False) -> str:
 
 def sconv_tune_reset() -> None:
     lib().sconv_tune_reset()
+
+
+def sconv_tune_export() -> str:
+    """The plans sconv_tune has found so far, as text (one line per plan) for sconv_tune_import."""
+    n = ctypes.c_size_t()
+    lib().sconv_tune_export(None, 0, ctypes.byref(n))
+    buf = ctypes.create_string_buffer(n.value)
+    rc = lib().sconv_tune_export(buf, n.value, None)
+    if rc:
+        raise SconvError(rc, "sconv_tune_export")
+    return buf.value.decode()
+
+
+def sconv_tune_import(text: str) -> None:
+    rc = lib().sconv_tune_import(text.encode())
+    if rc:
+        raise SconvError(rc, "sconv_tune_import")
 
 
 def sconv_workspace_size(desc: Desc, pooled: bool = False) -> int:

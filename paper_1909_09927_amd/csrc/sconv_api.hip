@@ -979,6 +979,89 @@ extern "C" int sconv_tune_reset(void)
     return SCONV_OK;
 }
 
+// Text form of the plan table, one line per entry:
+//   "sconv-plan 1 <17 key integers> <variant> <pinned> <geometry or -> <nwv> <ncs> <nss> <ms> <name>"
+static const char* const* geoms_of(Variant v)
+{
+    switch (v) {
+    case V_PW: return pw_geoms();
+    case V_TAP: return tap_geoms();
+    case V_QUAD: return quad_geoms();
+    case V_WIDE: return wide_geoms();
+    case V_GEN: return gen_geoms();
+    default: return nullptr;
+    }
+}
+
+extern "C" int sconv_tune_export(char* out, size_t out_size, size_t* needed)
+{
+    std::lock_guard<std::mutex> lock(g_lock);
+    std::string text;
+    char line[512];
+    for (const auto& kv : g_tuned) {
+        int n = snprintf(line, sizeof(line), "sconv-plan 1");
+        for (int32_t v : kv.first) n += snprintf(line + n, sizeof(line) - n, " %d", v);
+        const Tuned& t = kv.second;
+        snprintf(line + n, sizeof(line) - n, " %d %d %s %d %d %d %.6g %s\n", (int)t.v, t.pinned ? 1 : 0,
+                 t.pin.geom[0] ? t.pin.geom : "-", t.pin.nwv, t.pin.ncs, t.pin.nss, (double)t.ms, t.name);
+        text += line;
+    }
+    if (needed) *needed = text.size() + 1;
+    if (!out || out_size < text.size() + 1) return (out || out_size) ? SCONV_EINVAL : SCONV_OK;
+    memcpy(out, text.c_str(), text.size() + 1);
+    return SCONV_OK;
+}
+
+extern "C" int sconv_tune_import(const char* text)
+{
+    if (!text) return SCONV_EINVAL;
+    std::map<TuneKey, Tuned> parsed;
+    const char* p = text;
+    while (*p) {
+        const char* eol = strchr(p, '\n');
+        const size_t len = eol ? (size_t)(eol - p) : strlen(p);
+        std::string line(p, len);
+        p += len + (eol ? 1 : 0);
+        if (line.find_first_not_of(" \t\r") == std::string::npos) continue;
+        int pos = 0, version = 0;
+        if (sscanf(line.c_str(), " sconv-plan %d%n", &version, &pos) != 1 || version != 1) return SCONV_EINVAL;
+        TuneKey key;
+        for (int32_t& v : key) {
+            int used = 0;
+            if (sscanf(line.c_str() + pos, " %d%n", &v, &used) != 1) return SCONV_EINVAL;
+            pos += used;
+        }
+        Tuned t;
+        memset(&t, 0, sizeof(t));
+        int v = 0, pinned = 0, used = 0;
+        char geom[32], name[64];
+        double ms = 0.0;
+        if (sscanf(line.c_str() + pos, " %d %d %31s %d %d %d %lf %63s%n", &v, &pinned, geom, &t.pin.nwv, &t.pin.ncs,
+                   &t.pin.nss, &ms, name, &used) != 8)
+            return SCONV_EINVAL;
+        if (v < (int)V_ROWS || v > (int)V_GEN || strlen(geom) >= sizeof(t.pin.geom) || strlen(name) >= sizeof(t.name))
+            return SCONV_EINVAL;
+        // only decompositions the launchers know: a geometry of that variant, powers of two within their ranges
+        auto pow2_upto = [](int x, int hi) { return x == 0 || (x > 0 && x <= hi && (x & (x - 1)) == 0); };
+        if (!pow2_upto(t.pin.nwv, 16) || !pow2_upto(t.pin.ncs, 16) || !pow2_upto(t.pin.nss, 16)) return SCONV_EINVAL;
+        t.v = (Variant)v;
+        t.pinned = pinned != 0;
+        if (strcmp(geom, "-") != 0) {
+            bool known = false;
+            if (const char* const* g = geoms_of(t.v))
+                for (; *g; ++g) known |= strcmp(*g, geom) == 0;
+            if (!known) return SCONV_EINVAL;
+            snprintf(t.pin.geom, sizeof(t.pin.geom), "%s", geom);
+        }
+        t.ms = (float)ms;
+        snprintf(t.name, sizeof(t.name), "%s", name);
+        parsed[key] = t;
+    }
+    std::lock_guard<std::mutex> lock(g_lock);
+    for (const auto& kv : parsed) g_tuned[kv.first] = kv.second;
+    return SCONV_OK;
+}
+
 extern "C" int sconv_plan_name(const sconv_desc_t* desc, int pooled, char* out, int out_size)
 {
     if (!out || out_size <= 0) return SCONV_EINVAL;

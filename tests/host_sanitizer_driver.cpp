@@ -136,6 +136,30 @@ int main()
     }
     EXPECT(sconv_plan_name(&g, 1, nullptr, 10) == SCONV_EINVAL && sconv_plan_name(&g, 1, name, 0) == SCONV_EINVAL);
 
+    // the plan table as text
+    {
+        EXPECT(sconv_tune_reset() == SCONV_OK);
+        const char* line = "sconv-plan 1 8 256 56 56 256 3 3 1 1 1 0 0 0 1 0 0 0 2 1 q32t7d 8 4 0 0.24 quad3x3/q32t7d/8x4\n";
+        EXPECT(sconv_tune_import(line) == SCONV_OK);
+        size_t need = 0;
+        EXPECT(sconv_tune_export(nullptr, 0, &need) == SCONV_OK && need == strlen(line) + 1);
+        char buf[256];
+        EXPECT(sconv_tune_export(buf, sizeof(buf), nullptr) == SCONV_OK && strcmp(buf, line) == 0);
+        EXPECT(sconv_tune_export(buf, 5, nullptr) == SCONV_EINVAL);
+        sconv_desc_t q = desc(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, 0, 0, 0, SCONV_RELU);
+        EXPECT(sconv_plan_name(&q, 0, name, sizeof(name)) == SCONV_OK && strcmp(name, "quad3x3/q32t7d/8x4") == 0);
+        const char* junk[] = {"", "\n\n", "sconv-plan", "sconv-plan 1", "sconv-plan 1 1 2 3", "sconv-plan 7 x",
+                              "sconv-plan 1 8 256 56 56 256 3 3 1 1 1 0 0 0 1 0 0 0 2 1 nosuchgeometrynamethatistoolongtofit 8 4 0 0.2 n",
+                              "sconv-plan 1 8 256 56 56 256 3 3 1 1 1 0 0 0 1 0 0 0 -3 1 - 8 4 0 0.2 n",
+                              "sconv-plan 1 8 256 56 56 256 3 3 1 1 1 0 0 0 1 0 0 0 2 1 - 2147483647 4 0 0.2 n"};
+        for (const char* j : junk) {
+            const int rc = sconv_tune_import(j);
+            EXPECT(rc == SCONV_OK || rc == SCONV_EINVAL);
+        }
+        EXPECT(sconv_tune_import(nullptr) == SCONV_EINVAL);
+        EXPECT(sconv_tune_reset() == SCONV_OK);
+    }
+
     // process-state calls that need no device
     EXPECT(sconv_env_refresh() == SCONV_OK);
     EXPECT(sconv_tune_reset() == SCONV_OK);

@@ -1227,6 +1227,37 @@ def test_random_layers_with_prepared_filters_through_the_static_rules(device, mo
         assert (err <= 1e-4 * scale).all(), f"{what}: {int((err > 1e-4 * scale).sum())} outputs beyond the bar"
 
 
+def test_exported_plans_are_replayed_after_import(device, monkeypatch):
+    """Tune, export the table, forget it, import it: the same plans are launched without measuring again, and
+    their results meet the oracle."""
+    monkeypatch.delenv("SCONV_VARIANT", raising=False)
+    sconv.sconv_tune_reset()
+    try:
+        cases = []
+        for i, shp in enumerate([(4, 128, 14, 14, 128, 3, 3, 1, 1, 1, None), (2, 64, 28, 28, 64, 3, 3, 1, 1, 1, (2, 2, 2)),
+                                 (8, 256, 14, 14, 64, 1, 1, 1, 0, 1, None)]):
+            layer, x, w = _mk(360 + i, shp)
+            xd, wd = to_dev(x), to_dev(w)
+            _, plan = sconv.sconv_tune(xd, wd, shp[7], shp[8], shp[9], shp[10], relu=True)
+            cases.append((layer, x, w, shp, plan))
+        text = sconv.sconv_tune_export()
+        assert len(text.splitlines()) == len(cases)
+        sconv.sconv_tune_reset()
+        for layer, x, w, shp, plan in cases:
+            d = sconv.make_desc(*shp[:10], shp[10], True)
+            assert _untuned(sconv.sconv_plan_name(d, shp[10] is not None))
+        sconv.sconv_tune_import(text)
+        for layer, x, w, shp, plan in cases:
+            d = sconv.make_desc(*shp[:10], shp[10], True)
+            assert sconv.sconv_plan_name(d, shp[10] is not None) == plan
+            if layer.pool:
+                check_pool_forward(layer, x, w)
+            else:
+                check_forward(layer, x, w, relu=True)
+    finally:
+        sconv.sconv_tune_reset()
+
+
 def test_prepared_calls_keep_no_state_two_streams_and_a_graph(device, monkeypatch):
     """The ..._prep calls take everything as arguments: two streams, each with its own workspace and its own layer,
     run interleaved without touching each other; and such a call can be captured and replayed (no memset, no

@@ -322,3 +322,48 @@ def test_filter_prep_size_and_argument_checks():
         assert f(ctypes.byref(dd), p, p, p, need - 256, None, p, None, 0, None) == sconv.SCONV_EINVAL
         assert f(ctypes.byref(dd), p, p, p, need, None, p, p, 0, None) == sconv.SCONV_EINVAL   # half-given workspace
         assert f(ctypes.byref(dd), None, p, p, need, None, p, None, 0, None) == sconv.SCONV_EINVAL
+
+
+def test_tuned_plans_travel_as_text():
+    """sconv_tune_export / sconv_tune_import: a plan line names the descriptor, the density class and whether
+    filters come prepared; imported, later calls with that descriptor take it; malformed text imports nothing."""
+    sconv.sconv_tune_reset()
+    try:
+        assert sconv.sconv_tune_export() == ""
+        d = sconv.make_desc(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, None, True)
+        key = "8 256 56 56 256 3 3 1 1 1 0 0 0 1 0 0 0"
+        line = f"sconv-plan 1 {key} 2 1 q32t7d 8 4 0 0.24 quad3x3/q32t7d/8x4\n"
+        sconv.sconv_tune_import(line)
+        assert sconv.sconv_plan_name(d) == "quad3x3/q32t7d/8x4" and sconv.sconv_variant_name(d) == "quad3x3"
+        # another batch size, another density class, prepared filters: other keys, still untuned
+        assert "model" in sconv.sconv_plan_name(sconv.make_desc(4, 256, 56, 56, 256, 3, 3, 1, 1, 1, None, True))
+        assert "model" in sconv.sconv_plan_name(sconv.make_desc(8, 256, 56, 56, 256, 3, 3, 1, 1, 1, None, True, prepared=True))
+        text = sconv.sconv_tune_export()
+        assert text == line
+        # a second entry (pooled layer, prepared filters, dense class 3) and a round trip through reset
+        line2 = "sconv-plan 1 8 512 14 14 512 3 3 1 1 1 2 2 2 1 1 3 1 1 1 p2x14k1t 16 16 0 0.049 tap3x3/p2x14k1t/16x16\n"
+        sconv.sconv_tune_import(line2)
+        both = sconv.sconv_tune_export()
+        assert sorted(both.splitlines()) == sorted((line + line2).splitlines())
+        sconv.sconv_tune_reset()
+        assert sconv.sconv_tune_export() == ""
+        sconv.sconv_tune_import(both)
+        dp = sconv.make_desc(8, 512, 14, 14, 512, 3, 3, 1, 1, 1, (2, 2, 2), True, zero_ratio=0.85, prepared=True)
+        assert sconv.sconv_plan_name(dp, True) == "tap3x3/p2x14k1t/16x16"
+        # nothing of a text with a bad line is taken: unknown geometry, bad counts, wrong version, short line
+        sconv.sconv_tune_reset()
+        for bad in (line.replace("q32t7d", "q99"), line.replace(" 8 4 0 0.24", " 8 3 0 0.24"),
+                    line.replace("sconv-plan 1", "sconv-plan 2"), line2 + "sconv-plan 1 1 2 3\n",
+                    line.replace(" 2 1 q32t7d", " 9 1 q32t7d"), "hello\n"):
+            with pytest.raises(sconv.SconvError):
+                sconv.sconv_tune_import(bad)
+            assert sconv.sconv_tune_export() == ""
+        L = sconv.lib()
+        n = ctypes.c_size_t()
+        sconv.sconv_tune_import(line)
+        assert L.sconv_tune_export(None, 0, ctypes.byref(n)) == 0 and n.value == len(line) + 1
+        small = ctypes.create_string_buffer(8)
+        assert L.sconv_tune_export(small, 8, None) == sconv.SCONV_EINVAL
+        assert L.sconv_tune_import(None) == sconv.SCONV_EINVAL
+    finally:
+        sconv.sconv_tune_reset()
