@@ -11,9 +11,9 @@
  * is cached launch information (occupancy answers) for the device the first calls ran on - so one
  * process should drive one device -, the plans sconv_tune found, the workspaces lent with
  * sconv_set_workspace and the SCONV_* environment as first read.  Calls that change process state:
- * sconv_tune / sconv_tune_reset (plan table), sconv_set_workspace / sconv_clear_workspaces (lent
- * workspaces), sconv_env_refresh; every other call only reads it.  A caller that wants none of it
- * uses the ..._ws forms and never tunes.
+ * sconv_tune / sconv_tune_prep / sconv_tune_import / sconv_tune_reset (plan table), sconv_set_workspace /
+ * sconv_clear_workspaces (lent workspaces), sconv_env_refresh; every other call only reads it.  A caller
+ * that wants none of it uses the ..._ws or ..._prep forms and never tunes.
  *
  * Notation follows Table 1 of the paper: feature map i_h x i_w (H x W here), kernel k_h x k_w
  * (R x S), pooling window p_h x p_w, convolution stride c_s, pooling stride p_s.  Several input
