@@ -848,6 +848,10 @@ MICRO_MODES = [
     (9, "ff1_setpc", "s_ff1 + s_bitset0 + s_lshl + s_getpc + s_add + s_addc + s_setpc", 1),
     (10, "mfma_4x4x1", "8 independent v_mfma_f32_4x4x1 (256 multiply-adds each; 8 clocks at the published rate)", 8),
     (11, "mfma_16x16x1", "4 independent v_mfma_f32_16x16x1 (1024 multiply-adds each; 32 clocks at the published rate)", 4),
+    (12, "vskip5_on", "s_setvskip turning the vector-skip mode on + 5 v_fmac (not issued)", 1),
+    (13, "vskip5_off", "s_setvskip leaving the mode off + 5 v_fmac (they run)", 1),
+    (14, "vskip_pos_on", "s_setvskip on + v_readlane + s_nop 1 + 5 v_fmac: a zero position without a branch", 1),
+    (15, "vskip_pos_off", "the same with the mode off: a nonzero position", 1),
 ]
 
 

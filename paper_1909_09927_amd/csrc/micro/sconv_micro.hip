@@ -23,7 +23,11 @@ enum {
     MICRO_FF1_SETPC = 9,      // s_ff1 + s_bitset0 + s_lshl + s_add + s_addc + s_setpc (threaded dispatch)
     MICRO_MFMA_4X4X1 = 10,    // 8 independent v_mfma_f32_4x4x1 (16 blocks, 256 multiply-adds each) per repeat
     MICRO_MFMA_16X16X1 = 11,  // 4 independent v_mfma_f32_16x16x1 (4 blocks, 1024 multiply-adds each) per repeat
-    MICRO_MODES = 12
+    MICRO_VSKIP5_ON = 12,     // s_setvskip (skip mode on) + 5 v_fmac, which are then not issued
+    MICRO_VSKIP5_OFF = 13,    // s_setvskip (skip mode off) + 5 v_fmac, which run
+    MICRO_VSKIP_POS_ON = 14,  // s_setvskip on + v_readlane + 5 v_fmac: a zero position of the vector kernel, no branch
+    MICRO_VSKIP_POS_OFF = 15, // the same with skip mode off: a nonzero position
+    MICRO_MODES = 16
 };
 }
 
@@ -145,6 +149,27 @@ __global__ __launch_bounds__(256) void micro_kernel(int iters, unsigned m, float
                          "3:\n"
                          : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4)
                          : "s"(m), "v"(w) : "scc");
+        } else if constexpr (MODE == MICRO_VSKIP5_ON || MODE == MICRO_VSKIP5_OFF) {
+            // s_setvskip S0, S1: the wavefront's vector-skip mode := bit S1 of S0.  While it is set, vector ALU,
+            // vector memory and LDS instructions are not issued.  Cleared again before the block ends.
+            asm volatile(".rept 64\n"
+                         "s_setvskip %5, 0\n"
+                         "v_fmac_f32 %0, %5, %6\n v_fmac_f32 %1, %5, %6\n v_fmac_f32 %2, %5, %6\n v_fmac_f32 %3, %5, %6\n"
+                         "v_fmac_f32 %4, %5, %6\n"
+                         ".endr\n"
+                         "s_setvskip 0, 0\n"
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4)
+                         : "s"(m), "v"(w));
+        } else if constexpr (MODE == MICRO_VSKIP_POS_ON || MODE == MICRO_VSKIP_POS_OFF) {
+            asm volatile(".rept 64\n"
+                         "s_setvskip %5, 0\n"
+                         "v_readlane_b32 s40, %6, 7\n s_nop 1\n"
+                         "v_fmac_f32 %0, s40, %6\n v_fmac_f32 %1, s40, %6\n v_fmac_f32 %2, s40, %6\n v_fmac_f32 %3, s40, %6\n"
+                         "v_fmac_f32 %4, s40, %6\n"
+                         ".endr\n"
+                         "s_setvskip 0, 0\n"
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4)
+                         : "s"(m), "v"(w) : "s40");
         } else if constexpr (MODE == MICRO_FF1_SETPC) {
             // the dispatch sequence of a threaded position loop; the target is the next instruction
             asm volatile("s_mov_b64 s[42:43], -1\n"
@@ -185,6 +210,10 @@ extern "C" int sconv_micro_launch(int mode, int iters, int blocks, float* out_de
     case MICRO_READLANE_FMA5: return launch<MICRO_READLANE_FMA5>(iters, 0, blocks, out_dev, s);
     case MICRO_FAR_TAKEN: return launch<MICRO_FAR_TAKEN>(iters, 1, blocks, out_dev, s);
     case MICRO_FF1_SETPC: return launch<MICRO_FF1_SETPC>(iters, 0, blocks, out_dev, s);
+    case MICRO_VSKIP5_ON: return launch<MICRO_VSKIP5_ON>(iters, 0x3f800001u, blocks, out_dev, s);
+    case MICRO_VSKIP5_OFF: return launch<MICRO_VSKIP5_OFF>(iters, 0x3f800000u, blocks, out_dev, s);
+    case MICRO_VSKIP_POS_ON: return launch<MICRO_VSKIP_POS_ON>(iters, 1, blocks, out_dev, s);
+    case MICRO_VSKIP_POS_OFF: return launch<MICRO_VSKIP_POS_OFF>(iters, 0, blocks, out_dev, s);
     case MICRO_MFMA_4X4X1:
         hipLaunchKernelGGL(micro_mfma_kernel<MICRO_MFMA_4X4X1>, dim3(blocks), dim3(256), 0, s, iters, out_dev);
         return hipGetLastError() == hipSuccess ? 0 : -3;
