@@ -387,7 +387,8 @@ int sconv_tune_import(const char* text);
  * truncated to out_size): "variant/geometry/WxS" (wavefronts per workgroup x channel slices;
  * geometry "-": the variant has one; "dense" and names ending in d: the form without zero tests), or
  * "variant/geometry/WxSxP" when P workgroups split a tile's channels, for a tuned descriptor
- * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice);
+ * ("variant/model/kept" when tuning found nothing 3 % faster than the static choice, "tap3x3/model:geometry/WxS[xP]/kept"
+ * for the vector kernel, whose static plan has a name);
  * "variant/model" for a descriptor that was not tuned ("tap3x3/model:geometry/WxS[xP]": the vector
  * kernel's cost model is asked what it would launch on the default stream, so a split shows).  Nothing is enqueued; asks the HIP runtime
  * for the current device, as sconv_variant_name does.

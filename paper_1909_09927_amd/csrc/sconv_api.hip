@@ -593,8 +593,15 @@ static int tune(const Problem& p, bool pooled, const float* x, const float* w, f
         best.ms = t;
         best.pin = c.pin;
         best.pinned = c.pinned;
-        if (have_static && i == 0)
-            snprintf(best.name, sizeof(best.name), "%s/model/kept", variant_name(c.v));
+        if (have_static && i == 0) {
+            // (the vector kernel's static plan by name, so that records show what was kept)
+            char detail[32];
+            split_scratch_select(s);
+            if (c.v == V_TAP && !c.pinned && describe_tap(p, pooled, s, detail, sizeof(detail)))
+                snprintf(best.name, sizeof(best.name), "%s/model:%s/kept", variant_name(c.v), detail);
+            else
+                snprintf(best.name, sizeof(best.name), "%s/model/kept", variant_name(c.v));
+        }
         else if (c.pinned && c.pin.nss > 1)
             snprintf(best.name, sizeof(best.name), "%s/%s/%dx%dx%d", variant_name(c.v), c.pin.geom, c.pin.nwv,
                      c.pin.ncs, c.pin.nss);
