@@ -46,7 +46,7 @@ MFMA_VARIANTS = ("quad3x3", "quad1x1", "wide3x3", "gen")
 # by the copy calibration), keyed by (plan name, layer, batch): a figure from profiles/, not something this
 # run measures - the line names its source, and prints null when the plan that ran is not in the table.
 MEASURED_TRAFFIC = {
-    ("quad3x3/q32t7d/8x4", "vgg-256x56", 8): (54.8e6 + 25.7e6, "profiles/quad3x3_vgg-256x56_n8.txt"),
+    ("quad3x3/q32t7d/8x4", "vgg-256x56", 8): (54.8e6 + 25.9e6, "profiles/quad3x3_vgg-256x56_n8.txt"),
 }
 # elements per zero test of the kernels that skip whole groups (1: every zero element is skipped)
 SKIP_GRANULE = {"rows": 1, "tap3x3": 1, "quad3x3": 6, "quad1x1": 32, "wide3x3": 16, "gen": 16}
